@@ -1,0 +1,113 @@
+// Internal host-side helpers shared by the library's translation units.
+#pragma once
+#include <cstdint>
+#include <cstddef>
+#include "tensor_tiling.h"
+
+namespace tt {
+
+constexpr int kMaxShards = 1 << TT_MAX_K;
+
+// Letter used internally for a cut whose shards hold different partial sums (output of form F3).
+constexpr uint8_t kRed = 3;
+
+inline bool valid_k(int k) { return k >= 0 && k <= TT_MAX_K; }
+
+inline bool valid_tiling(const tt_tiling &t, int k)
+{
+    for (int j = 0; j < k; ++j)
+        if (t.cut[j] > TT_REP) return false;
+    return true;
+}
+
+// A k-cut tiling seen as a regular grid (flattening theorem, Sec. 4.4).
+// Shard-id bit for cut j is bit (k-1-j).  maskR / maskC / maskX select the id bits of the R cuts, the C cuts and
+// the remaining cuts (replicas, or partial-sum numbers for kRed).
+struct Grid {
+    int k = 0, kR = 0, kC = 0, kX = 0;
+    uint32_t maskR = 0, maskC = 0, maskX = 0;
+    int64_t rows = 0, cols = 0;   // full tensor
+    int64_t srows = 0, scols = 0; // shard extent
+};
+
+// letters[j] in {TT_R, TT_C, anything else = extra}.  Returns false if the cut is uneven.
+inline bool make_grid(const uint8_t *letters, int k, int64_t rows, int64_t cols, Grid *g)
+{
+    Grid out;
+    out.k = k;
+    out.rows = rows;
+    out.cols = cols;
+    for (int j = 0; j < k; ++j) {
+        uint32_t b = 1u << (k - 1 - j);
+        if (letters[j] == TT_R) { out.kR++; out.maskR |= b; }
+        else if (letters[j] == TT_C) { out.kC++; out.maskC |= b; }
+        else { out.kX++; out.maskX |= b; }
+    }
+    if (rows % (int64_t(1) << out.kR) || cols % (int64_t(1) << out.kC)) return false;
+    out.srows = rows >> out.kR;
+    out.scols = cols >> out.kC;
+    *g = out;
+    return true;
+}
+
+// bits of v scattered to the set positions of mask, most significant first (software pdep on <= 6 bits)
+inline uint32_t deposit(uint32_t v, uint32_t mask, int k)
+{
+    uint32_t out = 0;
+    int n = __builtin_popcount(mask);
+    for (int b = k - 1; b >= 0; --b)
+        if (mask & (1u << b)) { --n; if (v & (1u << n)) out |= 1u << b; }
+    return out;
+}
+inline uint32_t extract(uint32_t s, uint32_t mask, int k)
+{
+    uint32_t out = 0;
+    for (int b = k - 1; b >= 0; --b)
+        if (mask & (1u << b)) out = (out << 1) | ((s >> b) & 1u);
+    return out;
+}
+
+inline tt_tiling transpose_tiling(tt_tiling t, int k)
+{
+    for (int j = 0; j < k; ++j) t.cut[j] = t.cut[j] == TT_R ? TT_C : (t.cut[j] == TT_C ? TT_R : TT_REP);
+    return t;
+}
+
+// aligned tilings of a form sequence (Sec. 4.2.1)
+inline void aligned_tilings(const uint8_t *forms, int k, tt_tiling *aX, tt_tiling *aY, uint8_t *aZ /* k letters, kRed for F3 */)
+{
+    static const uint8_t ax[3] = {TT_R, TT_REP, TT_C}, ay[3] = {TT_REP, TT_C, TT_R}, az[3] = {TT_R, TT_C, kRed};
+    for (int j = 0; j < k; ++j) {
+        if (aX) aX->cut[j] = ax[forms[j]];
+        if (aY) aY->cut[j] = ay[forms[j]];
+        if (aZ) aZ[j] = az[forms[j]];
+    }
+}
+
+inline bool same_tiling(const tt_tiling &a, const tt_tiling &b, int k)
+{
+    for (int j = 0; j < k; ++j) if (a.cut[j] != b.cut[j]) return false;
+    return true;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- cost model (planner.cpp) used by the execute calls to pick default forms
+// Matmul Z = X Y with tensors given as (rows, cols, mult) and tilings already expressed on the operands as multiplied.
+struct CostTensor { int64_t rows, cols, mult; };
+uint64_t matmul_cost(const CostTensor &X, const CostTensor &Y, const CostTensor &Z, int64_t M, int64_t K, int64_t N,
+                     const uint8_t *tx, const uint8_t *ty, const uint8_t *tz, int k, uint8_t *forms_out,
+                     uint64_t *level_out);
+
+// ---- internal launchers (device pointers arrays are host arrays)
+tt_status launch_convert(void *const *dst, const uint8_t *B, const void *const *src, const uint8_t *A,
+                         const void *const *mask, const uint8_t *Am, int k, int64_t rows, int64_t cols,
+                         int elem_bytes, int gate_dtype, bool dst_unique /* replicas of B alias one buffer */,
+                         void *stream);
+tt_status launch_reduce(void *const *dst, const uint8_t *B, int out_dtype, const float *const *partials,
+                        const uint8_t *zletters /* R, C or kRed per cut */, int k, int64_t rows, int64_t cols, int act,
+                        void *stream);
+tt_status launch_gemm(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
+                      int64_t K, int trans_a, int trans_b, int in_dtype, int out_dtype, int act, void *stream);
+
+} // namespace tt

@@ -1,0 +1,195 @@
+"""Parity of the FC execute calls with the untiled fp64 oracle, per operation (each op is fed the stored operands,
+so tolerances do not compound along the chain)."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import paper_1805_04170_amd as tt
+from oracle import layers as ly
+from oracle import tiling as tl
+from oracle import execute as ex
+from synthetic import CONFIGS, bf16_bits_to_f64, normal_f32, to_bf16_bits
+
+from gpu_util import DEV, alloc_shards, dev_to_np, np_to_dev, shards_to_dev, shards_to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def tdtype(dt):
+    return torch.bfloat16 if dt == "bf16" else torch.float32
+
+
+def to_store(v, dt):
+    return to_bf16_bits(v) if dt == "bf16" else v.astype(np.float32)
+
+
+def f64(a, dt):
+    return bf16_bits_to_f64(a) if dt == "bf16" else a.astype(np.float64)
+
+
+def workspace(nbytes):
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=DEV)
+
+
+def assert_close(got_shards, t, rows, cols, want, mag, dt, what):
+    got = tl.untile(shards_to_np(got_shards), t, rows, cols)      # also checks replicas are identical
+    gf = f64(got, dt)
+    tol = (1e-2 if dt == "bf16" else 1e-5) * mag
+    if dt == "bf16":
+        tol = tol + 2.0 ** -8 * np.abs(want)                       # the result is stored in bf16
+    err = np.abs(gf - want)
+    assert np.all(np.isfinite(gf)), what
+    assert np.all(err <= tol + 1e-30), (what, float(err.max()), float((err / (tol + 1e-30)).max()))
+
+
+def run_layer(b, ni, no, k, dt, relu, tX, tW, tY, tdY, tdX, f_fwd, f_dg, f_wg, seed, with_dx=True):
+    lay = tt.layer("fc", "relu" if relu else "none", ni, no)
+    X = to_store(normal_f32(seed, 0, (b, ni), 1.0), dt)
+    W = to_store(normal_f32(seed, 1, (ni, no), 0.05), dt)
+    dY = to_store(normal_f32(seed, 2, (b, no), 1.0), dt)
+    bf = dt == "bf16"
+    Xs, Ws, dYs = shards_to_dev(X, tX, bf), shards_to_dev(W, tW, bf), shards_to_dev(dY, tdY, bf)
+    Ys = alloc_shards(b, no, tY, tdtype(dt), fill=float("nan"))
+    nb = tt.tt_fc_workspace_bytes(lay, b, k, dt, tt.TT_OP_FWD, tX, tW, tY, forms_a=f_fwd)
+    ws = workspace(nb)
+    tt.tt_fc_forward(lay, b, k, dt, tX, tW, tY, f_fwd, Xs, Ws, Ys, ws)
+    torch.cuda.synchronize()
+    Xf, Wf = f64(X, dt), f64(W, dt)
+    want_Y = ly.fc_forward(Xf, Wf, relu)
+    assert_close(Ys, tY, b, no, want_Y, ly.abs_product(Xf, Wf), dt, ("fwd", tX, tW, tY, f_fwd))
+    # backward consumes the stored Y the GPU produced (so the gate decision is taken on identical values)
+    Y_stored = f64(tl.untile(shards_to_np(Ys), tY, b, no), dt)
+    dXs = alloc_shards(b, ni, tdX, tdtype(dt), fill=float("nan")) if with_dx else None
+    dWs = alloc_shards(ni, no, tW, tdtype(dt), fill=float("nan"))
+    nb = tt.tt_fc_workspace_bytes(lay, b, k, dt, tt.TT_OP_DGRAD, tX, tW, tY, tdY, tdX, f_dg, f_wg, with_dx)
+    ws = workspace(nb)
+    tt.tt_fc_backward(lay, b, k, dt, tX, tW, tY, tdY, tdX, f_dg, f_wg, Xs, Ws, Ys, dYs, dXs, dWs, ws)
+    torch.cuda.synchronize()
+    dYf = f64(dY, dt)
+    want_dX, want_dW = ly.fc_backward(dYf, Xf, Wf, Y_stored, relu)
+    G = dYf * (Y_stored > 0) if relu else dYf
+    if with_dx:
+        assert_close(dXs, tdX, b, ni, want_dX, ly.abs_product(G, Wf.T), dt, ("dgrad", tdY, tW, tdX, f_dg))
+    assert_close(dWs, tW, ni, no, want_dW, ly.abs_product(Xf.T, G), dt, ("wgrad", tX, tdY, tW, f_wg))
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_named_tilings_one_and_two_cuts(dt, golden_loader):
+    g = golden_loader("paper_tilings.txt")
+    # T_data, T_model (one cut) and T_hybrid (two cuts) of Sec. 4.1: weight / activation / gradient tilings
+    for name in ["T_data", "T_model", "T_hybrid"]:
+        tW, tA, tG = g[name]
+        k = len(tW)
+        run_layer(32, 64, 48, k, dt, True, tA, tW, tA, tG, tG, None, None, None, 50 + k)
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_every_form_sequence_two_cuts(relu):
+    # fixed stored tilings, every aligned form sequence for each of the three products
+    seqs = ["".join(p) for p in itertools.product("123", repeat=2)]
+    for f in seqs:
+        run_layer(16, 32, 24, 2, "bf16", relu, "RC", "Cr", "rR", "CR", "RR", f, f, f, 60)
+
+
+def test_random_stored_tilings_default_forms():
+    rng = np.random.default_rng(5)
+    ts = tl.all_tilings(2)
+    for i in range(25):
+        tX, tW, tY, tdY, tdX = (ts[j] for j in rng.integers(0, 9, 5))
+        run_layer(16, 40, 24, 2, "bf16" if i % 2 else "f32", bool(i % 3), tX, tW, tY, tdY, tdX, None, None, None, 70 + i)
+
+
+def test_three_cuts_ragged_width_and_skip_dx():
+    run_layer(64, 96, 1000, 3, "bf16", False, "CCC", "RRR", "RRR", "rrr", "CCC", "333", "222", "111", 80)
+    run_layer(64, 96, 1000, 3, "bf16", True, "RRR", "rrr", "RRC", "RCR", "RRR", None, None, None, 81, with_dx=False)
+    run_layer(64, 1000, 40, 3, "bf16", True, "rCr", "CRC", "CrC", "CrC", "RCR", "232", "323", "212", 82)
+
+
+def test_uneven_and_bad_workspace_are_refused():
+    lay = tt.layer("fc", "none", 10, 6)
+    x = [torch.zeros(8, dtype=torch.bfloat16, device=DEV)] * 4
+    with pytest.raises(tt.TilingError) as e:
+        tt.tt_fc_forward(lay, 8, 2, "bf16", "RR", "rr", "CC", "22", x, x, x)
+    assert e.value.status == 2
+    lay = tt.layer("fc", "none", 16, 16)
+    with pytest.raises(tt.TilingError) as e:                     # K-split needs partial-sum workspace
+        tt.tt_fc_forward(lay, 8, 2, "bf16", "CC", "RR", "RR", "33", x, x, x)
+    assert e.value.status == 6
+
+
+def chain_tensors(cfg):
+    return cfg.x0(), [cfg.weight(l) for l in range(1, cfg.n_layers + 1)], cfg.grad_out()
+
+
+def run_chain(cfg, plan, check_rows=None):
+    """Forward and backward of a whole chain under a plan; each op is compared with the oracle applied to the
+    operands the GPU actually stored.  check_rows: rows of the activations to check (None = all)."""
+    dt, k, b, L = cfg.dtype, cfg.k, cfg.batch, cfg.n_layers
+    bf = dt == "bf16"
+    x0, Ws, gL = chain_tensors(cfg)
+    tx, tg, tw = plan.x(), plan.g(), plan.w()
+    layers = [tt.layer("fc", "relu" if cfg.act(l) else "none", cfg.widths[l - 1], cfg.widths[l]) for l in range(1, L + 1)]
+    xs = [shards_to_dev(x0, tx[0], bf)]
+    wsh = [shards_to_dev(Ws[l], tw[l], bf) for l in range(L)]
+    for l in range(1, L + 1):
+        f = plan.forms(l, tt.TT_OP_FWD)
+        ys = alloc_shards(b, cfg.widths[l], tx[l], tdtype(dt), fill=float("nan"))
+        nb = tt.tt_fc_workspace_bytes(layers[l - 1], b, k, dt, tt.TT_OP_FWD, tx[l - 1], tw[l - 1], tx[l], forms_a=f)
+        tt.tt_fc_forward(layers[l - 1], b, k, dt, tx[l - 1], tw[l - 1], tx[l], f, xs[l - 1], wsh[l - 1], ys, workspace(nb))
+        xs.append(ys)
+    torch.cuda.synchronize()
+    rows = slice(None) if check_rows is None else check_rows
+    full_x = [f64(tl.untile(shards_to_np(xs[l]), tx[l], b, cfg.widths[l]), dt) for l in range(L + 1)]
+    Wf = [f64(w, dt) for w in Ws]
+    for l in range(1, L + 1):
+        want = ly.fc_forward(full_x[l - 1][rows], Wf[l - 1], bool(cfg.act(l)))
+        mag = ly.abs_product(full_x[l - 1][rows], Wf[l - 1])
+        tol = (1e-2 if bf else 1e-5) * mag + (2.0 ** -8 * np.abs(want) if bf else 0)
+        assert np.all(np.abs(full_x[l][rows] - want) <= tol + 1e-30), ("fwd", l)
+    gs = [None] * (L + 1)
+    gs[L] = shards_to_dev(gL, tg[L], bf)
+    dws = [None] * L
+    for l in range(L, 0, -1):
+        fd, fw = plan.forms(l, tt.TT_OP_DGRAD), plan.forms(l, tt.TT_OP_WGRAD)
+        gs[l - 1] = alloc_shards(b, cfg.widths[l - 1], tg[l - 1], tdtype(dt), fill=float("nan"))
+        dws[l - 1] = alloc_shards(cfg.widths[l - 1], cfg.widths[l], tw[l - 1], tdtype(dt), fill=float("nan"))
+        nb = tt.tt_fc_workspace_bytes(layers[l - 1], b, k, dt, tt.TT_OP_DGRAD, tx[l - 1], tw[l - 1], tx[l], tg[l], tg[l - 1], fd, fw)
+        tt.tt_fc_backward(layers[l - 1], b, k, dt, tx[l - 1], tw[l - 1], tx[l], tg[l], tg[l - 1], fd, fw, xs[l - 1], wsh[l - 1],
+                          xs[l], gs[l], gs[l - 1], dws[l - 1], workspace(nb))
+    torch.cuda.synchronize()
+    full_g = [f64(tl.untile(shards_to_np(gs[l]), tg[l], b, cfg.widths[l]), dt) for l in range(L + 1)]
+    for l in range(L, 0, -1):
+        relu = bool(cfg.act(l))
+        G = full_g[l] * (full_x[l] > 0) if relu else full_g[l]
+        want_dx = G[rows] @ Wf[l - 1].T
+        mag = np.abs(G[rows]) @ np.abs(Wf[l - 1].T)
+        tol = (1e-2 if bf else 1e-5) * mag + (2.0 ** -8 * np.abs(want_dx) if bf else 0)
+        assert np.all(np.abs(full_g[l - 1][rows] - want_dx) <= tol + 1e-30), ("dgrad", l)
+        # weight gradient: sampled rows of dW (input neurons), all columns
+        ni = cfg.widths[l - 1]
+        pick = np.arange(ni) if check_rows is None else np.unique(np.linspace(0, ni - 1, 64).astype(int))
+        dW = f64(tl.untile(shards_to_np(dws[l - 1]), tw[l - 1], ni, cfg.widths[l]), dt)
+        want_dw = full_x[l - 1][:, pick].T @ G
+        mag = np.abs(full_x[l - 1][:, pick].T) @ np.abs(G)
+        tol = (1e-2 if bf else 1e-5) * mag + (2.0 ** -8 * np.abs(want_dw) if bf else 0)
+        assert np.all(np.abs(dW[pick] - want_dw) <= tol + 1e-30), ("wgrad", l)
+
+
+def plan_for(cfg, mode=tt.TT_PLAN_EXACT, **pins):
+    layers = [tt.layer("fc", "none", cfg.widths[l], cfg.widths[l + 1]) for l in range(cfg.n_layers)]
+    return tt.tt_plan_chain(layers, cfg.batch, cfg.k, mode, **pins)
+
+
+def test_config_tiny_mlp_fp32_planned_and_recursive():
+    cfg = CONFIGS["tiny_mlp"]
+    run_chain(cfg, plan_for(cfg))
+    run_chain(cfg, plan_for(cfg, tt.TT_PLAN_RECURSIVE))
+    run_chain(cfg, plan_for(cfg, pin_x0="RR", pin_g0="RR"))
+
+
+@pytest.mark.parametrize("name", ["alexnet_fc", "vgg16_fc"])
+def test_config_fc_stacks_full_size(name):
+    cfg = CONFIGS[name]
+    run_chain(cfg, plan_for(cfg), check_rows=np.array([0, 1, 31, 32, 100, 255]))

@@ -1,0 +1,102 @@
+"""Parity of the shard-product kernels with the fp64 oracle.
+bf16 inputs / fp32 accumulate: |gpu - oracle| <= 1e-2 * (|A| |B|)_ij  (+ half an ulp of a bf16 store);
+fp32: <= 1e-5 * (|A| |B|)_ij."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1805_04170_amd as tt
+from oracle import layers as ly
+from synthetic import bf16_bits_to_f64, normal_f32, to_bf16_bits
+
+from gpu_util import DEV, dev_to_np, np_to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def check(count, M, N, K, ta, tb, in_dt, out_dt, relu, seed):
+    bf = in_dt == "bf16"
+    As, Bs, Cs, want, mags = [], [], [], [], []
+    for s in range(count):
+        a = normal_f32(seed, 2 * s, (M, K), 1.0)
+        b = normal_f32(seed, 2 * s + 1, (K, N), 0.05)
+        if bf:
+            a, b = to_bf16_bits(a), to_bf16_bits(b)
+        af = bf16_bits_to_f64(a) if bf else a.astype(np.float64)
+        bfl = bf16_bits_to_f64(b) if bf else b.astype(np.float64)
+        z = af @ bfl
+        want.append(np.maximum(z, 0) if relu else z)
+        mags.append(ly.abs_product(af, bfl))
+        As.append(np_to_dev(a.T if ta else a, bf))
+        Bs.append(np_to_dev(b.T if tb else b, bf))
+        Cs.append(torch.full((M, N), float("nan"), dtype=torch.bfloat16 if out_dt == "bf16" else torch.float32, device=DEV))
+    tt.tt_shard_gemm(As, Bs, Cs, M, N, K, ta, tb, in_dt, out_dt, tt.TT_ACT_RELU if relu else tt.TT_ACT_NONE)
+    torch.cuda.synchronize()
+    for s in range(count):
+        got = dev_to_np(Cs[s])
+        gf = bf16_bits_to_f64(got) if out_dt == "bf16" else got.astype(np.float64)
+        tol = (1e-2 if bf else 1e-5) * mags[s]
+        if out_dt == "bf16":
+            tol = tol + 2.0 ** -8 * np.abs(want[s])
+        err = np.abs(gf - want[s])
+        assert np.all(np.isfinite(gf)), (s, "non-finite output")
+        assert np.all(err <= tol + 1e-30), (s, float(err.max()), float((err / (tol + 1e-30)).max()))
+        # the bound is loose for fp32 accumulation; also require a tight typical error so a dropped k-tile cannot hide
+        if bf and out_dt == "f32":
+            assert float(np.max(err / (mags[s] + 1e-30))) < 1e-4
+
+
+LAYOUTS = [(0, 0), (0, 1), (1, 0), (1, 1)]
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+@pytest.mark.parametrize("out_dt", ["bf16", "f32"])
+def test_bf16_mfma_tiles_and_tails(ta, tb, out_dt):
+    # several 128/256 tiles plus ragged tails in M, N and K (all multiples of 8 along contiguous dims)
+    check(3, 264, 200, 328, ta, tb, "bf16", out_dt, False, 31)
+    check(2, 128, 136, 64, ta, tb, "bf16", out_dt, True, 32)
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_bf16_small_and_tall(ta, tb):
+    check(8, 32, 512, 1024, ta, tb, "bf16", "f32", False, 33)      # batch-split shard: few rows
+    check(1, 520, 72, 40, ta, tb, "bf16", "bf16", False, 34)        # three row tiles, one short K tile
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_bf16_unaligned_falls_back(ta, tb):
+    check(2, 37, 125, 50, ta, tb, "bf16", "bf16", True, 35)         # 125-wide rows: no 16-byte vectors
+    check(2, 33, 10, 17, ta, tb, "bf16", "f32", False, 36)
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_fp32(ta, tb):
+    check(4, 32, 10, 256, ta, tb, "f32", "f32", False, 37)
+    check(2, 70, 130, 65, ta, tb, "f32", "f32", True, 38)
+
+
+def test_k_zero_and_empty():
+    C = [torch.full((8, 8), 5.0, dtype=torch.float32, device=DEV)]
+    A = [torch.zeros((8, 1), dtype=torch.bfloat16, device=DEV)]
+    tt.tt_shard_gemm(A, A, C, 8, 8, 0, 0, 0, "bf16", "f32")
+    torch.cuda.synchronize()
+    assert torch.all(C[0] == 0)
+    tt.tt_shard_gemm(A, A, C, 0, 8, 4, 0, 0, "bf16", "f32")          # nothing to do
+
+
+def test_vgg_shard_shape_sampled():
+    # the K-split shard product of the VGG-16 first classifier layer: 256 x 3136 x 4096, fp32 partial output;
+    # sampled rows checked against the oracle
+    M, K, N = 256, 3136, 4096
+    a = to_bf16_bits(normal_f32(41, 0, (M, K), 1.0)); b = to_bf16_bits(normal_f32(41, 1, (K, N), 0.005))
+    A = [np_to_dev(a, True)]; B = [np_to_dev(b, True)]
+    C = [torch.empty((M, N), dtype=torch.float32, device=DEV)]
+    tt.tt_shard_gemm(A, B, C, M, N, K, 0, 0, "bf16", "f32")
+    torch.cuda.synchronize()
+    got = dev_to_np(C[0]).astype(np.float64)
+    rows = [0, 1, 127, 128, 200, 255]
+    af, bfl = bf16_bits_to_f64(a[rows]), bf16_bits_to_f64(b)
+    want = af @ bfl
+    mag = np.abs(af) @ np.abs(bfl)
+    assert np.all(np.abs(got[rows] - want) <= 1e-2 * mag)
+    assert float(np.max(np.abs(got[rows] - want) / mag)) < 1e-4

@@ -1,0 +1,193 @@
+"""CPU-side checks of the product library: exported symbols, host planner against the oracle's brute force and
+Algorithm 1, geometry, and host-side argument errors.  No kernel is launched."""
+import ctypes
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1805_04170_amd as tt
+from oracle import cost as oc
+from oracle import tiling as tl
+from synthetic import CONFIGS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def fc_layers(widths, relu=False):
+    L = len(widths) - 1
+    return [tt.layer("fc", "relu" if (relu and l < L - 1) else "none", widths[l], widths[l + 1]) for l in range(L)]
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "tensor_tiling.h")).read()
+    declared = set(re.findall(r"\b(tt_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(tt.binding.EXPORTS)
+    L = ctypes.CDLL(tt.binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_no_oracle_in_product():
+    # the product never imports or calls the oracle
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "paper_1805_04170_amd")):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), (dirpath, f)
+
+
+def test_shard_shape_matches_oracle_and_rejects_uneven():
+    for t in tl.all_tilings(3):
+        assert tt.tt_shard_shape(64, 1000, t) == tl.shard_shape(64, 1000, t)
+    with pytest.raises(tt.TilingError) as e:
+        tt.tt_shard_shape(10, 6, "RR")
+    assert e.value.status == 2
+    with pytest.raises(tt.TilingError) as e:
+        tt.tt_shard_shape(8, 8, "RX")
+    assert e.value.status == 1
+
+
+@pytest.mark.parametrize("k", [1, 2])
+def test_exact_plan_equals_bruteforce(k):
+    rng = np.random.default_rng(100 + k)
+    for trial in range(8):
+        L = int(rng.integers(1, 3))
+        b = int(rng.choice([4, 6, 8, 12, 16, 48]))
+        widths = [int(v) for v in rng.choice([2, 4, 6, 8, 10, 12, 24, 32, 112], size=L + 1)]
+        chain = oc.make_chain(b, widths)
+        ref = oc.bruteforce(chain, k)
+        if ref[0] == oc.INF:
+            with pytest.raises(tt.TilingError):
+                tt.tt_plan_chain(fc_layers(widths), b, k, tt.TT_PLAN_EXACT)
+            continue
+        p = tt.tt_plan_chain(fc_layers(widths), b, k, tt.TT_PLAN_EXACT)
+        assert p.cost == ref[0], (b, widths)
+        # the returned tiling is valid: the oracle prices it at the same cost
+        assert oc.chain_cost(chain, k, p.x(), p.g(), p.w())[0] == p.cost
+        assert p.cost == sum(p.delta(j) << j for j in range(k))          # Theorem 1
+
+
+def test_exact_plan_three_cuts_single_layer():
+    chain = oc.make_chain(16, [24, 40])
+    ref = oc.bruteforce(chain, 3)
+    p = tt.tt_plan_chain(fc_layers([24, 40]), 16, 3, tt.TT_PLAN_EXACT)
+    assert p.cost == ref[0]
+
+
+def test_exact_plan_with_pins():
+    widths, b, k = [8, 24, 12], 16, 2
+    chain = oc.make_chain(b, widths)
+    for pins in [dict(pin_x0="RR", pin_g0="RR"), dict(pin_xL="RR", pin_gL="rr"), dict(pin_x0="Cr")]:
+        p = tt.tt_plan_chain(fc_layers(widths), b, k, tt.TT_PLAN_EXACT, **pins)
+        assert p.cost == oc.bruteforce(chain, k, **pins)[0]
+        if "pin_x0" in pins:
+            assert p.x()[0] == pins["pin_x0"]
+        if "pin_gL" in pins:
+            assert p.g()[-1] == pins["pin_gL"]
+
+
+def test_tiny_config_plan_is_the_bruteforce_optimum():
+    cfg = CONFIGS["tiny_mlp"]
+    p = tt.tt_plan_chain(fc_layers(cfg.widths), cfg.batch, cfg.k, tt.TT_PLAN_EXACT)
+    assert p.cost == oc.bruteforce(oc.make_chain(cfg.batch, list(cfg.widths)), cfg.k)[0] == 57984
+
+
+@pytest.mark.parametrize("name", ["tiny_mlp", "alexnet_fc", "vgg16_fc"])
+def test_recursive_plan_equals_algorithm1_oracle(name):
+    cfg = CONFIGS[name]
+    chain = oc.make_chain(cfg.batch, list(cfg.widths))
+    ref = oc.recursive(chain, cfg.k)
+    p = tt.tt_plan_chain(fc_layers(cfg.widths), cfg.batch, cfg.k, tt.TT_PLAN_RECURSIVE)
+    assert p.cost == ref[0]
+    assert (p.x(), p.g(), p.w()) == (ref[1], ref[2], ref[3])
+    assert [p.delta(j) for j in range(cfg.k)] == ref[4]
+    exact = tt.tt_plan_chain(fc_layers(cfg.widths), cfg.batch, cfg.k, tt.TT_PLAN_EXACT)
+    assert exact.cost <= p.cost
+    assert oc.chain_cost(chain, cfg.k, exact.x(), exact.g(), exact.w())[0] == exact.cost
+
+
+def test_recursive_random_chains_and_pins():
+    rng = np.random.default_rng(9)
+    for _ in range(10):
+        b = int(rng.choice([4, 8, 12, 16, 48])); widths = [int(v) for v in rng.choice([4, 8, 10, 12, 24, 32], size=3)]
+        chain = oc.make_chain(b, widths)
+        pins = dict(pin_x0="RR") if rng.random() < 0.5 else {}
+        ref = oc.recursive(chain, 2, **pins)
+        if ref[0] == oc.INF:
+            continue
+        p = tt.tt_plan_chain(fc_layers(widths), b, 2, tt.TT_PLAN_RECURSIVE, **pins)
+        assert (p.cost, p.x(), p.g(), p.w()) == (ref[0], ref[1], ref[2], ref[3])
+
+
+def test_plan_eval_equals_oracle_on_random_tilings():
+    rng = np.random.default_rng(3)
+    widths, b, k = [8, 16, 10], 12, 2
+    chain = oc.make_chain(b, widths)
+    ts = tl.all_tilings(k)
+    for _ in range(300):
+        x = [ts[i] for i in rng.integers(0, 9, 3)]; g = [ts[i] for i in rng.integers(0, 9, 3)]
+        w = [ts[i] for i in rng.integers(0, 9, 2)]
+        ref = oc.chain_cost(chain, k, x, g, w)
+        if ref[0] == oc.INF:
+            with pytest.raises(tt.TilingError) as e:
+                tt.tt_plan_eval(fc_layers(widths), b, k, x, g, w)
+            assert e.value.status == 2
+        else:
+            cost, delta, forms = tt.tt_plan_eval(fc_layers(widths), b, k, x, g, w)
+            assert (cost, delta, forms) == (ref[0], ref[2], ref[1])
+
+
+def test_conv_chain_plan():
+    # areas carry the image / filter-tap multipliers (Sec. 4.5); 1x1 images reduce to FC
+    conv = [tt.layer("conv", "none", 4, 8, H=1, W=1, R=1, S=1, pad=0), tt.layer("conv", "none", 8, 4, H=1, W=1, R=1, S=1, pad=0)]
+    assert tt.tt_plan_chain(conv, 8, 2).cost == tt.tt_plan_chain(fc_layers([4, 8, 4]), 8, 2).cost
+    big = [tt.layer("conv", "none", 4, 8, H=8, W=8, R=3, S=3, pad=1), tt.layer("conv", "none", 8, 4, H=8, W=8, R=3, S=3, pad=1)]
+    p = tt.tt_plan_chain(big, 8, 1)
+    ref = oc.bruteforce(oc.make_chain(8, [4, 8, 4], xmult=[64, 64, 64], wmult=[0, 9, 9]), 1)
+    assert p.cost == ref[0] and p.w() == ["r", "r"] and p.x() == ["R"] * 3      # large images: data parallel wins
+
+
+def test_planner_argument_errors():
+    with pytest.raises(tt.TilingError) as e:
+        tt.tt_plan_chain(fc_layers([8, 8]), 8, 7)
+    assert e.value.status == 1
+    with pytest.raises(tt.TilingError) as e:
+        tt.tt_plan_chain([tt.layer("fc", "none", 8, 4), tt.layer("fc", "none", 5, 4)], 8, 1)
+    assert e.value.status == 1
+    with pytest.raises(tt.TilingError) as e:
+        tt.tt_plan_chain(fc_layers([8, 8]), 8, 5, tt.TT_PLAN_EXACT)
+    assert e.value.status == 3
+    with pytest.raises(tt.TilingError) as e:
+        tt.tt_plan_chain(fc_layers([3, 5]), 7, 1)       # nothing can be cut evenly
+    assert e.value.status == 2
+
+
+def test_host_side_errors_of_device_calls_need_no_gpu():
+    # detected before any launch: bad letters, uneven cuts, bad element size, NULL shards
+    import ctypes as C
+    L = tt.binding.lib()
+    null = (C.c_void_p * 4)(0, 0, 0, 0)
+    one = (C.c_void_p * 4)(256, 256, 256, 256)
+    assert L.tt_retile(one, tt.tiling("RR"), one, tt.tiling("CC"), 2, 6, 8, 2, None) == 2      # 6 rows cut twice
+    assert L.tt_retile(one, tt.tiling("RR"), one, tt.tiling("CC"), 2, 8, 8, 3, None) == 1      # element size
+    assert L.tt_retile(null, tt.tiling("RR"), one, tt.tiling("CC"), 2, 8, 8, 2, None) == 1     # NULL shard
+    assert L.tt_retile(one, tt.tiling("RX"), one, tt.tiling("CC"), 2, 8, 8, 2, None) == 1      # bad letter
+    assert L.tt_retile(one, tt.tiling("RR"), one, tt.tiling("CC"), 2, 0, 8, 2, None) == 0      # empty tensor: no-op
+    lay = tt.layer("fc", "none", 10, 6)
+    f = tt.forms("22")
+    assert L.tt_fc_forward(C.byref(lay), 8, 2, tt.TT_BF16, tt.tiling("RR"), tt.tiling("rr"), tt.tiling("RR"), f,
+                           one, one, one, None, 0, None) == 2                                # 6 columns, two N-splits
+    conv = tt.layer("conv", "none", 8, 8, H=4, W=4, R=3, S=3, pad=1)
+    assert L.tt_fc_forward(C.byref(conv), 8, 2, tt.TT_BF16, tt.tiling("RR"), tt.tiling("rr"), tt.tiling("RR"), None,
+                           one, one, one, None, 0, None) == 1                                # wrong layer kind
+
+
+def test_workspace_query_runs_on_host():
+    lay = tt.layer("fc", "relu", 64, 32)
+    assert tt.tt_fc_workspace_bytes(lay, 16, 2, "bf16", tt.TT_OP_FWD, "RR", "rr", "RR", forms_a="11") == 0
+    n = tt.tt_fc_workspace_bytes(lay, 16, 2, "bf16", tt.TT_OP_FWD, "CC", "RR", "RR", forms_a="33")
+    assert n == 4 * 16 * 32 * 4                               # four fp32 partial blocks
+    assert tt.tt_fc_workspace_bytes(lay, 16, 2, "bf16", tt.TT_OP_DGRAD, "CC", "RR", "RR", "rr", "CC") > 0
