@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the tiled execution hot path on one MI355X.
+
+One step = forward and backward of the whole FC stack (all 3 products per layer, with their input conversions,
+output conversions and partial-sum reductions) under the planner's minimum-communication k-cut tiling, all 2^k
+shards living in this GPU's HBM.  Inputs are resident in HBM before the timed region.  The timed region replays a
+HIP graph of one step K times; a second, eager pass of K steps brackets every kernel with HIP events (on the launch
+stream) to get per-kernel durations for the roofline line.
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/*pmc*.txt); None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "alexnet_fc", "wide_mlp", "tiny_mlp"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
+    return ap.parse_args()
+
+
+class Chain:
+    """Device state of one FC chain under a plan: shards of x_l, g_l, W_l, dW_l and one workspace."""
+
+    def __init__(self, cfg, tt, torch, tilings=None):
+        import numpy as np
+        from synthetic import CONFIGS  # noqa: F401
+        self.cfg, self.tt, self.torch = cfg, tt, torch
+        self.k, self.b, self.L, self.dt = cfg.k, cfg.batch, cfg.n_layers, cfg.dtype
+        self.layers = [tt.layer("fc", "relu" if cfg.act(l) else "none", cfg.widths[l - 1], cfg.widths[l])
+                       for l in range(1, self.L + 1)]
+        if tilings is None:
+            plan = tt.tt_plan_chain([tt.layer("fc", "none", cfg.widths[l], cfg.widths[l + 1]) for l in range(self.L)],
+                                    self.b, self.k, tt.TT_PLAN_EXACT)
+            self.tx, self.tg, self.tw = plan.x(), plan.g(), plan.w()
+            self.forms = [[plan.forms(l, op) for op in range(3)] for l in range(1, self.L + 1)]
+            self.plan_cost = plan.cost
+        else:
+            self.tx, self.tg, self.tw, self.forms = tilings
+            self.plan_cost = None
+        tdt = torch.bfloat16 if self.dt == "bf16" else torch.float32
+        dev = "cuda:0"
+
+        def upload(T, t):
+            out = []
+            rows, cols = T.shape
+            sr, sc = tt.tt_shard_shape(rows, cols, t)
+            n = 1 << self.k
+            for s in range(n):
+                rb, cb = block_of(t, s)
+                piece = np.ascontiguousarray(T[rb * sr:(rb + 1) * sr, cb * sc:(cb + 1) * sc])
+                if self.dt == "bf16":
+                    out.append(torch.from_numpy(piece.view(np.int16)).to(dev).view(torch.bfloat16))
+                else:
+                    out.append(torch.from_numpy(piece).to(dev))
+            return out
+
+        def empty(rows, cols, t):
+            sr, sc = tt.tt_shard_shape(rows, cols, t)
+            return [torch.zeros((sr, sc), dtype=tdt, device=dev) for _ in range(1 << self.k)]
+
+        w = cfg.widths
+        self.x = [upload(cfg.x0(), self.tx[0])] + [empty(self.b, w[l], self.tx[l]) for l in range(1, self.L + 1)]
+        self.g = [empty(self.b, w[l], self.tg[l]) for l in range(self.L)] + [upload(cfg.grad_out(), self.tg[self.L])]
+        self.W = [upload(cfg.weight(l), self.tw[l - 1]) for l in range(1, self.L + 1)]
+        self.dW = [empty(w[l - 1], w[l], self.tw[l - 1]) for l in range(1, self.L + 1)]
+        need = 256
+        for l in range(1, self.L + 1):
+            f = self.forms[l - 1]
+            need = max(need, tt.tt_fc_workspace_bytes(self.layers[l - 1], self.b, self.k, self.dt, tt.TT_OP_FWD,
+                                                      self.tx[l - 1], self.tw[l - 1], self.tx[l], forms_a=f[0]))
+            need = max(need, tt.tt_fc_workspace_bytes(self.layers[l - 1], self.b, self.k, self.dt, tt.TT_OP_DGRAD,
+                                                      self.tx[l - 1], self.tw[l - 1], self.tx[l], self.tg[l], self.tg[l - 1],
+                                                      f[1], f[2]))
+        self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        self.ws_bytes = need
+
+    def step(self):
+        tt = self.tt
+        for l in range(1, self.L + 1):
+            tt.tt_fc_forward(self.layers[l - 1], self.b, self.k, self.dt, self.tx[l - 1], self.tw[l - 1], self.tx[l],
+                             self.forms[l - 1][0], self.x[l - 1], self.W[l - 1], self.x[l], self.ws)
+        for l in range(self.L, 0, -1):
+            tt.tt_fc_backward(self.layers[l - 1], self.b, self.k, self.dt, self.tx[l - 1], self.tw[l - 1], self.tx[l],
+                              self.tg[l], self.tg[l - 1], self.forms[l - 1][1], self.forms[l - 1][2], self.x[l - 1],
+                              self.W[l - 1], self.x[l], self.g[l], self.g[l - 1], self.dW[l - 1], self.ws)
+
+
+def block_of(t, s):
+    """(row block, column block) of shard s under tiling string t (host-side placement of synthetic inputs)."""
+    k = len(t)
+    rb = cb = 0
+    for j, ch in enumerate(t):
+        bit = (s >> (k - 1 - j)) & 1
+        if ch == "R":
+            rb = 2 * rb + bit
+        elif ch == "C":
+            cb = 2 * cb + bit
+    return rb, cb
+
+
+def aggregate(records):
+    agg = {}
+    for r in records:
+        key = (r["kernel"], r["count"], r["d0"], r["d1"], r["d2"])
+        a = agg.setdefault(key, dict(kernel=r["kernel"], count=r["count"], d0=r["d0"], d1=r["d1"], d2=r["d2"],
+                                     bytes=r["bytes"], flops=r["flops"], ms=0.0, launches=0))
+        a["ms"] += r["ms"]
+        a["launches"] += 1
+    return sorted(agg.values(), key=lambda a: -a["ms"])
+
+
+def cpu_baseline(cfg):
+    """The oracle (numpy fp64, untiled) timed on this host for one fwd+bwd step of the same workload."""
+    import numpy as np
+    from oracle import layers as ly
+    from synthetic import bf16_bits_to_f64
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    conv = (lambda a: bf16_bits_to_f64(a)) if cfg.dtype == "bf16" else (lambda a: a.astype(np.float64))
+    x = [conv(cfg.x0())]
+    Ws = [conv(cfg.weight(l)) for l in range(1, cfg.n_layers + 1)]
+    g = conv(cfg.grad_out())
+    t0 = time.perf_counter()
+    for l in range(1, cfg.n_layers + 1):
+        x.append(ly.fc_forward(x[l - 1], Ws[l - 1], bool(cfg.act(l))))
+    for l in range(cfg.n_layers, 0, -1):
+        g, _dw = ly.fc_backward(g, x[l - 1], Ws[l - 1], x[l], bool(cfg.act(l)))
+    dt = time.perf_counter() - t0
+    return {"value": cfg.flops() / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "1 full untiled fwd+bwd step of %s in fp64 numpy (%.1f GFLOP, %.2f s)" % (cfg.name, cfg.flops() / 1e9, dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (all 2^k shards are simulated in one HBM); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_1805_04170_amd as tt
+    from synthetic import CONFIGS
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    tt.binding.lib()
+    cfg = CONFIGS[args.workload]
+    torch.cuda.set_device(0)
+    chain = Chain(cfg, tt, torch)
+    K, W = args.steps, args.warmup
+
+    for _ in range(max(W, 1)):
+        chain.step()
+    torch.cuda.synchronize()
+
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            chain.step()
+        for _ in range(2):
+            graph.replay()
+        torch.cuda.synchronize()
+
+    run = graph.replay if graph is not None else chain.step
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        run()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / K
+    tflops = cfg.flops() / (elapsed / K) / 1e12
+
+    # per-kernel durations: eager pass, HIP events around every launch on the launch stream
+    tt.tt_profile_begin()
+    for _ in range(K):
+        chain.step()
+    records = tt.tt_profile_end()
+    agg = aggregate(records)
+    gemm_ms = sum(a["ms"] for a in agg if a["kernel"].startswith("gemm")) / K
+    conv_ms = sum(a["ms"] for a in agg if not a["kernel"].startswith("gemm")) / K
+    dom = agg[0]
+    dom_ms = dom["ms"] / dom["launches"]
+    key = "%s:%s" % (args.workload, dom["kernel"])
+    roofline = {
+        "bound": "mfma", "kernel": "%s count=%d M=%d N=%d K=%d" % (dom["kernel"], dom["count"], dom["d0"], dom["d1"], dom["d2"]),
+        "achieved": dom["flops"] / (dom_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "frac": dom["flops"] / (dom_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(key),
+        "avg_ms": dom_ms, "launches": dom["launches"],
+        "algorithmic_bytes": dom["bytes"], "hbm_GBps": dom["bytes"] / (dom_ms * 1e-3) / 1e9,
+        "hbm_frac": dom["bytes"] / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+    }
+    kernels = [{"kernel": a["kernel"], "count": a["count"], "d": [a["d0"], a["d1"], a["d2"]], "launches_per_step": a["launches"] / K,
+                "avg_ms": a["ms"] / a["launches"],
+                "TFLOPs": (a["flops"] / (a["ms"] / a["launches"] * 1e-3) / 1e12) if a["flops"] else None,
+                "GBps": a["bytes"] / (a["ms"] / a["launches"] * 1e-3) / 1e9} for a in agg]
+
+    # retile headline: the largest tensor of the workload between two non-replicated tilings
+    rows, cols = cfg.widths[0], cfg.widths[1]
+    ka = cfg.k
+    A, B = "R" * ka, "C" * ka
+    esz = 2 if cfg.dtype == "bf16" else 4
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    sr, sc = tt.tt_shard_shape(rows, cols, A)
+    src = [torch.zeros((sr, sc), dtype=tdt, device="cuda:0") for _ in range(1 << ka)]
+    sr, sc = tt.tt_shard_shape(rows, cols, B)
+    dst = [torch.zeros((sr, sc), dtype=tdt, device="cuda:0") for _ in range(1 << ka)]
+    for _ in range(3):
+        tt.tt_retile(dst, B, src, A, rows, cols, esz)
+    tt.tt_profile_begin()
+    for _ in range(20):
+        tt.tt_retile(dst, B, src, A, rows, cols, esz)
+    rrec = tt.tt_profile_end()
+    r_ms = sum(r["ms"] for r in rrec) / len(rrec)
+    r_gbs = rrec[0]["bytes"] / (r_ms * 1e-3) / 1e9
+    retile = {"tensor": "W_1 %dx%d %s" % (rows, cols, cfg.dtype), "from": A, "to": B, "bytes": rrec[0]["bytes"],
+              "avg_ms": r_ms, "GBps": r_gbs, "peak": PEAK_HBM_GBS, "frac": r_gbs / PEAK_HBM_GBS}
+    del src, dst
+
+    out = {
+        "metric": "tiled fwd+bwd TFLOP/s at VGG-16 FC shapes (% MFMA peak); retile GB/s (% HBM)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": "%s: batch %d, %s, k=%d (%d shards), planner EXACT tiling" % (
+            cfg.name, cfg.batch, "->".join(str(w) for w in cfg.widths), cfg.k, 1 << cfg.k),
+            "tiling_x": chain.tx, "tiling_g": chain.tg, "tiling_w": chain.tw, "plan_cost_elems": chain.plan_cost,
+            "timed": "hip graph replay" if graph is not None else "eager launches"},
+        "frac_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "roofline": roofline,
+        "retile": retile,
+        "breakdown_ms_per_step": {"products": gemm_ms, "conversions_and_reductions": conv_ms},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -200,6 +200,26 @@ tt_status tt_conv_backward(const tt_layer *layer, int64_t batch, int k, int dtyp
                            const void *const *Y, const void *const *dY, void *const *dX, void *const *dW,
                            void *workspace, size_t ws_bytes, void *stream);
 
+/* ------------------------------------------------------------ kernel timing
+ * Optional instrumentation for measurement (the counterpart of the paper's computation-only runs, Sec. 6.2: it
+ * separates the time of the conversion / reduction kernels from the time of the shard products).
+ * Between tt_profile_begin and tt_profile_end every kernel the calling thread launches through this library is
+ * bracketed by a pair of HIP events on the launch stream.  tt_profile_end waits for the last event, fills the
+ * records and disables recording.  Not to be used during stream capture.  The record list is per thread. */
+enum { TT_K_CONVERT = 0, TT_K_GATE = 1, TT_K_REDUCE = 2, TT_K_GEMM_NN = 3, TT_K_GEMM_NT = 4, TT_K_GEMM_TN = 5,
+       TT_K_GEMM_TT = 6, TT_K_GEMM_GENERIC = 7, TT_K_CONV_FWD = 8, TT_K_CONV_DGRAD = 9, TT_K_CONV_WGRAD = 10 };
+typedef struct {
+    int32_t kernel;      /* TT_K_* */
+    int32_t count;       /* shards covered by the launch */
+    int64_t d0, d1, d2;  /* products: M, N, K per shard; conversions / reductions: rows, cols, element bytes */
+    uint64_t bytes;      /* algorithmic HBM bytes of the launch (operands read once + outputs written once) */
+    uint64_t flops;      /* 2 M N K count for products, 0 otherwise */
+    float ms;            /* elapsed between the two events */
+} tt_kernel_record;
+tt_status tt_profile_begin(void);
+tt_status tt_profile_end(int *n_records);                 /* TT_EDEVICE if an event call fails */
+tt_status tt_profile_get(int index, tt_kernel_record *out); /* valid until the next tt_profile_begin */
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,8 +26,10 @@ EXPORTS = [
     "tt_strerror", "tt_shard_shape", "tt_plan_chain", "tt_plan_eval", "tt_plan_k", "tt_plan_layers", "tt_plan_cost",
     "tt_plan_delta", "tt_plan_tiling", "tt_plan_forms", "tt_plan_free", "tt_retile", "tt_retile_gate", "tt_reduce",
     "tt_shard_gemm", "tt_fc_workspace_bytes", "tt_fc_forward", "tt_fc_backward", "tt_conv_workspace_bytes",
-    "tt_conv_forward", "tt_conv_backward",
+    "tt_conv_forward", "tt_conv_backward", "tt_profile_begin", "tt_profile_end", "tt_profile_get",
 ]
+KERNEL_NAMES = ["convert", "gate", "reduce", "gemm_nn", "gemm_nt", "gemm_tn", "gemm_tt", "gemm_generic", "conv_fwd",
+                "conv_dgrad", "conv_wgrad"]
 
 
 class TilingError(RuntimeError):
@@ -38,6 +40,11 @@ class TilingError(RuntimeError):
 
 class tt_tiling(ctypes.Structure):
     _fields_ = [("cut", ctypes.c_uint8 * TT_MAX_K)]
+
+
+class tt_kernel_record(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("count", ctypes.c_int32), ("d0", ctypes.c_int64), ("d1", ctypes.c_int64),
+                ("d2", ctypes.c_int64), ("bytes", ctypes.c_uint64), ("flops", ctypes.c_uint64), ("ms", ctypes.c_float)]
 
 
 class tt_layer(ctypes.Structure):
@@ -98,6 +105,8 @@ def lib():
         L.tt_conv_forward.argtypes = fwd_args
         L.tt_fc_backward.argtypes = bwd_args
         L.tt_conv_backward.argtypes = bwd_args
+        L.tt_profile_end.argtypes = [ctypes.POINTER(ctypes.c_int)]
+        L.tt_profile_get.argtypes = [ctypes.c_int, ctypes.POINTER(tt_kernel_record)]
         _lib = L
     return _lib
 
@@ -342,3 +351,22 @@ def tt_conv_backward(lay, batch, k, dtype, tX, tW, tY, tdY, tdX, forms_dgrad, fo
                      workspace=None, stream=None):
     _backward(lib().tt_conv_backward, "tt_conv_backward", lay, batch, k, dtype, tX, tW, tY, tdY, tdX, forms_dgrad,
               forms_wgrad, X, W, Y, dY, dX, dW, workspace, stream)
+
+
+# ------------------------------------------------------------- kernel timing
+
+def tt_profile_begin():
+    _check(lib().tt_profile_begin(), "tt_profile_begin")
+
+
+def tt_profile_end():
+    """Returns the list of per-launch records as dicts."""
+    n = ctypes.c_int()
+    _check(lib().tt_profile_end(ctypes.byref(n)), "tt_profile_end")
+    out = []
+    for i in range(n.value):
+        r = tt_kernel_record()
+        _check(lib().tt_profile_get(i, ctypes.byref(r)), "tt_profile_get")
+        out.append(dict(kernel=KERNEL_NAMES[r.kernel], count=r.count, d0=r.d0, d1=r.d1, d2=r.d2, bytes=r.bytes,
+                        flops=r.flops, ms=r.ms))
+    return out

@@ -375,6 +375,10 @@ tt_status launch_convert(void *const *dst, const uint8_t *Bl, const void *const 
     if (blocks >= (uint64_t(1) << 31)) return TT_EUNSUPPORTED;
 
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    // algorithmic traffic: every unique block read once (plus the gate source), every destination copy written once
+    const uint64_t tensor_bytes = (uint64_t)rows * (uint64_t)cols * (uint64_t)elem_bytes;
+    ProfileScope scope(stream, gated ? TT_K_GATE : TT_K_CONVERT, n, rows, cols, elem_bytes,
+                       tensor_bytes * ((gated ? 2u : 1u) + p.nrep), 0);
     if (!gated) return launch_convert_g<0>(vbytes, p, (uint32_t)blocks, s);
     if (gate_dtype == TT_BF16) return launch_convert_g<1>(vbytes, p, (uint32_t)blocks, s);
     if (gate_dtype == TT_F32) return launch_convert_g<2>(vbytes, p, (uint32_t)blocks, s);
@@ -445,6 +449,8 @@ tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, cons
     uint64_t blocks = (uint64_t)p.tiles_per_piece * p.pieces * (uint64_t(1) << (B.kR + B.kC));
     if (blocks >= (uint64_t(1) << 31)) return TT_EUNSUPPORTED;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const uint64_t elems = (uint64_t)rows * (uint64_t)cols;
+    ProfileScope scope(stream, TT_K_REDUCE, n, rows, cols, (int64_t)out_b, elems * 4u * p.nred + elems * out_b * p.nrep, 0);
     if (ev == 4) return out_dtype == TT_BF16 ? launch_reduce_e<4, true>(p, (uint32_t)blocks, act, unroll, s)
                                               : launch_reduce_e<4, false>(p, (uint32_t)blocks, act, unroll, s);
     return out_dtype == TT_BF16 ? launch_reduce_e<1, true>(p, (uint32_t)blocks, act, unroll, s)

@@ -351,6 +351,12 @@ tt_status launch_gemm(int count, const void *const *A, const void *const *B, voi
     const int64_t a_contig = trans_a ? M : K, b_contig = trans_b ? K : N;
     const bool mfma_ok = in_dtype == TT_BF16 && K > 0 && a_contig % 8 == 0 && b_contig % 8 == 0 &&
                          all_aligned16(A, count) && all_aligned16(B, count);
+    const uint64_t in_b = in_dtype == TT_BF16 ? 2 : 4, out_b = out_dtype == TT_BF16 ? 2 : 4;
+    const int kclass = !mfma_ok ? TT_K_GEMM_GENERIC
+                                : (trans_a ? (trans_b ? TT_K_GEMM_TT : TT_K_GEMM_TN) : (trans_b ? TT_K_GEMM_NT : TT_K_GEMM_NN));
+    ProfileScope scope(stream, kclass, count, M, N, K,
+                       (uint64_t)count * (in_b * ((uint64_t)M * K + (uint64_t)K * N) + out_b * (uint64_t)M * N),
+                       2ull * (uint64_t)M * (uint64_t)N * (uint64_t)K * (uint64_t)count);
     if (mfma_ok) {
         GemmParams p;
         for (int i = 0; i < kMaxShards; ++i) {

@@ -110,4 +110,13 @@ tt_status launch_reduce(void *const *dst, const uint8_t *B, int out_dtype, const
 tt_status launch_gemm(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
                       int64_t K, int trans_a, int trans_b, int in_dtype, int out_dtype, int act, void *stream);
 
+// ---- optional kernel timing (profile.cpp).  A scope object brackets one launch with two events when the calling
+// thread has recording switched on; otherwise it does nothing.
+struct ProfileScope {
+    ProfileScope(void *stream, int kernel, int count, int64_t d0, int64_t d1, int64_t d2, uint64_t bytes, uint64_t flops);
+    ~ProfileScope();
+    int slot;
+    void *stream;
+};
+
 } // namespace tt
