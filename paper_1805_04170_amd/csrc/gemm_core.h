@@ -100,6 +100,10 @@ template <int ROWS, bool KC> struct Slots {
 };
 
 // ---- register staging of one operand tile -------------------------------------------------------------------------
+// Transposing side (!KC): the tile is cut into blocks of 4 k x 8 rows; block b = (rv, kg) covers rows 8 rv .. 8 rv + 7
+// and k = 4 kg .. 4 kg + 3.  Lanes run over kg first (16 k-groups), then rv: the 8-byte LDS stores of a wave then fall
+// on 32 distinct 8-byte bank groups (two lanes each, the minimum), where running over rv first would pile eight lanes on
+// each group.  Global loads still cover 64 contiguous bytes per k-row per wave (4 lanes x 16 bytes).
 template <int ROWS, bool KC> struct Stage {
     static constexpr int NS = Slots<ROWS, KC>::value;
     static constexpr int NV = KC ? NS : NS * 4;
@@ -112,9 +116,8 @@ template <int ROWS, bool KC> struct Stage {
 #pragma unroll
             for (int i = 0; i < NS; ++i) ld.init(i, row0 + ((tid + i * kThreads) >> 3));
         } else {
-            constexpr int RV = ROWS / 8;
 #pragma unroll
-            for (int i = 0; i < NS; ++i) ld.init(i, row0 + ((tid + i * kThreads) % RV) * 8);
+            for (int i = 0; i < NS; ++i) ld.init(i, row0 + ((tid + i * kThreads) >> 4) * 8);
         }
     }
 
@@ -131,10 +134,9 @@ template <int ROWS, bool KC> struct Stage {
                 r[i] = KMASK ? ld.load_masked(i, k) : ld.load(i, k);
             }
         } else {
-            constexpr int RV = ROWS / 8;
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
-                const int kg = (tid + i * kThreads) / RV;
+                const int kg = (tid + i * kThreads) & 15;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int k = k0 + kg * 4 + q;
@@ -154,11 +156,10 @@ template <int ROWS, bool KC> struct Stage {
                 *reinterpret_cast<u32x4 *>(lds + (v >> 3) * LDK + ((v & 7) << 3)) = r[i];
             }
         } else {
-            constexpr int RV = ROWS / 8;
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
                 const int b = tid + i * kThreads;
-                const int rv = b % RV, kg = b / RV;
+                const int rv = b >> 4, kg = b & 15;
                 uint16_t *dst = lds + (rv * 8) * LDK + kg * 4;
                 const u32x4 &a = r[i * 4 + 0], &bq = r[i * 4 + 1], &c = r[i * 4 + 2], &d = r[i * 4 + 3];
 #pragma unroll
@@ -206,22 +207,27 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
     SB::bind(lb, n0);
     const int nk = (K + BK - 1) / BK;
 
+    // Fragment reads run one k-step ahead of the MFMAs that consume them (two register sets), so the matrix pipe does
+    // not idle behind LDS latency when a SIMD holds a single wave.
     auto compute = [&](const uint16_t *As, const uint16_t *Bs) {
+        bf16x8 af[2][TM], bf[2][TN];
+        const uint16_t *ap = As + (wm0 + (lane & 31)) * LDK + (lane >> 5) * 8;
+        const uint16_t *bp = Bs + (wn0 + (lane & 31)) * LDK + (lane >> 5) * 8;
+        auto fetch = [&](int ks, int set) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[set][i] = *reinterpret_cast<const bf16x8 *>(ap + i * 32 * LDK + ks * 16);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bf[set][j] = *reinterpret_cast<const bf16x8 *>(bp + j * 32 * LDK + ks * 16);
+        };
+        fetch(0, 0);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[TM], bf[TN];
-            const int koff = ks * 16 + (lane >> 5) * 8;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8 *>(As + (wm0 + i * 32 + (lane & 31)) * LDK + koff);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                bf[j] = *reinterpret_cast<const bf16x8 *>(Bs + (wn0 + j * 32 + (lane & 31)) * LDK + koff);
+            if (ks + 1 < BK / 16) fetch(ks + 1, (ks + 1) & 1);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bf[ks & 1][j], acc[i][j], 0, 0, 0);
         }
     };
 
