@@ -1,0 +1,282 @@
+// Convolution shard products as implicit GEMMs on the MFMA tile engine (gemm_core.h).
+//
+// Stride-1 cross-correlation with zero padding (the textbook definition; arXiv 1805.04170 Sec. 4.5 only says which
+// dimensions of the 4-D tensors are cut).  Layouts: activations NHWC, filters [K][R][S][C]; per shard the channel
+// counts are the shard's own (Cs input channels, Ks output channels), the batch is the shard's Ns images.
+//
+//   forward   Y[(n,p,q)][ko]   = sum_{(r,s,c)}  X[n, p+r-pad, q+s-pad, c] * W[ko][(r,s,c)]
+//             GEMM M = Ns*P*Q, N = Ks, K = R*S*Cs;  A gathered (K contiguous along c), B dense rows of W
+//   dgrad     dX[(n,h,w)][c]   = sum_{(r,s,ko)} dY[n, h+pad-r, w+pad-s, ko] * W[ko][r][s][c]
+//             GEMM M = Ns*H*W, N = Cs, K = R*S*Ks;  A gathered from dY, B = filters read as [(r,s,ko)][c] (c contiguous)
+//   wgrad     dW[ko][(r,s,c)]  = sum_{(n,p,q)}  dY[(n,p,q)][ko] * X[n, p+r-pad, q+s-pad, c]
+//             GEMM M = Ks, N = R*S*Cs, K = Ns*P*Q;  A = dY transposed (dense), B gathered from X (c contiguous)
+// No im2col buffer is ever materialised: the gather happens while operand tiles are staged into LDS.
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include "gemm_core.h"
+#include "tt_internal.h"
+
+namespace tt {
+namespace {
+
+using core::and_mask;
+using core::kThreads;
+using core::kXcds;
+using core::u32x4;
+
+struct ConvGeom {
+    int32_t Ns, H, W, P, Q, R, S, pad;
+    int32_t Cs, Ks; // channels per shard: input, output
+};
+
+struct ConvParams {
+    const void *A[kMaxShards];
+    const void *B[kMaxShards];
+    void *C[kMaxShards];
+    ConvGeom g;
+    int32_t M, N, K, ldc;
+    int32_t tiles_m, tiles_n, per_xcd, total, relu;
+};
+
+__device__ __forceinline__ u32x4 load16(const char *base, int32_t elem_off)
+{
+    return *reinterpret_cast<const u32x4 *>(base + (ptrdiff_t)elem_off * 2);
+}
+
+// A operand of forward and dgrad: rows are output pixels (n, oy, ox), k = (tap, channel) with the channel contiguous.
+// in_y = oy + off + sgn * r, in_x = ox + off + sgn * s   (forward: off = -pad, sgn = +1; dgrad: off = +pad, sgn = -1)
+template <int SLOTS> struct GatherKC {
+    static constexpr bool KC = true;
+    const char *base;
+    int IH, IW, OH, OW, R, S, off, sgn, Ch; // Ch: channels per pixel of the source
+    int rows, K;
+    int32_t pix[SLOTS];   // element offset of source pixel (n, oy + off, ox + off), may be negative
+    uint32_t taps[SLOTS]; // bit t set: tap t reads inside the image
+    __device__ __forceinline__ void init(int slot, int row)
+    {
+        row = row < rows ? row : rows - 1;
+        const int n = row / (OH * OW), rem = row - n * (OH * OW);
+        const int oy = rem / OW, ox = rem - oy * OW;
+        pix[slot] = ((n * IH + oy + off) * IW + ox + off) * Ch;
+        uint32_t m = 0;
+        for (int r = 0; r < R; ++r)
+            for (int s = 0; s < S; ++s) {
+                const int iy = oy + off + sgn * r, ix = ox + off + sgn * s;
+                if (iy >= 0 && iy < IH && ix >= 0 && ix < IW) m |= 1u << (r * S + s);
+            }
+        taps[slot] = m;
+    }
+    __device__ __forceinline__ u32x4 load_masked(int slot, int k) const
+    {
+        const int tap = k / Ch, c = k - tap * Ch;
+        const int r = tap / S, s = tap - r * S;
+        const bool ok = k < K && ((taps[slot] >> tap) & 1u);
+        const int32_t o = pix[slot] + sgn * (r * IW + s) * Ch + c;
+        return and_mask(load16(base, ok ? o : 0), ok);
+    }
+    __device__ __forceinline__ u32x4 load(int slot, int k) const { return load_masked(slot, k); }
+};
+
+// B operand of dgrad: filters [Ks][R][S][Cs] read as rows c (contiguous), k = (tap, ko)
+template <int SLOTS> struct FilterRC {
+    static constexpr bool KC = false;
+    const char *base;
+    int RS, Cs, Ks, rows, K;
+    int32_t c0[SLOTS];
+    __device__ __forceinline__ void init(int slot, int row) { c0[slot] = row < rows ? row : rows - 8; }
+    __device__ __forceinline__ u32x4 load_masked(int slot, int k) const
+    {
+        const bool ok = k < K;
+        const int kk = ok ? k : K - 1;
+        const int tap = kk / Ks, ko = kk - tap * Ks;
+        return and_mask(load16(base, (ko * RS + tap) * Cs + c0[slot]), ok);
+    }
+    __device__ __forceinline__ u32x4 load(int slot, int k) const { return load_masked(slot, k); }
+};
+
+// B operand of wgrad: rows are (tap, c) with c contiguous, k = (n, p, q) walks the output pixels
+template <int SLOTS> struct GatherRC {
+    static constexpr bool KC = false;
+    const char *base;
+    int H, W, P, Q, S, pad, Cs, rows, K;
+    int32_t dy[SLOTS], dx[SLOTS], c0[SLOTS];
+    __device__ __forceinline__ void init(int slot, int row)
+    {
+        row = row < rows ? row : rows - 8;
+        const int tap = row / Cs;
+        c0[slot] = row - tap * Cs;
+        const int r = tap / S;
+        dy[slot] = r - pad;
+        dx[slot] = tap - r * S - pad;
+    }
+    __device__ __forceinline__ u32x4 load_masked(int slot, int k) const
+    {
+        const int kk = k < K ? k : K - 1;
+        const int n = kk / (P * Q), rem = kk - n * (P * Q);
+        const int p = rem / Q, q = rem - p * Q;
+        const int iy = p + dy[slot], ix = q + dx[slot];
+        const bool ok = k < K && iy >= 0 && iy < H && ix >= 0 && ix < W;
+        const int32_t o = ((n * H + iy) * W + ix) * Cs + c0[slot];
+        return and_mask(load16(base, ok ? o : 0), ok);
+    }
+    __device__ __forceinline__ u32x4 load(int slot, int k) const { return load_masked(slot, k); }
+};
+
+struct TileId { int shard, m0, n0; };
+template <int BM, int BN> __device__ __forceinline__ bool tile_of(const ConvParams &p, TileId *t)
+{
+    const int logical = core::logical_block(p.per_xcd, p.total);
+    if (logical < 0) return false;
+    const int tiles = p.tiles_m * p.tiles_n;
+    t->shard = logical / tiles;
+    const int r = logical - t->shard * tiles;
+    // consecutive workgroups walk the N tiles of one M tile: they share the gathered A rows in L2
+    t->n0 = (r % p.tiles_n) * BN;
+    t->m0 = (r / p.tiles_n) * BM;
+    return true;
+}
+
+// OP 0: forward, 1: dgrad
+template <int BM, int BN, int DEPTH, bool KMASK, int OP, bool OUT_BF16>
+__global__ __launch_bounds__(kThreads) void conv_gather_a_kernel(const ConvParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    TileId t;
+    if (!tile_of<BM, BN>(p, &t)) return;
+    const ConvGeom &g = p.g;
+    GatherKC<core::Slots<BM, true>::value> la;
+    la.base = reinterpret_cast<const char *>(p.A[t.shard]);
+    la.R = g.R; la.S = g.S;
+    la.rows = p.M; la.K = p.K;
+    if (OP == 0) { la.IH = g.H; la.IW = g.W; la.OH = g.P; la.OW = g.Q; la.off = -g.pad; la.sgn = 1; la.Ch = g.Cs; }
+    else         { la.IH = g.P; la.IW = g.Q; la.OH = g.H; la.OW = g.W; la.off = g.pad;  la.sgn = -1; la.Ch = g.Ks; }
+    if constexpr (OP == 0) {
+        core::DenseKC<core::Slots<BN, true>::value> lb;
+        lb.base = reinterpret_cast<const char *>(p.B[t.shard]);
+        lb.ld = p.K; lb.rows = p.N; lb.K = p.K;
+        core::tile_product<BM, BN, 2, 2, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
+    } else {
+        FilterRC<core::Slots<BN, false>::value> lb;
+        lb.base = reinterpret_cast<const char *>(p.B[t.shard]);
+        lb.RS = g.R * g.S; lb.Cs = g.Cs; lb.Ks = g.Ks; lb.rows = p.N; lb.K = p.K;
+        core::tile_product<BM, BN, 2, 2, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
+    }
+}
+
+template <int BM, int BN, int DEPTH, bool KMASK, bool OUT_BF16>
+__global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const ConvParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    TileId t;
+    if (!tile_of<BM, BN>(p, &t)) return;
+    const ConvGeom &g = p.g;
+    core::DenseRC<core::Slots<BM, false>::value> la; // dY shard [(n,p,q)][ko]: rows ko contiguous
+    la.base = reinterpret_cast<const char *>(p.A[t.shard]);
+    la.ld = g.Ks; la.rows = p.M; la.K = p.K;
+    GatherRC<core::Slots<BN, false>::value> lb;
+    lb.base = reinterpret_cast<const char *>(p.B[t.shard]);
+    lb.H = g.H; lb.W = g.W; lb.P = g.P; lb.Q = g.Q; lb.S = g.S; lb.pad = g.pad; lb.Cs = g.Cs; lb.rows = p.N; lb.K = p.K;
+    core::tile_product<BM, BN, 2, 2, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, false, smem);
+}
+
+template <typename Kern> tt_status launch(Kern kern, size_t smem, ConvParams &p, int BM, int BN, int count, hipStream_t s)
+{
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+        return TT_EDEVICE;
+    p.tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.N + BN - 1) / BN;
+    const int64_t total = (int64_t)p.tiles_m * p.tiles_n * count;
+    if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
+    p.total = (int32_t)total;
+    p.per_xcd = (int32_t)((total + kXcds - 1) / kXcds);
+    hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * kXcds), dim3(kThreads), smem, s, p);
+    return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
+}
+
+template <int OP, bool OUT_BF16> tt_status launch_gather_a(ConvParams &p, int count, hipStream_t s)
+{
+    const bool kmask = p.K % core::BK != 0;
+    if (p.M > 128) {
+        constexpr size_t sm = core::smem_bytes<256, 128>();
+        return kmask ? launch(conv_gather_a_kernel<256, 128, 2, true, OP, OUT_BF16>, sm, p, 256, 128, count, s)
+                     : launch(conv_gather_a_kernel<256, 128, 2, false, OP, OUT_BF16>, sm, p, 256, 128, count, s);
+    }
+    constexpr size_t sm = core::smem_bytes<128, 128>();
+    return kmask ? launch(conv_gather_a_kernel<128, 128, 1, true, OP, OUT_BF16>, sm, p, 128, 128, count, s)
+                 : launch(conv_gather_a_kernel<128, 128, 1, false, OP, OUT_BF16>, sm, p, 128, 128, count, s);
+}
+
+template <bool OUT_BF16> tt_status launch_wgrad(ConvParams &p, int count, hipStream_t s)
+{
+    const bool kmask = p.K % core::BK != 0;
+    if (p.M > 128) {
+        constexpr size_t sm = core::smem_bytes<256, 128>();
+        return kmask ? launch(conv_wgrad_kernel<256, 128, 2, true, OUT_BF16>, sm, p, 256, 128, count, s)
+                     : launch(conv_wgrad_kernel<256, 128, 2, false, OUT_BF16>, sm, p, 256, 128, count, s);
+    }
+    constexpr size_t sm = core::smem_bytes<128, 128>();
+    return kmask ? launch(conv_wgrad_kernel<128, 128, 1, true, OUT_BF16>, sm, p, 128, 128, count, s)
+                 : launch(conv_wgrad_kernel<128, 128, 1, false, OUT_BF16>, sm, p, 128, 128, count, s);
+}
+
+bool aligned16(const void *const *ptrs, int n)
+{
+    for (int i = 0; i < n; ++i)
+        if (!ptrs[i] || (reinterpret_cast<uintptr_t>(ptrs[i]) & 15)) return false;
+    return true;
+}
+
+} // namespace
+
+// op: TT_OP_FWD  A = X shards,  B = filter shards, C = Y shards  (Ns*P*Q x Ks)
+//     TT_OP_DGRAD A = dY shards, B = filter shards, C = dX shards (Ns*H*W x Cs)
+//     TT_OP_WGRAD A = dY shards, B = X shards,      C = dW shards (Ks x R*S*Cs)
+// Shard geometry: Ns images, Cs input channels, Ks output channels per shard.
+tt_status launch_conv(int op, int count, const void *const *A, const void *const *B, void *const *C, int64_t Ns,
+                      int64_t Cs, int64_t Ks, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad, int out_dtype,
+                      int act, void *stream)
+{
+    if (!A || !B || !C || count < 1 || count > kMaxShards) return TT_EINVAL;
+    if (Ns <= 0 || Cs <= 0 || Ks <= 0 || H <= 0 || W <= 0 || R <= 0 || S <= 0 || pad < 0) return TT_EINVAL;
+    const int64_t P = H + 2 * pad - R + 1, Q = W + 2 * pad - S + 1;
+    if (P <= 0 || Q <= 0) return TT_EINVAL;
+    if (out_dtype != TT_BF16 && out_dtype != TT_F32) return TT_EINVAL;
+    // the MFMA engine moves 16-byte vectors along channels and keeps offsets in 32 bits
+    if (Cs % 8 || Ks % 8 || R * S > 32) return TT_EUNSUPPORTED;
+    const int64_t lim = int64_t(1) << 30;
+    if (Ns * H * W * Cs >= lim || Ns * P * Q * Ks >= lim || Ks * R * S * Cs >= lim) return TT_EUNSUPPORTED;
+    if (!aligned16(A, count) || !aligned16(B, count) || !aligned16(const_cast<const void *const *>(C), count)) return TT_EUNSUPPORTED;
+
+    ConvParams p;
+    for (int i = 0; i < kMaxShards; ++i) {
+        p.A[i] = i < count ? A[i] : nullptr;
+        p.B[i] = i < count ? B[i] : nullptr;
+        p.C[i] = i < count ? C[i] : nullptr;
+    }
+    p.g = ConvGeom{(int32_t)Ns, (int32_t)H, (int32_t)W, (int32_t)P, (int32_t)Q, (int32_t)R, (int32_t)S, (int32_t)pad,
+                   (int32_t)Cs, (int32_t)Ks};
+    p.relu = act == TT_ACT_RELU;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const bool obf = out_dtype == TT_BF16;
+    const uint64_t ob = obf ? 2 : 4;
+    int64_t M, N, K;
+    int kclass;
+    if (op == TT_OP_FWD) { M = Ns * P * Q; N = Ks; K = R * S * Cs; kclass = TT_K_CONV_FWD; }
+    else if (op == TT_OP_DGRAD) { M = Ns * H * W; N = Cs; K = R * S * Ks; kclass = TT_K_CONV_DGRAD; }
+    else if (op == TT_OP_WGRAD) { M = Ks; N = R * S * Cs; K = Ns * P * Q; kclass = TT_K_CONV_WGRAD; }
+    else return TT_EINVAL;
+    if (K < 8) return TT_EUNSUPPORTED;
+    p.M = (int32_t)M; p.N = (int32_t)N; p.K = (int32_t)K; p.ldc = (int32_t)N;
+    // algorithmic bytes: each tensor of the shard touched once
+    const uint64_t x_b = (uint64_t)(Ns * H * W * Cs) * 2, y_b = (uint64_t)(Ns * P * Q * Ks), w_b = (uint64_t)(Ks * R * S * Cs);
+    const uint64_t bytes = op == TT_OP_FWD ? x_b + w_b * 2 + y_b * ob
+                         : op == TT_OP_DGRAD ? y_b * 2 + w_b * 2 + (uint64_t)(Ns * H * W * Cs) * ob
+                                             : y_b * 2 + x_b + w_b * ob;
+    ProfileScope scope(stream, kclass, count, M, N, K, bytes * (uint64_t)count,
+                       2ull * (uint64_t)M * (uint64_t)N * (uint64_t)K * (uint64_t)count);
+    if (op == TT_OP_FWD) return obf ? launch_gather_a<0, true>(p, count, s) : launch_gather_a<0, false>(p, count, s);
+    if (op == TT_OP_DGRAD) return obf ? launch_gather_a<1, true>(p, count, s) : launch_gather_a<1, false>(p, count, s);
+    return obf ? launch_wgrad<true>(p, count, s) : launch_wgrad<false>(p, count, s);
+}
+
+} // namespace tt

@@ -85,11 +85,12 @@ struct OutputPlan {
     uint8_t zl[TT_MAX_K];
 };
 
-inline tt_status plan_output(const uint8_t *forms, const tt_tiling &tZ, void *const *Z, int64_t rows, int64_t cols, int k,
-                             int dtype, int act, Workspace &ws, OutputPlan *op)
+// zl: the temporary outputs' grid letters per cut (TT_R, TT_C or kRed) in the coordinates of the rows x cols matrix
+inline tt_status plan_output_letters(const uint8_t *zl, const tt_tiling &tZ, void *const *Z, int64_t rows, int64_t cols,
+                                     int k, int dtype, int act, Workspace &ws, OutputPlan *op)
 {
     Grid gz, gt;
-    aligned_tilings(forms, k, nullptr, nullptr, op->zl);
+    for (int j = 0; j < k; ++j) op->zl[j] = zl[j];
     if (!make_grid(op->zl, k, rows, cols, &gz) || !make_grid(tZ.cut, k, rows, cols, &gt)) return TT_EINFEASIBLE;
     const int n = 1 << k;
     const size_t esz = dtype == TT_BF16 ? 2 : 4;
@@ -110,6 +111,14 @@ inline tt_status plan_output(const uint8_t *forms, const tt_tiling &tZ, void *co
     const size_t bytes = (size_t)gz.srows * (size_t)gz.scols * (red ? 4 : esz);
     for (int s = 0; s < n; ++s) op->gemm_out[s] = ws.take(bytes);
     return ws.overflow ? TT_EWORKSPACE : TT_OK;
+}
+
+inline tt_status plan_output(const uint8_t *forms, const tt_tiling &tZ, void *const *Z, int64_t rows, int64_t cols, int k,
+                             int dtype, int act, Workspace &ws, OutputPlan *op)
+{
+    uint8_t zl[TT_MAX_K];
+    aligned_tilings(forms, k, nullptr, nullptr, zl);
+    return plan_output_letters(zl, tZ, Z, rows, cols, k, dtype, act, ws, op);
 }
 
 inline tt_status finish_output(const OutputPlan &op, const tt_tiling &tZ, void *const *Z, int64_t rows, int64_t cols, int k,

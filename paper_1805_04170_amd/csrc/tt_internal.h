@@ -110,6 +110,13 @@ tt_status launch_reduce(void *const *dst, const uint8_t *B, int out_dtype, const
 tt_status launch_gemm(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
                       int64_t K, int trans_a, int trans_b, int in_dtype, int out_dtype, int act, void *stream);
 
+// Convolution shard products (conv.hip).  op TT_OP_FWD: A = X shards, B = filter shards, C = Y shards;
+// TT_OP_DGRAD: A = dY, B = filters, C = dX;  TT_OP_WGRAD: A = dY, B = X, C = dW.  Ns images, Cs input channels and
+// Ks output channels per shard; bf16 operands.
+tt_status launch_conv(int op, int count, const void *const *A, const void *const *B, void *const *C, int64_t Ns,
+                      int64_t Cs, int64_t Ks, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad, int out_dtype,
+                      int act, void *stream);
+
 // ---- optional kernel timing (profile.cpp).  A scope object brackets one launch with two events when the calling
 // thread has recording switched on; otherwise it does nothing.
 struct ProfileScope {

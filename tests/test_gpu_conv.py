@@ -1,0 +1,171 @@
+"""Parity of the convolution execute calls (implicit GEMM) with the fp64 oracle (textbook definition in
+oracle/layers.py, pinned against torch's CPU conv2d in the non-GPU tests).
+Storage: activations NHWC seen as (N*H*W) x C matrices, filters [K][R][S][C] seen as (K*R*S) x C."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import paper_1805_04170_amd as tt
+from oracle import execute as ex
+from oracle import layers as ly
+from oracle import tiling as tl
+from synthetic import CONFIGS, bf16_bits_to_f64, normal_f32, to_bf16_bits
+
+from gpu_util import DEV, alloc_shards, np_to_dev, shards_to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def act_matrix(T):            # logical NCHW -> (N*H*W) x C
+    n, c, h, w = T.shape
+    return np.ascontiguousarray(T.transpose(0, 2, 3, 1)).reshape(n * h * w, c)
+
+
+def act_from_matrix(Mx, n, c, h, w):
+    return Mx.reshape(n, h, w, c).transpose(0, 3, 1, 2)
+
+
+def filt_matrix(Wt):          # logical K C R S -> (K*R*S) x C
+    k, c, r, s = Wt.shape
+    return np.ascontiguousarray(Wt.transpose(0, 2, 3, 1)).reshape(k * r * s, c)
+
+
+def filt_from_matrix(Mx, k, c, r, s):
+    return Mx.reshape(k, r, s, c).transpose(0, 3, 1, 2)
+
+
+def up(Mx, t):
+    return [np_to_dev(s, True) for s in tl.tile(Mx, t)]
+
+
+def ws(nbytes):
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=DEV)
+
+
+def close(got, want, mag, what):
+    tol = 1e-2 * mag + 2.0 ** -8 * np.abs(want)
+    err = np.abs(got - want)
+    assert np.all(np.isfinite(got)), what
+    assert np.all(err <= tol + 1e-30), (what, float(err.max()), float((err / (tol + 1e-30)).max()))
+
+
+def conv_mag_fwd(X, W, pad):
+    return ly.conv_forward(np.abs(X), np.abs(W), pad)
+
+
+def run_conv(N, C, K, H, Wd, R, S, pad, k, relu, tX, tW, tY, tdY, tdX, f_fwd, f_dg, f_wg, seed, with_dx=True):
+    lay = tt.layer("conv", "relu" if relu else "none", C, K, H=H, W=Wd, R=R, S=S, pad=pad)
+    P, Q = H + 2 * pad - R + 1, Wd + 2 * pad - S + 1
+    Xb = to_bf16_bits(normal_f32(seed, 0, (N, C, H, Wd), 1.0))
+    Wb = to_bf16_bits(normal_f32(seed, 1, (K, C, R, S), 0.05))
+    dYb = to_bf16_bits(normal_f32(seed, 2, (N, K, P, Q), 1.0))
+    X, W, dY = bf16_bits_to_f64(Xb), bf16_bits_to_f64(Wb), bf16_bits_to_f64(dYb)
+    tWs = ex.transpose_tiling(tW)                      # letters on the filter storage matrix
+    Xs, Ws_, dYs = up(act_matrix(Xb), tX), up(filt_matrix(Wb), tWs), up(act_matrix(dYb), tdY)
+    Ys = alloc_shards(N * P * Q, K, tY, torch.bfloat16, fill=float("nan"))
+    nb = tt.tt_conv_workspace_bytes(lay, N, k, "bf16", tt.TT_OP_FWD, tX, tW, tY, forms_a=f_fwd)
+    tt.tt_conv_forward(lay, N, k, "bf16", tX, tW, tY, f_fwd, Xs, Ws_, Ys, ws(nb))
+    torch.cuda.synchronize()
+    Ym = bf16_bits_to_f64(tl.untile(shards_to_np(Ys), tY, N * P * Q, K))
+    Yg = act_from_matrix(Ym, N, K, P, Q)
+    want = ly.conv_forward(X, W, pad)
+    if relu:
+        want = np.maximum(want, 0)
+    close(Yg, want, conv_mag_fwd(X, W, pad), ("fwd", tX, tW, tY, f_fwd))
+    dXs = alloc_shards(N * H * Wd, C, tdX, torch.bfloat16, fill=float("nan")) if with_dx else None
+    dWs = alloc_shards(K * R * S, C, tWs, torch.bfloat16, fill=float("nan"))
+    nb = tt.tt_conv_workspace_bytes(lay, N, k, "bf16", tt.TT_OP_DGRAD, tX, tW, tY, tdY, tdX, f_dg, f_wg, with_dx)
+    tt.tt_conv_backward(lay, N, k, "bf16", tX, tW, tY, tdY, tdX, f_dg, f_wg, Xs, Ws_, Ys, dYs, dXs, dWs, ws(nb))
+    torch.cuda.synchronize()
+    G = dY * (Yg > 0) if relu else dY
+    if with_dx:
+        dXg = act_from_matrix(bf16_bits_to_f64(tl.untile(shards_to_np(dXs), tdX, N * H * Wd, C)), N, C, H, Wd)
+        close(dXg, ly.conv_dgrad(G, W, pad, H, Wd), ly.conv_dgrad(np.abs(G), np.abs(W), pad, H, Wd), ("dgrad", tdY, tW, tdX, f_dg))
+    dWg = filt_from_matrix(bf16_bits_to_f64(tl.untile(shards_to_np(dWs), tWs, K * R * S, C)), K, C, R, S)
+    close(dWg, ly.conv_wgrad(X, G, pad, R, S), ly.conv_wgrad(np.abs(X), np.abs(G), pad, R, S), ("wgrad", tX, tdY, tW, f_wg))
+
+
+def test_single_shard_and_one_cut():
+    run_conv(2, 16, 24, 6, 5, 3, 3, 1, 0, False, "", "", "", "", "", "", "", "", 100)
+    # data parallel (batch split), model parallel on output channels, on input channels
+    run_conv(4, 16, 32, 6, 6, 3, 3, 1, 1, True, "R", "r", "R", "R", "R", "1", "1", "3", 101)
+    run_conv(4, 16, 32, 6, 6, 3, 3, 1, 1, True, "r", "C", "C", "C", "r", "2", "3", "2", 102)
+    run_conv(4, 16, 32, 6, 6, 3, 3, 1, 1, False, "C", "R", "r", "r", "C", "3", "2", "1", 103)
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_every_form_sequence_two_cuts(relu):
+    for f in ["".join(p) for p in itertools.product("123", repeat=2)]:
+        run_conv(4, 32, 32, 5, 6, 3, 3, 1, 2, relu, "RC", "Cr", "rR", "CR", "RR", f, f, f, 110)
+
+
+def test_random_stored_tilings_default_forms():
+    rng = np.random.default_rng(6)
+    ts = tl.all_tilings(2)
+    for i in range(12):
+        tX, tW, tY, tdY, tdX = (ts[j] for j in rng.integers(0, 9, 5))
+        run_conv(4, 32, 64, 4, 4, 3, 3, 1, 2, bool(i % 2), tX, tW, tY, tdY, tdX, None, None, None, 120 + i)
+
+
+def test_other_filter_shapes():
+    run_conv(4, 64, 32, 7, 7, 1, 1, 0, 2, True, "RR", "rr", "RR", "RR", "RR", None, None, None, 130)     # 1x1
+    run_conv(2, 16, 16, 9, 8, 5, 5, 2, 1, False, "R", "r", "R", "R", "R", None, None, None, 131)          # 5x5 "same"
+    run_conv(2, 16, 16, 8, 8, 3, 3, 0, 1, False, "C", "R", "r", "r", "C", None, None, None, 132, False)   # no padding, no dX
+    run_conv(8, 8, 8, 3, 3, 3, 3, 1, 3, True, "RRR", "rrr", "RRR", "RRR", "RRR", "111", "111", "333", 133)  # 8 channels: K tail
+
+
+def test_refusals():
+    lay = tt.layer("conv", "none", 12, 16, H=4, W=4, R=3, S=3, pad=1)       # 12 channels: no 16-byte channel vectors
+    x = [torch.zeros(4096, dtype=torch.bfloat16, device=DEV)]
+    with pytest.raises(tt.TilingError) as e:
+        tt.tt_conv_forward(lay, 2, 0, "bf16", "", "", "", "", x, x, x)
+    assert e.value.status == 3
+    lay = tt.layer("conv", "none", 16, 16, H=4, W=4, R=3, S=3, pad=1)
+    with pytest.raises(tt.TilingError) as e:                                  # fp32 convolutions are not built
+        tt.tt_conv_forward(lay, 2, 0, "f32", "", "", "", "", x, x, x)
+    assert e.value.status == 3
+    with pytest.raises(tt.TilingError) as e:                                  # batch 2 cannot be cut twice
+        tt.tt_conv_forward(lay, 2, 2, "bf16", "RR", "rr", "RR", "11", x * 4, x * 4, x * 4)
+    assert e.value.status == 2
+
+
+@pytest.mark.parametrize("split", ["planner", "batch", "out_channel"])
+def test_config_vgg_conv4_full_size_sampled(split):
+    cfg = CONFIGS["vgg16_conv4"]
+    N, C, K, H, Wd, R, S, pad, k = cfg.N, cfg.C, cfg.K, cfg.H, cfg.W, cfg.R, cfg.S, cfg.pad, cfg.k
+    P, Q = cfg.P, cfg.Q
+    lay = tt.layer("conv", "none", C, K, H=H, W=Wd, R=R, S=S, pad=pad)
+    if split == "planner":
+        p = tt.tt_plan_chain([lay], N, k)
+        tX, tY, tW, tdY, tdX = p.x()[0], p.x()[1], p.w()[0], p.g()[1], p.g()[0]
+        f = [p.forms(1, o) for o in range(3)]
+    elif split == "batch":
+        tX = tY = tdY = tdX = "RRR"; tW = "rrr"; f = ["111", "111", "333"]
+    else:
+        tX = tdX = "rrr"; tY = tdY = "CCC"; tW = "CCC"; f = ["222", "333", "222"]
+    Xb, Wb, dYb = cfg.x(), cfg.weight(), cfg.grad_out()
+    tWs = ex.transpose_tiling(tW)
+    Xs, Ws_, dYs = up(act_matrix(Xb), tX), up(filt_matrix(Wb), tWs), up(act_matrix(dYb), tdY)
+    Ys = alloc_shards(N * P * Q, K, tY, torch.bfloat16, fill=float("nan"))
+    dXs = alloc_shards(N * H * Wd, C, tdX, torch.bfloat16, fill=float("nan"))
+    dWs = alloc_shards(K * R * S, C, tWs, torch.bfloat16, fill=float("nan"))
+    nb = max(tt.tt_conv_workspace_bytes(lay, N, k, "bf16", tt.TT_OP_FWD, tX, tW, tY, forms_a=f[0]),
+             tt.tt_conv_workspace_bytes(lay, N, k, "bf16", tt.TT_OP_DGRAD, tX, tW, tY, tdY, tdX, f[1], f[2]))
+    w = ws(nb)
+    tt.tt_conv_forward(lay, N, k, "bf16", tX, tW, tY, f[0], Xs, Ws_, Ys, w)
+    tt.tt_conv_backward(lay, N, k, "bf16", tX, tW, tY, tdY, tdX, f[1], f[2], Xs, Ws_, Ys, dYs, dXs, dWs, w)
+    torch.cuda.synchronize()
+    X, W, dY = bf16_bits_to_f64(Xb), bf16_bits_to_f64(Wb), bf16_bits_to_f64(dYb)
+    Yg = act_from_matrix(bf16_bits_to_f64(tl.untile(shards_to_np(Ys), tY, N * P * Q, K)), N, K, P, Q)
+    dXg = act_from_matrix(bf16_bits_to_f64(tl.untile(shards_to_np(dXs), tdX, N * H * Wd, C)), N, C, H, Wd)
+    dWg = filt_from_matrix(bf16_bits_to_f64(tl.untile(shards_to_np(dWs), tWs, K * R * S, C)), K, C, R, S)
+    for n in (0, 37, 63):                                  # whole images, one per shard region
+        close(Yg[n:n + 1], ly.conv_forward(X[n:n + 1], W, pad), conv_mag_fwd(X[n:n + 1], W, pad), ("fwd", n))
+        close(dXg[n:n + 1], ly.conv_dgrad(dY[n:n + 1], W, pad, H, Wd),
+              ly.conv_dgrad(np.abs(dY[n:n + 1]), np.abs(W), pad, H, Wd), ("dgrad", n))
+    for k0, c0 in ((0, 0), (250, 500), (504, 8)):          # 8 x 8 blocks of filters, all taps, summed over the whole batch
+        want = ly.conv_wgrad(X[:, c0:c0 + 8], dY[:, k0:k0 + 8], pad, R, S)
+        mag = ly.conv_wgrad(np.abs(X[:, c0:c0 + 8]), np.abs(dY[:, k0:k0 + 8]), pad, R, S)
+        close(dWg[k0:k0 + 8, c0:c0 + 8], want, mag, ("wgrad", k0, c0))
