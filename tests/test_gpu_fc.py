@@ -193,3 +193,39 @@ def test_config_tiny_mlp_fp32_planned_and_recursive():
 def test_config_fc_stacks_full_size(name):
     cfg = CONFIGS[name]
     run_chain(cfg, plan_for(cfg), check_rows=np.array([0, 1, 31, 32, 100, 255]))
+
+
+class ForcedPlan:
+    """A fixed graph tiling with the accessors of a planner result."""
+
+    def __init__(self, L, tx, tg, tw, forms):
+        self._x, self._g, self._w, self._f = [tx] * (L + 1), [tg] * (L + 1), [tw] * L, forms
+
+    def x(self):
+        return self._x
+
+    def g(self):
+        return self._g
+
+    def w(self):
+        return self._w
+
+    def forms(self, layer_index, op):
+        return self._f[op]
+
+
+def test_config_wide_mlp_full_size_forced_tiling():
+    # 8 x (8192 -> 8192), batch 512, 16 shards; every tensor stored as a 4 x 4 grid (RRCC); the forward and dgrad
+    # products split the reduction dimension twice (4-way partial-sum reduce) and need a real conversion of their
+    # first operand; the weight gradient lands directly in the stored grid.
+    cfg = CONFIGS["wide_mlp"]
+    plan = ForcedPlan(cfg.n_layers, "RRCC", "RRCC", "RRCC", ["3322", "2233", "1122"])
+    run_chain(cfg, plan, check_rows=np.array([0, 127, 128, 300, 511]))
+
+
+def test_wide_mlp_shapes_sixteen_way_reduce():
+    # the variant with all four cuts on the reduction dimension (16 partial sums), at reduced width
+    from synthetic.configs import FcChain
+    cfg = FcChain("wide_small", 128, (1024, 1024, 1024), 4, "bf16", 0.01, 2005)
+    plan = ForcedPlan(cfg.n_layers, "CCCC", "rrrr", "RRRR", ["3333", "2222", "1111"])
+    run_chain(cfg, plan)
