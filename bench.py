@@ -32,7 +32,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "alexnet_fc", "wide_mlp", "tiny_mlp"])
+    ap.add_argument("--workload", default="vgg16_fc",
+                    choices=["vgg16_fc", "alexnet_fc", "wide_mlp", "tiny_mlp", "vgg16_conv4"])
+    ap.add_argument("--conv-split", default="planner", choices=["planner", "batch", "out_channel"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
     return ap.parse_args()
@@ -105,6 +107,66 @@ class Chain:
                               self.W[l - 1], self.x[l], self.g[l], self.g[l - 1], self.dW[l - 1], self.ws)
 
 
+class ConvLayerBench:
+    """Device state of one convolution layer (forward + backward) under a tiling."""
+
+    def __init__(self, cfg, tt, torch, split):
+        import numpy as np
+        self.cfg, self.tt = cfg, tt
+        N, C, K, k = cfg.N, cfg.C, cfg.K, cfg.k
+        self.lay = tt.layer("conv", "none", C, K, H=cfg.H, W=cfg.W, R=cfg.R, S=cfg.S, pad=cfg.pad)
+        if split == "planner":
+            p = tt.tt_plan_chain([self.lay], N, k)
+            self.t = dict(X=p.x()[0], Y=p.x()[1], W=p.w()[0], dY=p.g()[1], dX=p.g()[0])
+            self.f = [p.forms(1, o) for o in range(3)]
+            self.plan_cost = p.cost
+        elif split == "batch":
+            self.t = dict(X="R" * k, Y="R" * k, W="r" * k, dY="R" * k, dX="R" * k)
+            self.f = ["1" * k, "1" * k, "3" * k]
+            self.plan_cost = None
+        else:
+            self.t = dict(X="r" * k, Y="C" * k, W="C" * k, dY="C" * k, dX="r" * k)
+            self.f = ["2" * k, "3" * k, "2" * k]
+            self.plan_cost = None
+        tWs = self.t["W"].translate(str.maketrans("RC", "CR"))    # letters on the (K*R*S) x C storage matrix
+        self.tWs = tWs
+        dev = "cuda:0"
+
+        def upload(M2, t):
+            rows, cols = M2.shape
+            sr, sc = tt.tt_shard_shape(rows, cols, t)
+            out = []
+            for s in range(1 << k):
+                rb, cb = block_of(t, s)
+                piece = np.ascontiguousarray(M2[rb * sr:(rb + 1) * sr, cb * sc:(cb + 1) * sc])
+                out.append(torch.from_numpy(piece.view(np.int16)).to(dev).view(torch.bfloat16))
+            return out
+
+        def empty(rows, cols, t):
+            sr, sc = tt.tt_shard_shape(rows, cols, t)
+            return [torch.zeros((sr, sc), dtype=torch.bfloat16, device=dev) for _ in range(1 << k)]
+
+        x = cfg.x().transpose(0, 2, 3, 1).reshape(N * cfg.H * cfg.W, C)
+        w = cfg.weight().transpose(0, 2, 3, 1).reshape(K * cfg.R * cfg.S, C)
+        g = cfg.grad_out().transpose(0, 2, 3, 1).reshape(N * cfg.P * cfg.Q, K)
+        self.X, self.Wt, self.dY = upload(x, self.t["X"]), upload(w, tWs), upload(g, self.t["dY"])
+        self.Y = empty(N * cfg.P * cfg.Q, K, self.t["Y"])
+        self.dX = empty(N * cfg.H * cfg.W, C, self.t["dX"])
+        self.dW = empty(K * cfg.R * cfg.S, C, tWs)
+        t = self.t
+        need = max(256, tt.tt_conv_workspace_bytes(self.lay, N, k, "bf16", tt.TT_OP_FWD, t["X"], t["W"], t["Y"], forms_a=self.f[0]),
+                   tt.tt_conv_workspace_bytes(self.lay, N, k, "bf16", tt.TT_OP_DGRAD, t["X"], t["W"], t["Y"], t["dY"], t["dX"],
+                                              self.f[1], self.f[2]))
+        self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        self.tx, self.tg, self.tw = [t["X"], t["Y"]], [t["dX"], t["dY"]], [t["W"]]
+
+    def step(self):
+        tt, t, c = self.tt, self.t, self.cfg
+        tt.tt_conv_forward(self.lay, c.N, c.k, "bf16", t["X"], t["W"], t["Y"], self.f[0], self.X, self.Wt, self.Y, self.ws)
+        tt.tt_conv_backward(self.lay, c.N, c.k, "bf16", t["X"], t["W"], t["Y"], t["dY"], t["dX"], self.f[1], self.f[2],
+                            self.X, self.Wt, self.Y, self.dY, self.dX, self.dW, self.ws)
+
+
 def block_of(t, s):
     """(row block, column block) of shard s under tiling string t (host-side placement of synthetic inputs)."""
     k = len(t)
@@ -140,6 +202,19 @@ def cpu_baseline(cfg):
     except Exception:
         cores = os.cpu_count() or 1
     conv = (lambda a: bf16_bits_to_f64(a)) if cfg.dtype == "bf16" else (lambda a: a.astype(np.float64))
+    if not hasattr(cfg, "widths"):
+        # convolution: a bounded sample (4 of the N images) of forward + dgrad + wgrad
+        ns = 4
+        X, Wt, G = conv(cfg.x()[:ns]), conv(cfg.weight()), conv(cfg.grad_out()[:ns])
+        t0 = time.perf_counter()
+        ly.conv_forward(X, Wt, cfg.pad)
+        ly.conv_dgrad(G, Wt, cfg.pad, cfg.H, cfg.W)
+        ly.conv_wgrad(X, G, cfg.pad, cfg.R, cfg.S)
+        dt = time.perf_counter() - t0
+        fl = cfg.flops() * ns / cfg.N
+        return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+                "sample": "fwd+dgrad+wgrad of %d of the %d images of %s in fp64 numpy (%.1f GFLOP, %.2f s)" % (
+                    ns, cfg.N, cfg.name, fl / 1e9, dt)}
     x = [conv(cfg.x0())]
     Ws = [conv(cfg.weight(l)) for l in range(1, cfg.n_layers + 1)]
     g = conv(cfg.grad_out())
@@ -168,7 +243,16 @@ def main():
     tt.binding.lib()
     cfg = CONFIGS[args.workload]
     torch.cuda.set_device(0)
-    chain = Chain(cfg, tt, torch)
+    is_conv = not hasattr(cfg, "widths")
+    if is_conv:
+        chain = ConvLayerBench(cfg, tt, torch, args.conv_split)
+    elif args.workload == "wide_mlp":
+        # forced tiling: every tensor stored as a 4 x 4 grid; forward / dgrad split the reduction dimension twice
+        L = cfg.n_layers
+        chain = Chain(cfg, tt, torch, tilings=(["RRCC"] * (L + 1), ["RRCC"] * (L + 1), ["RRCC"] * L,
+                                               [["3322", "2233", "1122"]] * L))
+    else:
+        chain = Chain(cfg, tt, torch)
     K, W = args.steps, args.warmup
 
     for _ in range(max(W, 1)):
@@ -200,8 +284,9 @@ def main():
         chain.step()
     records = tt.tt_profile_end()
     agg = aggregate(records)
-    gemm_ms = sum(a["ms"] for a in agg if a["kernel"].startswith("gemm")) / K
-    conv_ms = sum(a["ms"] for a in agg if not a["kernel"].startswith("gemm")) / K
+    is_product = lambda a: a["kernel"].startswith("gemm") or a["kernel"].startswith("conv_")
+    gemm_ms = sum(a["ms"] for a in agg if is_product(a)) / K
+    conv_ms = sum(a["ms"] for a in agg if not is_product(a)) / K
     dom = agg[0]
     dom_ms = dom["ms"] / dom["launches"]
     key = "%s:%s" % (args.workload, dom["kernel"])
@@ -220,7 +305,7 @@ def main():
                 "GBps": a["bytes"] / (a["ms"] / a["launches"] * 1e-3) / 1e9} for a in agg]
 
     # retile headline: the largest tensor of the workload between two non-replicated tilings
-    rows, cols = cfg.widths[0], cfg.widths[1]
+    rows, cols = (cfg.widths[0], cfg.widths[1]) if not is_conv else (cfg.K * cfg.R * cfg.S, cfg.C)
     ka = cfg.k
     A, B = "R" * ka, "C" * ka
     esz = 2 if cfg.dtype == "bf16" else 4
@@ -246,8 +331,11 @@ def main():
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": "%s: batch %d, %s, k=%d (%d shards), planner EXACT tiling" % (
-            cfg.name, cfg.batch, "->".join(str(w) for w in cfg.widths), cfg.k, 1 << cfg.k),
+        "config": {"workload": ("%s: batch %d, %s, k=%d (%d shards), %s tiling" % (
+            cfg.name, cfg.batch, "->".join(str(w) for w in cfg.widths), cfg.k, 1 << cfg.k,
+            "planner EXACT" if chain.plan_cost is not None else "forced RRCC grid")) if not is_conv else (
+            "%s: N=%d C=%d K=%d %dx%d %dx%d pad %d, k=%d (%d shards), %s split" % (
+                cfg.name, cfg.N, cfg.C, cfg.K, cfg.H, cfg.W, cfg.R, cfg.S, cfg.pad, cfg.k, 1 << cfg.k, args.conv_split)),
             "tiling_x": chain.tx, "tiling_g": chain.tg, "tiling_w": chain.tw, "plan_cost_elems": chain.plan_cost,
             "timed": "hip graph replay" if graph is not None else "eager launches"},
         "frac_mfma_peak": tflops / PEAK_BF16_TFLOPS,

@@ -45,13 +45,18 @@ __device__ __forceinline__ u32x4 load16(const char *base, int32_t elem_off)
 
 // A operand of forward and dgrad: rows are output pixels (n, oy, ox), k = (tap, channel) with the channel contiguous.
 // in_y = oy + off + sgn * r, in_x = ox + off + sgn * s   (forward: off = -pad, sgn = +1; dgrad: off = +pad, sgn = -1)
-template <int SLOTS> struct GatherKC {
+template <int SLOTS, bool ONE_TAP> struct GatherKC {
     static constexpr bool KC = true;
+    static constexpr bool kFence = false;
     const char *base;
     int IH, IW, OH, OW, R, S, off, sgn, Ch; // Ch: channels per pixel of the source
     int rows, K;
     int32_t pix[SLOTS];   // element offset of source pixel (n, oy + off, ox + off), may be negative
     uint32_t taps[SLOTS]; // bit t set: tap t reads inside the image
+    // per K tile, when a tile lies inside one tap (Ch a multiple of the tile depth): the tap and the offset of the
+    // tile's first channel relative to pix[]
+    int tile_k0, tile_tap;
+    int32_t tile_delta;
     __device__ __forceinline__ void init(int slot, int row)
     {
         row = row < rows ? row : rows - 1;
@@ -66,8 +71,20 @@ template <int SLOTS> struct GatherKC {
             }
         taps[slot] = m;
     }
+    __device__ __forceinline__ void begin_tile(int k0)
+    {
+        tile_k0 = k0;
+        const int kk = k0 < K ? k0 : 0;
+        tile_tap = kk / Ch;
+        const int r = tile_tap / S, s = tile_tap - r * S;
+        tile_delta = sgn * (r * IW + s) * Ch + (kk - tile_tap * Ch);
+    }
     __device__ __forceinline__ u32x4 load_masked(int slot, int k) const
     {
+        if constexpr (ONE_TAP) { // a K tile never straddles two taps (Ch is a multiple of the tile depth)
+            const bool ok = k < K && ((taps[slot] >> tile_tap) & 1u);
+            return and_mask(load16(base, ok ? pix[slot] + tile_delta + (k - tile_k0) : 0), ok);
+        }
         const int tap = k / Ch, c = k - tap * Ch;
         const int r = tap / S, s = tap - r * S;
         const bool ok = k < K && ((taps[slot] >> tap) & 1u);
@@ -80,23 +97,30 @@ template <int SLOTS> struct GatherKC {
 // B operand of dgrad: filters [Ks][R][S][Cs] read as rows c (contiguous), k = (tap, ko)
 template <int SLOTS> struct FilterRC {
     static constexpr bool KC = false;
+    static constexpr bool kFence = false;
     const char *base;
     int RS, Cs, Ks, rows, K;
     int32_t c0[SLOTS];
     __device__ __forceinline__ void init(int slot, int row) { c0[slot] = row < rows ? row : rows - 8; }
-    __device__ __forceinline__ u32x4 load_masked(int slot, int k) const
+    __device__ __forceinline__ void begin_tile(int) {}
+    template <bool KMASK> __device__ __forceinline__ void load4(int slot, int k, u32x4 *out) const
     {
-        const bool ok = k < K;
-        const int kk = ok ? k : K - 1;
-        const int tap = kk / Ks, ko = kk - tap * Ks;
-        return and_mask(load16(base, (ko * RS + tap) * Cs + c0[slot]), ok);
+        // four consecutive k: one division, then step (ko wraps into the next tap)
+        const int kf = k < K ? k : K - 1;
+        int tap = kf / Ks, ko = kf - tap * Ks;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const bool ok = k + q < K;
+            out[q] = and_mask(load16(base, (ko * RS + tap) * Cs + c0[slot]), ok);
+            if (k + q + 1 < K) { ++ko; if (ko == Ks) { ko = 0; ++tap; } }
+        }
     }
-    __device__ __forceinline__ u32x4 load(int slot, int k) const { return load_masked(slot, k); }
 };
 
 // B operand of wgrad: rows are (tap, c) with c contiguous, k = (n, p, q) walks the output pixels
 template <int SLOTS> struct GatherRC {
     static constexpr bool KC = false;
+    static constexpr bool kFence = false;
     const char *base;
     int H, W, P, Q, S, pad, Cs, rows, K;
     int32_t dy[SLOTS], dx[SLOTS], c0[SLOTS];
@@ -109,17 +133,22 @@ template <int SLOTS> struct GatherRC {
         dy[slot] = r - pad;
         dx[slot] = tap - r * S - pad;
     }
-    __device__ __forceinline__ u32x4 load_masked(int slot, int k) const
+    __device__ __forceinline__ void begin_tile(int) {}
+    template <bool KMASK> __device__ __forceinline__ void load4(int slot, int k, u32x4 *out) const
     {
-        const int kk = k < K ? k : K - 1;
-        const int n = kk / (P * Q), rem = kk - n * (P * Q);
-        const int p = rem / Q, q = rem - p * Q;
-        const int iy = p + dy[slot], ix = q + dx[slot];
-        const bool ok = k < K && iy >= 0 && iy < H && ix >= 0 && ix < W;
-        const int32_t o = ((n * H + iy) * W + ix) * Cs + c0[slot];
-        return and_mask(load16(base, ok ? o : 0), ok);
+        const int kf = k < K ? k : K - 1;
+        int n = kf / (P * Q);
+        const int rem = kf - n * (P * Q);
+        int p = rem / Q, q = rem - p * Q;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int iy = p + dy[slot], ix = q + dx[slot];
+            const bool ok = k + j < K && iy >= 0 && iy < H && ix >= 0 && ix < W;
+            const int32_t o = ((n * H + iy) * W + ix) * Cs + c0[slot];
+            out[j] = and_mask(load16(base, ok ? o : 0), ok);
+            if (++q == Q) { q = 0; if (++p == P) { p = 0; ++n; } }
+        }
     }
-    __device__ __forceinline__ u32x4 load(int slot, int k) const { return load_masked(slot, k); }
 };
 
 struct TileId { int shard, m0, n0; };
@@ -137,14 +166,14 @@ template <int BM, int BN> __device__ __forceinline__ bool tile_of(const ConvPara
 }
 
 // OP 0: forward, 1: dgrad
-template <int BM, int BN, int DEPTH, bool KMASK, int OP, bool OUT_BF16>
+template <int BM, int BN, int DEPTH, bool KMASK, int OP, bool OUT_BF16, bool ONE_TAP>
 __global__ __launch_bounds__(kThreads) void conv_gather_a_kernel(const ConvParams p)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     TileId t;
     if (!tile_of<BM, BN>(p, &t)) return;
     const ConvGeom &g = p.g;
-    GatherKC<core::Slots<BM, true>::value> la;
+    GatherKC<core::Slots<BM, true>::value, ONE_TAP> la;
     la.base = reinterpret_cast<const char *>(p.A[t.shard]);
     la.R = g.R; la.S = g.S;
     la.rows = p.M; la.K = p.K;
@@ -193,17 +222,24 @@ template <typename Kern> tt_status launch(Kern kern, size_t smem, ConvParams &p,
     return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
 }
 
-template <int OP, bool OUT_BF16> tt_status launch_gather_a(ConvParams &p, int count, hipStream_t s)
+template <int OP, bool OUT_BF16, bool ONE_TAP> tt_status launch_gather_a_t(ConvParams &p, int count, hipStream_t s)
 {
     const bool kmask = p.K % core::BK != 0;
     if (p.M > 128) {
         constexpr size_t sm = core::smem_bytes<256, 128>();
-        return kmask ? launch(conv_gather_a_kernel<256, 128, 2, true, OP, OUT_BF16>, sm, p, 256, 128, count, s)
-                     : launch(conv_gather_a_kernel<256, 128, 2, false, OP, OUT_BF16>, sm, p, 256, 128, count, s);
+        return kmask ? launch(conv_gather_a_kernel<256, 128, 2, true, OP, OUT_BF16, ONE_TAP>, sm, p, 256, 128, count, s)
+                     : launch(conv_gather_a_kernel<256, 128, 2, false, OP, OUT_BF16, ONE_TAP>, sm, p, 256, 128, count, s);
     }
     constexpr size_t sm = core::smem_bytes<128, 128>();
-    return kmask ? launch(conv_gather_a_kernel<128, 128, 1, true, OP, OUT_BF16>, sm, p, 128, 128, count, s)
-                 : launch(conv_gather_a_kernel<128, 128, 1, false, OP, OUT_BF16>, sm, p, 128, 128, count, s);
+    return kmask ? launch(conv_gather_a_kernel<128, 128, 1, true, OP, OUT_BF16, ONE_TAP>, sm, p, 128, 128, count, s)
+                 : launch(conv_gather_a_kernel<128, 128, 1, false, OP, OUT_BF16, ONE_TAP>, sm, p, 128, 128, count, s);
+}
+
+template <int OP, bool OUT_BF16> tt_status launch_gather_a(ConvParams &p, int count, hipStream_t s)
+{
+    const int ch = OP == 0 ? p.g.Cs : p.g.Ks; // channels per pixel of the gathered tensor
+    return ch % core::BK == 0 ? launch_gather_a_t<OP, OUT_BF16, true>(p, count, s)
+                              : launch_gather_a_t<OP, OUT_BF16, false>(p, count, s);
 }
 
 template <bool OUT_BF16> tt_status launch_wgrad(ConvParams &p, int count, hipStream_t s)

@@ -145,17 +145,22 @@ tt_status launch_mfma_cfg(GemmParams &p, int count, hipStream_t s)
 // Tile choice.  Tall 256 x 128 tiles stream each weight element once per 256 batch rows and suit long K loops;
 // 128 x 128 tiles leave room for two workgroups per CU, which hides the prologue / epilogue of short K loops
 // (weight gradients: K = batch).  TT_GEMM_TILE=0|1 overrides (tuning aid).
-int pick_tile(int64_t M, int64_t N, int64_t K)
+// 256 x 256 tiles (128 x 128 per wave) halve the LDS traffic per MFMA; used when the launch still has enough tiles to
+// cover the 256 CUs.
+int pick_tile(int64_t M, int64_t N, int64_t K, int count)
 {
     static const int forced = [] { const char *e = std::getenv("TT_GEMM_TILE"); return e ? std::atoi(e) : -1; }();
-    if (forced == 0 || forced == 1) return forced;
-    (void)N;
+    if (forced >= 0 && forced <= 2) return forced;
+    const int64_t big = ((M + 255) / 256) * ((N + 255) / 256) * count;
+    if (M > 128 && N > 128 && K >= 512 && big >= 200) return 2;
     return (M > 128 && K >= 1024) ? 0 : 1;
 }
 
 template <bool KMASK, bool A_KC, bool B_KC, bool OUT_BF16, bool VEC> tt_status launch_mfma_tile(GemmParams &p, int count, hipStream_t s)
 {
-    if (pick_tile(p.M, p.N, p.K) == 0) return launch_mfma_cfg<256, 128, 2, 2, 2, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
+    const int tile = pick_tile(p.M, p.N, p.K, count);
+    if (tile == 2) return launch_mfma_cfg<256, 256, 2, 2, 1, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
+    if (tile == 0) return launch_mfma_cfg<256, 128, 2, 2, 2, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
     return launch_mfma_cfg<128, 128, 2, 2, 1, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
 }
 

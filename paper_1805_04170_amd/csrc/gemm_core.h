@@ -45,6 +45,8 @@ __device__ __forceinline__ u32x4 zero4()
 //                               false = rows are contiguous in memory, K strides
 //   init(slot, row)           : KC: bind the slot to one row;  !KC: bind the slot to 8 consecutive rows starting at row
 //   load(slot, k)             : KC: 8 consecutive k starting at k (multiple of 8);  !KC: the slot's 8 rows at this k
+//   begin_tile(k0)            : called once per K tile before its loads (wave-uniform k0)
+//   load4<KMASK>(slot, k, out): !KC only: the slot's 8 rows at k, k+1, k+2, k+3
 // Out-of-range rows / k return zeros.
 // Rows are remembered as 32-bit byte offsets from a wave-uniform base (scalar base + vector offset addressing).
 // Loads are UNCONDITIONAL and never sit under a branch or feed a select: a load whose only use is one arm of a select is
@@ -62,6 +64,7 @@ __device__ __forceinline__ u32x4 and_mask(u32x4 v, bool keep)
 }
 template <int SLOTS> struct DenseKC {
     static constexpr bool KC = true;
+    static constexpr bool kFence = true;
     const char *base;
     int ld, rows, K;
     uint32_t off[SLOTS];
@@ -77,9 +80,11 @@ template <int SLOTS> struct DenseKC {
     {
         return and_mask(load(slot, k < K ? k : K - 8), k < K);
     }
+    __device__ __forceinline__ void begin_tile(int) {}
 };
 template <int SLOTS> struct DenseRC {
     static constexpr bool KC = false;
+    static constexpr bool kFence = true;
     const char *base;
     int ld, rows, K;
     uint32_t off[SLOTS];
@@ -91,6 +96,13 @@ template <int SLOTS> struct DenseRC {
     __device__ __forceinline__ u32x4 load_masked(int slot, int k) const
     {
         return and_mask(load(slot, k < K ? k : K - 1), k < K);
+    }
+    __device__ __forceinline__ void begin_tile(int) {}
+    // four consecutive k for one slot
+    template <bool KMASK> __device__ __forceinline__ void load4(int slot, int k, u32x4 *out) const
+    {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) out[q] = KMASK ? load_masked(slot, k + q) : load(slot, k + q);
     }
 };
 
@@ -123,10 +135,11 @@ template <int ROWS, bool KC> struct Stage {
 
     // KMASK = false: K is a multiple of BK; a tile start beyond K (prefetch past the end) is pulled back to the last
     // tile (its data is never used).  KMASK = true: per-vector clamping and zeroing.
-    template <bool KMASK, class L> __device__ __forceinline__ void load(const L &ld, int k0)
+    template <bool KMASK, class L> __device__ __forceinline__ void load(L &ld, int k0)
     {
         const int tid = threadIdx.x;
         if constexpr (!KMASK) k0 = k0 < ld.K ? k0 : ld.K - BK;
+        ld.begin_tile(k0);
         if constexpr (KC) {
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
@@ -137,11 +150,7 @@ template <int ROWS, bool KC> struct Stage {
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
                 const int kg = (tid + i * kThreads) & 15;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int k = k0 + kg * 4 + q;
-                    r[i * 4 + q] = KMASK ? ld.load_masked(i, k) : ld.load(i, k);
-                }
+                ld.template load4<KMASK>(i, k0 + kg * 4, &r[i * 4]);
             }
         }
     }
@@ -245,14 +254,18 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
             {
                 sa0.template load<KMASK>(la, (kt + 2) * BK);
                 sb0.template load<KMASK>(lb, (kt + 2) * BK);
+                if constexpr (LA::kFence && LB::kFence) __builtin_amdgcn_sched_barrier(0); // keep the prefetch ahead of the MFMAs (see below)
                 compute(smem, smem + A_ELEMS);
+                if constexpr (LA::kFence && LB::kFence) __builtin_amdgcn_sched_barrier(0);
                 if (kt + 1 < nk) { sa1.store(smem + BUF); sb1.store(smem + BUF + A_ELEMS); }
                 __syncthreads();
             }
             if (kt + 1 < nk) {
                 sa1.template load<KMASK>(la, (kt + 3) * BK);
                 sb1.template load<KMASK>(lb, (kt + 3) * BK);
+                if constexpr (LA::kFence && LB::kFence) __builtin_amdgcn_sched_barrier(0);
                 compute(smem + BUF, smem + BUF + A_ELEMS);
+                if constexpr (LA::kFence && LB::kFence) __builtin_amdgcn_sched_barrier(0);
                 if (kt + 2 < nk) { sa0.store(smem); sb0.store(smem + A_ELEMS); }
                 __syncthreads();
             }
@@ -269,7 +282,12 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
             const bool more = kt + 1 < nk;
             sa0.template load<KMASK>(la, (kt + 1) * BK);
             sb0.template load<KMASK>(lb, (kt + 1) * BK);
+            // Scheduling fences (dense loaders): without them the compiler, short of registers, sinks the global
+            // loads below the MFMA block and waits for them at once, so no memory latency is hidden.  Gather loaders
+            // do better unfenced: their address arithmetic then interleaves with the MFMAs.
+            if constexpr (LA::kFence && LB::kFence) __builtin_amdgcn_sched_barrier(0);
             compute(cur, cur + A_ELEMS);
+            if constexpr (LA::kFence && LB::kFence) __builtin_amdgcn_sched_barrier(0);
             if (more) { sa0.store(nxt); sb0.store(nxt + A_ELEMS); }
             __syncthreads();
         }
