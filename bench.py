@@ -22,9 +22,14 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/*pmc*.txt); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM traffic per launch (read + write bytes) of the large shard products from the rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs summarised in profiles/vgg16_fc_step_hbm_traffic_pmc.txt (counters scaled by what the same counters
+# read for the W_1 retile, a copy of known size).  Keyed by workload, kernel and per-shard M x N x K; None if not measured.
+MEASURED_TRAFFIC_BYTES = {
+    "vgg16_fc:gemm_tn:3136x4096x256": int((46.21 + 205.51) * 1e6),
+    "vgg16_fc:gemm_nn:256x4096x3136": int((218.53 + 33.55) * 1e6),
+    "vgg16_fc:gemm_nt:256x3136x4096": int((222.60 + 12.84) * 1e6),
+}
 
 
 def parse():
@@ -289,7 +294,7 @@ def main():
     conv_ms = sum(a["ms"] for a in agg if not is_product(a)) / K
     dom = agg[0]
     dom_ms = dom["ms"] / dom["launches"]
-    key = "%s:%s" % (args.workload, dom["kernel"])
+    key = "%s:%s:%dx%dx%d" % (args.workload, dom["kernel"], dom["d0"], dom["d1"], dom["d2"])
     roofline = {
         "bound": "mfma", "kernel": "%s count=%d M=%d N=%d K=%d" % (dom["kernel"], dom["count"], dom["d0"], dom["d1"], dom["d2"]),
         "achieved": dom["flops"] / (dom_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
