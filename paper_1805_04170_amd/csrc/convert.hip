@@ -169,6 +169,7 @@ struct ReduceParams {
     uint8_t red_ids[kMaxShards]; // id bits of partial number p
     GridDev Z, B;                // scols_v in units of EV elements
     uint32_t k, nrep, nred;
+    uint32_t ksplit; // partial buffers per shard (extra split of the reduction dimension inside a shard)
     uint32_t piece_rows, piece_cv, pieces_c, pieces, tiles_per_piece, piece_vecs, step_rows, step_cv;
 };
 
@@ -219,8 +220,9 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(const ReduceParams p)
         if (cv >= p.piece_cv) { cv -= p.piece_cv; ++row; }
     }
     // partial sums are added in increasing partial number: a fixed order, independent of the launch shape
-    for (uint32_t q = 0; q < p.nred; ++q) {
-        const FV *src = reinterpret_cast<const FV *>(p.part[sz.shard | p.red_ids[q]]);
+    for (uint32_t qq = 0; qq < p.nred * p.ksplit; ++qq) {
+        const uint32_t q = qq / p.ksplit, c = qq - q * p.ksplit;
+        const FV *src = reinterpret_cast<const FV *>(p.part[(sz.shard | p.red_ids[q]) * p.ksplit + c]);
         FV v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -398,8 +400,9 @@ template <int EV, bool OUT_BF16> static tt_status launch_reduce_e(const ReducePa
 }
 
 tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, const float *const *partials,
-                        const uint8_t *zl, int k, int64_t rows, int64_t cols, int act, void *stream)
+                        const uint8_t *zl, int k, int64_t rows, int64_t cols, int act, int ksplit, void *stream)
 {
+    if (ksplit < 1 || (ksplit << k) > kMaxShards) return TT_EINVAL;
     if (!dst || !partials || !valid_k(k) || rows < 0 || cols < 0) return TT_EINVAL;
     if (rows == 0 || cols == 0) return TT_OK;
     if (out_dtype != TT_F32 && out_dtype != TT_BF16) return TT_EINVAL;
@@ -409,18 +412,20 @@ tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, cons
     if (!make_grid(zl, k, rows, cols, &Z) || !make_grid(Bl, k, rows, cols, &B)) return TT_EINFEASIBLE;
     const int n = 1 << k;
     for (int s = 0; s < n; ++s)
-        if (!dst[s] || !partials[s]) return TT_EINVAL;
+        if (!dst[s]) return TT_EINVAL;
+    for (int s = 0; s < n * ksplit; ++s)
+        if (!partials[s]) return TT_EINVAL;
     int64_t piece_rows = Z.srows < B.srows ? Z.srows : B.srows;
     int64_t piece_cols = Z.scols < B.scols ? Z.scols : B.scols;
     const size_t out_b = out_dtype == TT_BF16 ? 2 : 4;
     int ev = 4;
-    if (piece_cols % 4 || !aligned_all(reinterpret_cast<const void *const *>(partials), n, 16) ||
+    if (piece_cols % 4 || !aligned_all(reinterpret_cast<const void *const *>(partials), n * ksplit, 16) ||
         !aligned_all(const_cast<const void *const *>(dst), n, 4 * out_b))
         ev = 1;
 
     ReduceParams p;
     for (int s = 0; s < kMaxShards; ++s) {
-        p.part[s] = s < n ? partials[s] : nullptr;
+        p.part[s] = s < n * ksplit ? partials[s] : nullptr;
         p.dst[s] = s < n ? dst[s] : nullptr;
         p.rep_ids[s] = 0;
         p.red_ids[s] = 0;
@@ -430,6 +435,7 @@ tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, cons
     p.k = (uint32_t)k;
     p.nrep = 1u << B.kX;
     p.nred = 1u << Z.kX;
+    p.ksplit = (uint32_t)ksplit;
     for (uint32_t r = 0; r < p.nrep; ++r) p.rep_ids[r] = (uint8_t)deposit(r, B.maskX, k);
     for (uint32_t q = 0; q < p.nred; ++q) p.red_ids[q] = (uint8_t)deposit(q, Z.maskX, k);
     const int64_t piece_cv = piece_cols / ev;
@@ -450,7 +456,7 @@ tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, cons
     if (blocks >= (uint64_t(1) << 31)) return TT_EUNSUPPORTED;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const uint64_t elems = (uint64_t)rows * (uint64_t)cols;
-    ProfileScope scope(stream, TT_K_REDUCE, n, rows, cols, (int64_t)out_b, elems * 4u * p.nred + elems * out_b * p.nrep, 0);
+    ProfileScope scope(stream, TT_K_REDUCE, n, rows, cols, (int64_t)out_b, elems * 4u * p.nred * p.ksplit + elems * out_b * p.nrep, 0);
     if (ev == 4) return out_dtype == TT_BF16 ? launch_reduce_e<4, true>(p, (uint32_t)blocks, act, unroll, s)
                                               : launch_reduce_e<4, false>(p, (uint32_t)blocks, act, unroll, s);
     return out_dtype == TT_BF16 ? launch_reduce_e<1, true>(p, (uint32_t)blocks, act, unroll, s)
@@ -487,5 +493,5 @@ extern "C" tt_status tt_reduce(void *const *dst, tt_tiling B, int out_dtype, con
         if (forms[j] > TT_F3) return TT_EINVAL;
         zl[j] = forms[j] == TT_F1 ? TT_R : (forms[j] == TT_F2 ? TT_C : tt::kRed);
     }
-    return tt::launch_reduce(dst, B.cut, out_dtype, partials, zl, k, rows, cols, act, stream);
+    return tt::launch_reduce(dst, B.cut, out_dtype, partials, zl, k, rows, cols, act, 1, stream);
 }

@@ -82,19 +82,22 @@ struct OutputPlan {
     int gemm_dtype = TT_F32;
     int gemm_act = TT_ACT_NONE;
     int mode = 0; // 0: products write the stored shards; 1: conversion afterwards; 2: reduction afterwards
+    int ksplit = 1; // > 1: each shard product is cut further along K into ksplit partial sums (mode 2)
     uint8_t zl[TT_MAX_K];
 };
 
 // zl: the temporary outputs' grid letters per cut (TT_R, TT_C or kRed) in the coordinates of the rows x cols matrix
+// ksplit: extra K split inside every shard (see pick_ksplit); forces the reduction path
 inline tt_status plan_output_letters(const uint8_t *zl, const tt_tiling &tZ, void *const *Z, int64_t rows, int64_t cols,
-                                     int k, int dtype, int act, Workspace &ws, OutputPlan *op)
+                                     int k, int dtype, int act, Workspace &ws, OutputPlan *op, int ksplit = 1)
 {
     Grid gz, gt;
     for (int j = 0; j < k; ++j) op->zl[j] = zl[j];
     if (!make_grid(op->zl, k, rows, cols, &gz) || !make_grid(tZ.cut, k, rows, cols, &gt)) return TT_EINFEASIBLE;
     const int n = 1 << k;
     const size_t esz = dtype == TT_BF16 ? 2 : 4;
-    if (gz.kX == 0 && gt.kX == 0 && gz.kR == gt.kR && gz.kC == gt.kC) {
+    op->ksplit = ksplit;
+    if (ksplit == 1 && gz.kX == 0 && gt.kX == 0 && gz.kR == gt.kR && gz.kC == gt.kC) {
         op->mode = 0;
         op->gemm_dtype = dtype;
         op->gemm_act = act;
@@ -104,21 +107,34 @@ inline tt_status plan_output_letters(const uint8_t *zl, const tt_tiling &tZ, voi
         }
         return TT_OK;
     }
-    const bool red = gz.kX > 0;
+    const bool red = gz.kX > 0 || ksplit > 1;
+    if (n * ksplit > kMaxShards) return TT_EINVAL;
     op->mode = red ? 2 : 1;
     op->gemm_dtype = red ? TT_F32 : dtype;
     op->gemm_act = red ? TT_ACT_NONE : act; // the element-wise function comes after the sum
     const size_t bytes = (size_t)gz.srows * (size_t)gz.scols * (red ? 4 : esz);
-    for (int s = 0; s < n; ++s) op->gemm_out[s] = ws.take(bytes);
+    for (int s = 0; s < n * ksplit; ++s) op->gemm_out[s] = ws.take(bytes);
     return ws.overflow ? TT_EWORKSPACE : TT_OK;
 }
 
 inline tt_status plan_output(const uint8_t *forms, const tt_tiling &tZ, void *const *Z, int64_t rows, int64_t cols, int k,
-                             int dtype, int act, Workspace &ws, OutputPlan *op)
+                             int dtype, int act, Workspace &ws, OutputPlan *op, int ksplit = 1)
 {
     uint8_t zl[TT_MAX_K];
     aligned_tilings(forms, k, nullptr, nullptr, zl);
-    return plan_output_letters(zl, tZ, Z, rows, cols, k, dtype, act, ws, op);
+    return plan_output_letters(zl, tZ, Z, rows, cols, k, dtype, act, ws, op, ksplit);
+}
+
+// Extra split of the reduction dimension inside every shard product.  Skinny products (few output tiles, long K: the
+// batch-256 layers) leave most CUs idle and too few bytes in flight to stream the weights; cutting K puts more
+// workgroups on the machine at the price of fp32 partial sums that the reduction kernel adds up.
+inline int pick_ksplit(int64_t M, int64_t N, int64_t K, int count, int dtype, bool a_contig8, bool b_contig8)
+{
+    if (dtype != TT_BF16 || !a_contig8 || !b_contig8) return 1;
+    const int64_t blocks = ((M + (M > 128 ? 255 : 127)) / (M > 128 ? 256 : 128)) * ((N + 127) / 128) * count;
+    int s = 1;
+    while (blocks * s < 384 && s < 8 && K / (2 * s) >= 512 && count * 2 * s <= kMaxShards) s *= 2;
+    return s;
 }
 
 inline tt_status finish_output(const OutputPlan &op, const tt_tiling &tZ, void *const *Z, int64_t rows, int64_t cols, int k,
@@ -132,7 +148,7 @@ inline tt_status finish_output(const OutputPlan &op, const tt_tiling &tZ, void *
                               cols, dtype == TT_BF16 ? 2 : 4, 0, false, stream);
     }
     return launch_reduce(Z, tZ.cut, dtype, reinterpret_cast<const float *const *>(op.gemm_out), op.zl, k, rows, cols, act,
-                         stream);
+                         op.ksplit, stream);
 }
 
 inline bool forms_feasible(const uint8_t *forms, int k, int64_t M, int64_t N, int64_t K)

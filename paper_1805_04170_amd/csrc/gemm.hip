@@ -25,30 +25,35 @@ struct GemmParams {
     int32_t lda, ldb, ldc;
     int32_t tiles_m, tiles_n;
     int32_t per_xcd;  // logical workgroups per XCD (grid = per_xcd * 8)
-    int32_t total;    // tiles_m * tiles_n * count
+    int32_t total;    // tiles_m * tiles_n * count * ksplit
     int32_t relu;
+    int32_t ksplit;   // each shard's K range is cut into ksplit chunks of kchunk (a multiple of 64); chunk c of shard s
+    int32_t kchunk;   // writes its own output C[s * ksplit + c] (partial sums, added up by the reduction kernel)
 };
 
 template <int BM, int BN, int WM, int WN, int DEPTH, bool KMASK, bool A_KC, bool B_KC, bool OUT_BF16, bool VEC>
-__global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(const GemmParams p)
+__global__ __launch_bounds__(kThreads, DEPTH == 0 ? 2 : 1) void gemm_bf16_kernel(const GemmParams p)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     const int logical = core::logical_block(p.per_xcd, p.total);
     if (logical < 0) return;
     const int tiles = p.tiles_m * p.tiles_n;
-    const int shard = logical / tiles;
-    const int t = logical - shard * tiles;
+    const int vshard = logical / tiles;
+    const int t = logical - vshard * tiles;
     const int tm = t % p.tiles_m, tn = t / p.tiles_m;
+    const int shard = vshard / p.ksplit;
+    const int kbeg = (vshard - shard * p.ksplit) * p.kchunk;
+    const int klen = p.K - kbeg < p.kchunk ? p.K - kbeg : p.kchunk;
 
     using LA = std::conditional_t<A_KC, core::DenseKC<core::Slots<BM, true>::value>, core::DenseRC<core::Slots<BM, false>::value>>;
     using LB = std::conditional_t<B_KC, core::DenseKC<core::Slots<BN, true>::value>, core::DenseRC<core::Slots<BN, false>::value>>;
     LA la;
-    la.base = reinterpret_cast<const char *>(p.A[shard]);
-    la.ld = p.lda; la.rows = p.M; la.K = p.K;
+    la.base = reinterpret_cast<const char *>(p.A[shard]) + (size_t)kbeg * (A_KC ? 2 : 2 * (size_t)p.lda);
+    la.ld = p.lda; la.rows = p.M; la.K = klen;
     LB lb;
-    lb.base = reinterpret_cast<const char *>(p.B[shard]);
-    lb.ld = p.ldb; lb.rows = p.N; lb.K = p.K;
-    core::tile_product<BM, BN, WM, WN, DEPTH, KMASK, OUT_BF16, VEC>(la, lb, p.C[shard], p.ldc, p.M, p.N, p.K, tm * BM, tn * BN, p.relu != 0, smem);
+    lb.base = reinterpret_cast<const char *>(p.B[shard]) + (size_t)kbeg * (B_KC ? 2 : 2 * (size_t)p.ldb);
+    lb.ld = p.ldb; lb.rows = p.N; lb.K = klen;
+    core::tile_product<BM, BN, WM, WN, DEPTH, KMASK, OUT_BF16, VEC>(la, lb, p.C[vshard], p.ldc, p.M, p.N, klen, tm * BM, tn * BN, p.relu != 0, smem);
 }
 
 // ---------------------------------------------------------------- generic kernel (fp32, or any unaligned shape)
@@ -61,6 +66,7 @@ struct GenericParams {
     int64_t sam, sak, sbk, sbn;
     int32_t ldc;
     int32_t tiles_m, tiles_n;
+    int32_t ksplit, kchunk;
 };
 
 template <bool IN_BF16> __device__ __forceinline__ float load_in(const void *p, int64_t off)
@@ -76,24 +82,27 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(const GenericPar
     __shared__ float As[KB][T + 1];
     __shared__ float Bs[KB][T + 1];
     int tiles = p.tiles_m * p.tiles_n;
-    int shard = blockIdx.x / tiles;
-    int t = blockIdx.x - shard * tiles;
+    int vshard = blockIdx.x / tiles;
+    int t = blockIdx.x - vshard * tiles;
     int m0 = (t % p.tiles_m) * T, n0 = (t / p.tiles_m) * T;
+    const int shard = vshard / p.ksplit;
+    const int kbeg = (vshard - shard * p.ksplit) * p.kchunk;
+    const int kend = kbeg + p.kchunk < p.K ? kbeg + p.kchunk : p.K;
     const void *A = p.A[shard];
     const void *B = p.B[shard];
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     float acc[4][4] = {};
-    for (int k0 = 0; k0 < p.K; k0 += KB) {
+    for (int k0 = kbeg; k0 < kend; k0 += KB) {
         for (int i = threadIdx.x; i < T * KB; i += kThreads) {
             // A tile: pick the loop order that walks the contiguous stride
             int kk, mm;
             if (p.sak == 1) { kk = i % KB; mm = i / KB; } else { mm = i % T; kk = i / T; }
             int gm = m0 + mm, gk = k0 + kk;
-            As[kk][mm] = (gm < p.M && gk < p.K) ? load_in<IN_BF16>(A, gm * p.sam + gk * p.sak) : 0.0f;
+            As[kk][mm] = (gm < p.M && gk < kend) ? load_in<IN_BF16>(A, gm * p.sam + gk * p.sak) : 0.0f;
             int kb, nn;
             if (p.sbk == 1) { kb = i % KB; nn = i / KB; } else { nn = i % T; kb = i / T; }
             int gn = n0 + nn, gkb = k0 + kb;
-            Bs[kb][nn] = (gn < p.N && gkb < p.K) ? load_in<IN_BF16>(B, gkb * p.sbk + gn * p.sbn) : 0.0f;
+            Bs[kb][nn] = (gn < p.N && gkb < kend) ? load_in<IN_BF16>(B, gkb * p.sbk + gn * p.sbn) : 0.0f;
         }
         __syncthreads();
 #pragma unroll
@@ -116,8 +125,8 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(const GenericPar
             if (row >= p.M || col >= p.N) continue;
             float v = acc[i][j];
             if (RELU) v = v > 0.0f ? v : 0.0f;
-            if (OUT_BF16) reinterpret_cast<uint16_t *>(p.C[shard])[(size_t)row * p.ldc + col] = (uint16_t)f32_to_bf16_bits(v);
-            else reinterpret_cast<float *>(p.C[shard])[(size_t)row * p.ldc + col] = v;
+            if (OUT_BF16) reinterpret_cast<uint16_t *>(p.C[vshard])[(size_t)row * p.ldc + col] = (uint16_t)f32_to_bf16_bits(v);
+            else reinterpret_cast<float *>(p.C[vshard])[(size_t)row * p.ldc + col] = v;
         }
 }
 
@@ -125,7 +134,7 @@ template <int BM, int BN, int WM, int WN, int DEPTH, bool KMASK, bool A_KC, bool
 tt_status launch_mfma_cfg(GemmParams &p, int count, hipStream_t s)
 {
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, DEPTH, KMASK, A_KC, B_KC, OUT_BF16, VEC>;
-    constexpr size_t smem = core::smem_bytes<BM, BN>();
+    constexpr size_t smem = core::smem_bytes<BM, BN, DEPTH>();
     static bool configured = false; // per instantiation; setting the attribute twice is harmless
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
@@ -134,7 +143,7 @@ tt_status launch_mfma_cfg(GemmParams &p, int count, hipStream_t s)
     }
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
-    int64_t total = (int64_t)p.tiles_m * p.tiles_n * count;
+    int64_t total = (int64_t)p.tiles_m * p.tiles_n * count * p.ksplit;
     if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
     p.total = (int32_t)total;
     p.per_xcd = (int32_t)((total + kXcds - 1) / kXcds);
@@ -150,7 +159,7 @@ tt_status launch_mfma_cfg(GemmParams &p, int count, hipStream_t s)
 int pick_tile(int64_t M, int64_t N, int64_t K, int count)
 {
     static const int forced = [] { const char *e = std::getenv("TT_GEMM_TILE"); return e ? std::atoi(e) : -1; }();
-    if (forced >= 0 && forced <= 2) return forced;
+    if (forced >= 0 && forced <= 3) return forced;
     const int64_t big = ((M + 255) / 256) * ((N + 255) / 256) * count;
     if (M > 128 && N > 128 && K >= 512 && big >= 200) return 2;
     return (M > 128 && K >= 1024) ? 0 : 1;
@@ -158,7 +167,8 @@ int pick_tile(int64_t M, int64_t N, int64_t K, int count)
 
 template <bool KMASK, bool A_KC, bool B_KC, bool OUT_BF16, bool VEC> tt_status launch_mfma_tile(GemmParams &p, int count, hipStream_t s)
 {
-    const int tile = pick_tile(p.M, p.N, p.K, count);
+    const int tile = pick_tile(p.M, p.N, p.ksplit > 1 ? p.kchunk : p.K, count * p.ksplit);
+    if (tile == 3) return launch_mfma_cfg<256, 128, 2, 2, 0, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
     if (tile == 2) return launch_mfma_cfg<256, 256, 2, 2, 1, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
     if (tile == 0) return launch_mfma_cfg<256, 128, 2, 2, 2, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
     return launch_mfma_cfg<128, 128, 2, 2, 1, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
@@ -181,7 +191,7 @@ template <bool A_KC, bool B_KC> tt_status launch_mfma_out(GemmParams &p, int cou
 template <bool IN_BF16> tt_status launch_generic_in(const GenericParams &p, int count, int out_dtype, int act, hipStream_t s)
 {
     const bool relu = act == TT_ACT_RELU;
-    dim3 grid((uint32_t)(p.tiles_m * p.tiles_n * count)), block(kThreads);
+    dim3 grid((uint32_t)(p.tiles_m * p.tiles_n * count * p.ksplit)), block(kThreads);
     if (out_dtype == TT_BF16) {
         if (relu) hipLaunchKernelGGL((gemm_generic_kernel<IN_BF16, true, true>), grid, block, 0, s, p);
         else hipLaunchKernelGGL((gemm_generic_kernel<IN_BF16, true, false>), grid, block, 0, s, p);
@@ -202,15 +212,21 @@ bool all_aligned16(const void *const *ptrs, int n)
 } // namespace
 
 tt_status launch_gemm(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
-                      int64_t K, int trans_a, int trans_b, int in_dtype, int out_dtype, int act, void *stream)
+                      int64_t K, int trans_a, int trans_b, int in_dtype, int out_dtype, int act, int ksplit, void *stream)
 {
     if (!A || !B || !C || count < 0 || count > kMaxShards || M < 0 || N < 0 || K < 0) return TT_EINVAL;
     if ((in_dtype != TT_BF16 && in_dtype != TT_F32) || (out_dtype != TT_BF16 && out_dtype != TT_F32)) return TT_EINVAL;
     if (act != TT_ACT_NONE && act != TT_ACT_RELU) return TT_EINVAL;
+    if (ksplit < 1 || count * ksplit > kMaxShards) return TT_EINVAL;
     if (count == 0 || M == 0 || N == 0) return TT_OK;
     if (M >= (int64_t(1) << 31) || N >= (int64_t(1) << 31) || K >= (int64_t(1) << 31)) return TT_EUNSUPPORTED;
     for (int s = 0; s < count; ++s)
-        if (!A[s] || !B[s] || !C[s]) return TT_EINVAL;
+        if (!A[s] || !B[s]) return TT_EINVAL;
+    for (int s = 0; s < count * ksplit; ++s)
+        if (!C[s]) return TT_EINVAL;
+    // K chunk per split: a multiple of the tile depth; every chunk must be non-empty
+    const int64_t kchunk = ksplit == 1 ? (K > 0 ? K : 1) : ((K + ksplit - 1) / ksplit + 63) / 64 * 64;
+    if (ksplit > 1 && kchunk * (ksplit - 1) >= K) return TT_EINVAL;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
     // MFMA path needs 16-byte vectors along each operand's contiguous dimension
@@ -230,15 +246,17 @@ tt_status launch_gemm(int count, const void *const *A, const void *const *B, voi
         for (int i = 0; i < kMaxShards; ++i) {
             p.A[i] = i < count ? A[i] : nullptr;
             p.B[i] = i < count ? B[i] : nullptr;
-            p.C[i] = i < count ? C[i] : nullptr;
+            p.C[i] = i < count * ksplit ? C[i] : nullptr;
         }
         p.M = (int32_t)M; p.N = (int32_t)N; p.K = (int32_t)K;
         p.lda = (int32_t)a_contig;
         p.ldb = (int32_t)b_contig;
         p.ldc = (int32_t)N;
+        p.ksplit = ksplit;
+        p.kchunk = (int32_t)kchunk;
         const bool a_kc = !trans_a, b_kc = trans_b != 0;
         // 16-byte stores along C's rows need 16-byte row pitch and base addresses
-        const bool vec = N % (out_dtype == TT_BF16 ? 8 : 4) == 0 && all_aligned16(const_cast<const void *const *>(C), count);
+        const bool vec = N % (out_dtype == TT_BF16 ? 8 : 4) == 0 && all_aligned16(const_cast<const void *const *>(C), count * ksplit);
         if (a_kc && b_kc) return launch_mfma_out<true, true>(p, count, out_dtype, act, vec, s);
         if (a_kc && !b_kc) return launch_mfma_out<true, false>(p, count, out_dtype, act, vec, s);
         if (!a_kc && !b_kc) return launch_mfma_out<false, false>(p, count, out_dtype, act, vec, s);
@@ -248,7 +266,7 @@ tt_status launch_gemm(int count, const void *const *A, const void *const *B, voi
     for (int i = 0; i < kMaxShards; ++i) {
         g.A[i] = i < count ? A[i] : nullptr;
         g.B[i] = i < count ? B[i] : nullptr;
-        g.C[i] = i < count ? C[i] : nullptr;
+        g.C[i] = i < count * ksplit ? C[i] : nullptr;
     }
     g.M = (int32_t)M; g.N = (int32_t)N; g.K = (int32_t)K;
     g.sam = trans_a ? 1 : K; g.sak = trans_a ? M : 1;
@@ -256,7 +274,9 @@ tt_status launch_gemm(int count, const void *const *A, const void *const *B, voi
     g.ldc = (int32_t)N;
     g.tiles_m = (int32_t)((M + 63) / 64);
     g.tiles_n = (int32_t)((N + 63) / 64);
-    if ((int64_t)g.tiles_m * g.tiles_n * count >= (int64_t(1) << 31)) return TT_EUNSUPPORTED;
+    g.ksplit = ksplit;
+    g.kchunk = (int32_t)kchunk;
+    if ((int64_t)g.tiles_m * g.tiles_n * count * ksplit >= (int64_t(1) << 31)) return TT_EUNSUPPORTED;
     return in_dtype == TT_BF16 ? launch_generic_in<true>(g, count, out_dtype, act, s)
                                : launch_generic_in<false>(g, count, out_dtype, act, s);
 }
@@ -267,5 +287,5 @@ extern "C" tt_status tt_shard_gemm(int count, const void *const *A, const void *
                                    int64_t N, int64_t K, int trans_a, int trans_b, int in_dtype, int out_dtype, int act,
                                    void *stream)
 {
-    return tt::launch_gemm(count, A, B, C, M, N, K, trans_a, trans_b, in_dtype, out_dtype, act, stream);
+    return tt::launch_gemm(count, A, B, C, M, N, K, trans_a, trans_b, in_dtype, out_dtype, act, 1, stream);
 }

@@ -184,7 +184,11 @@ template <int ROWS, bool KC> struct Stage {
     }
 };
 
-template <int BM, int BN> constexpr size_t smem_bytes() { return 2 * (size_t)(BM + BN) * LDK * sizeof(uint16_t); }
+// DEPTH 1, 2: double-buffered LDS; DEPTH 0: one LDS buffer (two barriers per K tile), for two workgroups per CU
+template <int BM, int BN, int DEPTH = 1> constexpr size_t smem_bytes()
+{
+    return (DEPTH == 0 ? 1 : 2) * (size_t)(BM + BN) * LDK * sizeof(uint16_t);
+}
 
 // ---- the tile product ---------------------------------------------------------------------------------------------
 // C tile origin (m0, n0); C is row-major with leading dimension ldc, M x N valid.  KMASK: K is not a multiple of 64
@@ -270,6 +274,22 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
                 __syncthreads();
             }
         }
+    } else if constexpr (DEPTH == 0) {
+        // One LDS buffer and one tile in registers: small enough (LDS and registers) for two workgroups per CU, whose
+        // waves fill each other's barrier and memory waits.
+        sa0.template load<KMASK>(la, 0);
+        sb0.template load<KMASK>(lb, 0);
+        for (int kt = 0; kt < nk; ++kt) {
+            sa0.store(smem);
+            sb0.store(smem + A_ELEMS);
+            __syncthreads();
+            sa0.template load<KMASK>(la, (kt + 1) * BK);
+            sb0.template load<KMASK>(lb, (kt + 1) * BK);
+            if constexpr (LA::kFence && LB::kFence) __builtin_amdgcn_sched_barrier(0);
+            compute(smem, smem + A_ELEMS);
+            if constexpr (LA::kFence && LB::kFence) __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+        }
     } else {
         // one tile in flight in registers (fewer registers: more workgroups per CU)
         sa0.template load<KMASK>(la, 0);
@@ -318,7 +338,7 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
         constexpr int SW = TN * 32;        // strip width (elements)
         constexpr int SLD = SW + 4;        // padded fp32 row
         float *strip = reinterpret_cast<float *>(smem) + wave * (32 * SLD);
-        static_assert(4 * 32 * SLD * sizeof(float) <= smem_bytes<BM, BN>(), "strip staging fits in the operand buffers");
+        static_assert(4 * 32 * SLD * sizeof(float) <= smem_bytes<BM, BN, DEPTH>(), "strip staging fits in the operand buffers");
         constexpr int EPV = OUT_BF16 ? 8 : 4;            // elements per 16-byte output vector
         constexpr int VPR = SW / EPV;                    // vectors per strip row
         constexpr int RPI = 64 / VPR;                    // strip rows covered by one wave-wide store

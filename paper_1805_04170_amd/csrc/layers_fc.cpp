@@ -58,9 +58,11 @@ tt_status forward(const FcArgs &a, Workspace &ws)
     if ((st = prepare_operand(X, aX, k, esz, nullptr, a.dtype, ws, a.stream, &Xa)) != TT_OK) return st;
     if ((st = prepare_operand(W, aW, k, esz, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
     OutputPlan op;
-    if ((st = plan_output(forms, a.tY, a.Yout, M, N, k, a.dtype, a.layer->act, ws, &op)) != TT_OK) return st;
+    const int64_t Ms = M >> k1, Ns = N >> k2, Ks = K >> k3;
+    const int ksplit = pick_ksplit(Ms, Ns, Ks, n, a.dtype, Ks % 8 == 0, Ns % 8 == 0);
+    if ((st = plan_output(forms, a.tY, a.Yout, M, N, k, a.dtype, a.layer->act, ws, &op, ksplit)) != TT_OK) return st;
     if (ws.dry) return TT_OK;
-    st = launch_gemm(n, Xa.ptr, Wa.ptr, op.gemm_out, M >> k1, N >> k2, K >> k3, 0, 0, a.dtype, op.gemm_dtype, op.gemm_act,
+    st = launch_gemm(n, Xa.ptr, Wa.ptr, op.gemm_out, Ms, Ns, Ks, 0, 0, a.dtype, op.gemm_dtype, op.gemm_act, ksplit,
                      a.stream);
     if (st != TT_OK) return st;
     return finish_output(op, a.tY, a.Yout, M, N, k, a.dtype, a.layer->act, a.stream);
@@ -104,11 +106,13 @@ tt_status backward(const FcArgs &a, Workspace &ws)
         if (!gated) { G = Ga; gated = true; }
         if ((st = prepare_operand(W, aW, k, esz, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
         OutputPlan op;
-        if ((st = plan_output(f, a.tdX, a.dX, b, ni, k, a.dtype, TT_ACT_NONE, ws, &op)) != TT_OK) return st;
+        const int64_t Ms = b >> k1, Ns = ni >> k2, Ks = no >> k3;
+        const int ksplit = pick_ksplit(Ms, Ns, Ks, n, a.dtype, Ks % 8 == 0, Ks % 8 == 0);
+        if ((st = plan_output(f, a.tdX, a.dX, b, ni, k, a.dtype, TT_ACT_NONE, ws, &op, ksplit)) != TT_OK) return st;
         if (!ws.dry) {
             // W shard is (n_in/..) x (n_out/..) row-major = N x K: trans_b
-            st = launch_gemm(n, Ga.ptr, Wa.ptr, op.gemm_out, b >> k1, ni >> k2, no >> k3, 0, 1, a.dtype, op.gemm_dtype,
-                             op.gemm_act, a.stream);
+            st = launch_gemm(n, Ga.ptr, Wa.ptr, op.gemm_out, Ms, Ns, Ks, 0, 1, a.dtype, op.gemm_dtype, op.gemm_act, ksplit,
+                             a.stream);
             if (st != TT_OK) return st;
             if ((st = finish_output(op, a.tdX, a.dX, b, ni, k, a.dtype, TT_ACT_NONE, a.stream)) != TT_OK) return st;
         }
@@ -132,7 +136,7 @@ tt_status backward(const FcArgs &a, Workspace &ws)
         if (!ws.dry) {
             // X shard is (b/..) x (n_in/..) row-major = K x M: trans_a
             st = launch_gemm(n, Xa.ptr, Ga.ptr, op.gemm_out, ni >> k1, no >> k2, b >> k3, 1, 0, a.dtype, op.gemm_dtype,
-                             op.gemm_act, a.stream);
+                             op.gemm_act, 1, a.stream);
             if (st != TT_OK) return st;
             if ((st = finish_output(op, a.tW, a.dW, ni, no, k, a.dtype, TT_ACT_NONE, a.stream)) != TT_OK) return st;
         }

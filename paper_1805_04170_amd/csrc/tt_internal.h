@@ -104,11 +104,14 @@ tt_status launch_convert(void *const *dst, const uint8_t *B, const void *const *
                          const void *const *mask, const uint8_t *Am, int k, int64_t rows, int64_t cols,
                          int elem_bytes, int gate_dtype, bool dst_unique /* replicas of B alias one buffer */,
                          void *stream);
+// ksplit > 1: every shard comes as ksplit partial buffers (partials[s * ksplit + c]) that are summed as well
 tt_status launch_reduce(void *const *dst, const uint8_t *B, int out_dtype, const float *const *partials,
                         const uint8_t *zletters /* R, C or kRed per cut */, int k, int64_t rows, int64_t cols, int act,
-                        void *stream);
+                        int ksplit, void *stream);
+// ksplit > 1: each shard's K range is cut into ksplit chunks; chunk c of shard s writes C[s * ksplit + c]
 tt_status launch_gemm(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
-                      int64_t K, int trans_a, int trans_b, int in_dtype, int out_dtype, int act, void *stream);
+                      int64_t K, int trans_a, int trans_b, int in_dtype, int out_dtype, int act, int ksplit,
+                      void *stream);
 
 // Convolution shard products (conv.hip).  op TT_OP_FWD: A = X shards, B = filter shards, C = Y shards;
 // TT_OP_DGRAD: A = dY, B = filters, C = dX;  TT_OP_WGRAD: A = dY, B = X, C = dW.  Ns images, Cs input channels and
