@@ -15,7 +15,7 @@ LIB = os.path.join(PKG, "libtensor_tiling.so")
 
 # -packed-fp32-ops: keep the compiler from forming packed fp32 instructions (hipcc's host pass warns that it does
 # not know the feature; harmless)
-COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC] + os.environ.get("TT_EXTRA_CXXFLAGS", "").split()
 HIPFLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

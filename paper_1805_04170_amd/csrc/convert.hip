@@ -180,6 +180,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                  // round to nearest even
 }
 
+// two floats -> packed bf16 pair (low half = a), round to nearest even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    bf16x2_t v = {(__bf16)a, (__bf16)b};
+    return *reinterpret_cast<uint32_t *>(&v);
+}
+
 template <int EV> struct FVec;
 template <> struct FVec<4> { using type = f32x4; };
 template <> struct FVec<1> { using type = float; };
@@ -251,8 +259,8 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(const ReduceParams p)
             if constexpr (OUT_BF16) {
                 if constexpr (EV == 4) {
                     u32x2 o;
-                    o.x = f32_to_bf16_bits(acc[u][0]) | (f32_to_bf16_bits(acc[u][1]) << 16);
-                    o.y = f32_to_bf16_bits(acc[u][2]) | (f32_to_bf16_bits(acc[u][3]) << 16);
+                    o.x = pack_bf16x2(acc[u][0], acc[u][1]);
+                    o.y = pack_bf16x2(acc[u][2], acc[u][3]);
                     __builtin_nontemporal_store(o, reinterpret_cast<u32x2 *>(d) + doff[u]);
                 } else {
                     reinterpret_cast<uint16_t *>(d)[doff[u]] = (uint16_t)f32_to_bf16_bits(acc[u][0]);

@@ -7,6 +7,7 @@
 // read).  Likewise replicas of an aligned temporary share one buffer.  Real copies happen only when block shapes
 // differ, or when the gradient gate has to be applied.
 #pragma once
+#include <cstdlib>
 #include <cstring>
 #include "tt_internal.h"
 
@@ -131,9 +132,13 @@ inline tt_status plan_output(const uint8_t *forms, const tt_tiling &tZ, void *co
 inline int pick_ksplit(int64_t M, int64_t N, int64_t K, int count, int dtype, bool a_contig8, bool b_contig8)
 {
     if (dtype != TT_BF16 || !a_contig8 || !b_contig8) return 1;
-    const int64_t blocks = ((M + (M > 128 ? 255 : 127)) / (M > 128 ? 256 : 128)) * ((N + 127) / 128) * count;
+    if (const char *e = std::getenv("TT_KSPLIT")) { // tuning aid
+        const int f = std::atoi(e);
+        if (f >= 1 && K / f >= 256 && count * f <= kMaxShards) return f;
+    }
+    const int64_t blocks = ((M + 255) / 256) * ((N + 255) / 256) * count; // 256 x 256 tiles, one per CU
     int s = 1;
-    while (blocks * s < 384 && s < 8 && K / (2 * s) >= 512 && count * 2 * s <= kMaxShards) s *= 2;
+    while (blocks * s < 256 && s < 8 && K / (2 * s) >= 512 && count * 2 * s <= kMaxShards) s *= 2;
     return s;
 }
 

@@ -32,7 +32,7 @@ struct GemmParams {
 };
 
 template <int BM, int BN, int WM, int WN, int DEPTH, bool KMASK, bool A_KC, bool B_KC, bool OUT_BF16, bool VEC>
-__global__ __launch_bounds__(kThreads, DEPTH == 0 ? 2 : 1) void gemm_bf16_kernel(const GemmParams p)
+__global__ __launch_bounds__(WM * WN * 64, (WM * WN / 4) * (DEPTH == 0 ? (BM == 128 ? 3 : 2) : 1)) void gemm_bf16_kernel(const GemmParams p)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     const int logical = core::logical_block(p.per_xcd, p.total);
@@ -45,8 +45,9 @@ __global__ __launch_bounds__(kThreads, DEPTH == 0 ? 2 : 1) void gemm_bf16_kernel
     const int kbeg = (vshard - shard * p.ksplit) * p.kchunk;
     const int klen = p.K - kbeg < p.kchunk ? p.K - kbeg : p.kchunk;
 
-    using LA = std::conditional_t<A_KC, core::DenseKC<core::Slots<BM, true>::value>, core::DenseRC<core::Slots<BM, false>::value>>;
-    using LB = std::conditional_t<B_KC, core::DenseKC<core::Slots<BN, true>::value>, core::DenseRC<core::Slots<BN, false>::value>>;
+    constexpr int NT = WM * WN * 64;
+    using LA = std::conditional_t<A_KC, core::DenseKC<core::Slots<BM, true, NT>::value>, core::DenseRC<core::Slots<BM, false, NT>::value>>;
+    using LB = std::conditional_t<B_KC, core::DenseKC<core::Slots<BN, true, NT>::value>, core::DenseRC<core::Slots<BN, false, NT>::value>>;
     LA la;
     la.base = reinterpret_cast<const char *>(p.A[shard]) + (size_t)kbeg * (A_KC ? 2 : 2 * (size_t)p.lda);
     la.ld = p.lda; la.rows = p.M; la.K = klen;
@@ -147,27 +148,31 @@ tt_status launch_mfma_cfg(GemmParams &p, int count, hipStream_t s)
     if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
     p.total = (int32_t)total;
     p.per_xcd = (int32_t)((total + kXcds - 1) / kXcds);
-    hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * kXcds), dim3(kThreads), smem, s, p);
+    hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * kXcds), dim3(WM * WN * 64), smem, s, p);
     return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
 }
 
-// Tile choice.  Tall 256 x 128 tiles stream each weight element once per 256 batch rows and suit long K loops;
-// 128 x 128 tiles leave room for two workgroups per CU, which hides the prologue / epilogue of short K loops
-// (weight gradients: K = batch).  TT_GEMM_TILE=0|1 overrides (tuning aid).
-// 256 x 256 tiles (128 x 128 per wave) halve the LDS traffic per MFMA; used when the launch still has enough tiles to
-// cover the 256 CUs.
+// Tile choice (TT_GEMM_TILE=0..5 overrides; tuning aid).
+//   5: 256 x 256, eight waves (two per SIMD, 128 x 64 each): the default whenever the launch has enough tiles to put
+//      work on at least half the CUs; two resident waves per SIMD cover each other's LDS / memory waits and the large
+//      tile halves operand traffic per flop.
+//   0: 256 x 128, four waves, two K tiles prefetched in registers: long K loops with few column tiles.
+//   1: 128 x 128, four waves, up to two workgroups per CU: small products and short K loops.
+//   2, 3, 4: 256 x 256 four-wave, 256 x 128 and 128 x 128 single-LDS-buffer variants kept for experiments.
 int pick_tile(int64_t M, int64_t N, int64_t K, int count)
 {
     static const int forced = [] { const char *e = std::getenv("TT_GEMM_TILE"); return e ? std::atoi(e) : -1; }();
-    if (forced >= 0 && forced <= 3) return forced;
+    if (forced >= 0 && forced <= 5) return forced;
     const int64_t big = ((M + 255) / 256) * ((N + 255) / 256) * count;
-    if (M > 128 && N > 128 && K >= 512 && big >= 200) return 2;
+    if (M > 128 && N > 128 && big >= 128) return 5;
     return (M > 128 && K >= 1024) ? 0 : 1;
 }
 
 template <bool KMASK, bool A_KC, bool B_KC, bool OUT_BF16, bool VEC> tt_status launch_mfma_tile(GemmParams &p, int count, hipStream_t s)
 {
     const int tile = pick_tile(p.M, p.N, p.ksplit > 1 ? p.kchunk : p.K, count * p.ksplit);
+    if (tile == 5) return launch_mfma_cfg<256, 256, 2, 4, 1, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
+    if (tile == 4) return launch_mfma_cfg<128, 128, 2, 2, 0, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
     if (tile == 3) return launch_mfma_cfg<256, 128, 2, 2, 0, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
     if (tile == 2) return launch_mfma_cfg<256, 256, 2, 2, 1, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
     if (tile == 0) return launch_mfma_cfg<256, 128, 2, 2, 2, KMASK, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);

@@ -33,6 +33,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
+// two floats -> packed bf16 pair (low half = a); round to nearest even, compiled to v_cvt_pk_bf16_f32 on gfx950
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    bf16x2_t v = {(__bf16)a, (__bf16)b};
+    return *reinterpret_cast<uint32_t *>(&v);
+}
+
 __device__ __forceinline__ u32x4 zero4()
 {
     u32x4 z = {0, 0, 0, 0};
@@ -107,8 +115,9 @@ template <int SLOTS> struct DenseRC {
 };
 
 // number of loader slots a tile side of ROWS rows needs
-template <int ROWS, bool KC> struct Slots {
-    static constexpr int value = KC ? ROWS * (BK / 8) / kThreads : (BK / 4) * (ROWS / 8) / kThreads;
+template <int ROWS, bool KC, int NT = kThreads> struct Slots {
+    static constexpr int value = KC ? ROWS * (BK / 8) / NT : (BK / 4) * (ROWS / 8) / NT;
+    static_assert(value >= 1, "tile side too small for the workgroup");
 };
 
 // ---- register staging of one operand tile -------------------------------------------------------------------------
@@ -116,8 +125,8 @@ template <int ROWS, bool KC> struct Slots {
 // and k = 4 kg .. 4 kg + 3.  Lanes run over kg first (16 k-groups), then rv: the 8-byte LDS stores of a wave then fall
 // on 32 distinct 8-byte bank groups (two lanes each, the minimum), where running over rv first would pile eight lanes on
 // each group.  Global loads still cover 64 contiguous bytes per k-row per wave (4 lanes x 16 bytes).
-template <int ROWS, bool KC> struct Stage {
-    static constexpr int NS = Slots<ROWS, KC>::value;
+template <int ROWS, bool KC, int NT = kThreads> struct Stage {
+    static constexpr int NS = Slots<ROWS, KC, NT>::value;
     static constexpr int NV = KC ? NS : NS * 4;
     u32x4 r[NV];
 
@@ -126,10 +135,10 @@ template <int ROWS, bool KC> struct Stage {
         const int tid = threadIdx.x;
         if constexpr (KC) {
 #pragma unroll
-            for (int i = 0; i < NS; ++i) ld.init(i, row0 + ((tid + i * kThreads) >> 3));
+            for (int i = 0; i < NS; ++i) ld.init(i, row0 + ((tid + i * NT) >> 3));
         } else {
 #pragma unroll
-            for (int i = 0; i < NS; ++i) ld.init(i, row0 + ((tid + i * kThreads) >> 4) * 8);
+            for (int i = 0; i < NS; ++i) ld.init(i, row0 + ((tid + i * NT) >> 4) * 8);
         }
     }
 
@@ -143,13 +152,13 @@ template <int ROWS, bool KC> struct Stage {
         if constexpr (KC) {
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
-                const int k = k0 + (((tid + i * kThreads) & 7) << 3);
+                const int k = k0 + (((tid + i * NT) & 7) << 3);
                 r[i] = KMASK ? ld.load_masked(i, k) : ld.load(i, k);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
-                const int kg = (tid + i * kThreads) & 15;
+                const int kg = (tid + i * NT) & 15;
                 ld.template load4<KMASK>(i, k0 + kg * 4, &r[i * 4]);
             }
         }
@@ -161,13 +170,13 @@ template <int ROWS, bool KC> struct Stage {
         if constexpr (KC) {
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
-                const int v = tid + i * kThreads;
+                const int v = tid + i * NT;
                 *reinterpret_cast<u32x4 *>(lds + (v >> 3) * LDK + ((v & 7) << 3)) = r[i];
             }
         } else {
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
-                const int b = tid + i * kThreads;
+                const int b = tid + i * NT;
                 const int rv = b >> 4, kg = b & 15;
                 uint16_t *dst = lds + (rv * 8) * LDK + kg * 4;
                 const u32x4 &a = r[i * 4 + 0], &bq = r[i * 4 + 1], &c = r[i * 4 + 2], &d = r[i * 4 + 3];
@@ -198,7 +207,8 @@ template <int BM, int BN, int WM, int WN, int DEPTH, bool KMASK, bool OUT_BF16, 
 __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, int M, int N, int K, int m0, int n0,
                                              bool relu, uint16_t *smem)
 {
-    static_assert(WM * WN == 4, "four waves");
+    static_assert(WM * WN == 4 || WM * WN == 8, "four or eight waves");
+    constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int A_ELEMS = BM * LDK, B_ELEMS = BN * LDK, BUF = A_ELEMS + B_ELEMS;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -212,8 +222,8 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    using SA = Stage<BM, LA::KC>;
-    using SB = Stage<BN, LB::KC>;
+    using SA = Stage<BM, LA::KC, NT>;
+    using SB = Stage<BN, LB::KC, NT>;
     SA sa0, sa1;
     SB sb0, sb1;
     SA::bind(la, m0);
@@ -233,6 +243,7 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
             for (int j = 0; j < TN; ++j) bf[set][j] = *reinterpret_cast<const bf16x8 *>(bp + j * 32 * LDK + ks * 16);
         };
         fetch(0, 0);
+        __builtin_amdgcn_iglp_opt(1); // scheduler hint: interleave the LDS fragment reads with the MFMAs
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             if (ks + 1 < BK / 16) fetch(ks + 1, (ks + 1) & 1);
@@ -338,7 +349,7 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
         constexpr int SW = TN * 32;        // strip width (elements)
         constexpr int SLD = SW + 4;        // padded fp32 row
         float *strip = reinterpret_cast<float *>(smem) + wave * (32 * SLD);
-        static_assert(4 * 32 * SLD * sizeof(float) <= smem_bytes<BM, BN, DEPTH>(), "strip staging fits in the operand buffers");
+        static_assert(WM * WN * 32 * SLD * sizeof(float) <= smem_bytes<BM, BN, DEPTH>(), "strip staging fits in the operand buffers");
         constexpr int EPV = OUT_BF16 ? 8 : 4;            // elements per 16-byte output vector
         constexpr int VPR = SW / EPV;                    // vectors per strip row
         constexpr int RPI = 64 / VPR;                    // strip rows covered by one wave-wide store
@@ -350,7 +361,7 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     float v = acc[i][j][e];
-                    if (relu) v = v > 0.0f ? v : 0.0f;
+                    if (relu) v = fmaxf(v, 0.0f);
                     strip[(8 * (e >> 2) + (lane >> 5) * 4 + (e & 3)) * SLD + j * 32 + (lane & 31)] = v;
                 }
             // wave-private data: only this wave's own LDS writes have to land before it reads them back
@@ -364,10 +375,8 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
                 if (row < M && col < N) { // N is a multiple of EPV on this path: a vector is all in or all out
                     if constexpr (OUT_BF16) {
                         f32x4 x = *reinterpret_cast<const f32x4 *>(sp), y = *reinterpret_cast<const f32x4 *>(sp + 4);
-                        u32x4 o = {f32_to_bf16_bits(x[0]) | (f32_to_bf16_bits(x[1]) << 16),
-                                   f32_to_bf16_bits(x[2]) | (f32_to_bf16_bits(x[3]) << 16),
-                                   f32_to_bf16_bits(y[0]) | (f32_to_bf16_bits(y[1]) << 16),
-                                   f32_to_bf16_bits(y[2]) | (f32_to_bf16_bits(y[3]) << 16)};
+                        u32x4 o = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(y[0], y[1]),
+                                   pack_bf16x2(y[2], y[3])};
                         *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(Cv) + (size_t)row * ldc + col) = o;
                     } else {
                         *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(Cv) + (size_t)row * ldc + col) =
