@@ -170,6 +170,7 @@ struct ReduceParams {
     GridDev Z, B;                // scols_v in units of EV elements
     uint32_t k, nrep, nred;
     uint32_t ksplit; // partial buffers per shard (extra split of the reduction dimension inside a shard)
+    uint32_t relu;
     uint32_t piece_rows, piece_cv, pieces_c, pieces, tiles_per_piece, piece_vecs, step_rows, step_cv;
 };
 
@@ -192,7 +193,9 @@ template <int EV> struct FVec;
 template <> struct FVec<4> { using type = f32x4; };
 template <> struct FVec<1> { using type = float; };
 
-template <int EV, bool OUT_BF16, bool RELU, int U>
+// CHUNK partial buffers are read per round with all loads in flight together (the partial count is a power of two and
+// a multiple of CHUNK); lanes past the end of a piece read a clamped in-range address and store nothing.
+template <int EV, bool OUT_BF16, int U, int CHUNK>
 __global__ __launch_bounds__(kThreads) void reduce_kernel(const ReduceParams p)
 {
     using FV = typename FVec<EV>::type;
@@ -218,7 +221,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(const ReduceParams p)
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         ok[u] = idx < p.piece_vecs;
-        soff[u] = sz.base_v + (uint64_t)row * p.Z.scols_v + cv;
+        soff[u] = ok[u] ? sz.base_v + (uint64_t)row * p.Z.scols_v + cv : sz.base_v;
         doff[u] = dbase + (uint64_t)row * p.B.scols_v + cv;
 #pragma unroll
         for (int e = 0; e < EV; ++e) acc[u][e] = 0.0f;
@@ -228,29 +231,32 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(const ReduceParams p)
         if (cv >= p.piece_cv) { cv -= p.piece_cv; ++row; }
     }
     // partial sums are added in increasing partial number: a fixed order, independent of the launch shape
-    for (uint32_t qq = 0; qq < p.nred * p.ksplit; ++qq) {
-        const uint32_t q = qq / p.ksplit, c = qq - q * p.ksplit;
-        const FV *src = reinterpret_cast<const FV *>(p.part[(sz.shard | p.red_ids[q]) * p.ksplit + c]);
-        FV v[U];
+    for (uint32_t q0 = 0; q0 < p.nred * p.ksplit; q0 += CHUNK) {
+        FV v[CHUNK][U];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (ok[u]) v[u] = __builtin_nontemporal_load(src + soff[u]);
+        for (int j = 0; j < CHUNK; ++j) {
+            const uint32_t qq = q0 + j, q = qq / p.ksplit, c = qq - q * p.ksplit;
+            const FV *src = reinterpret_cast<const FV *>(p.part[(sz.shard | p.red_ids[q]) * p.ksplit + c]);
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (ok[u]) {
+            for (int u = 0; u < U; ++u) v[j][u] = __builtin_nontemporal_load(src + soff[u]);
+        }
+#pragma unroll
+        for (int j = 0; j < CHUNK; ++j)
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
                 if constexpr (EV == 4) {
-                    acc[u][0] += v[u].x; acc[u][1] += v[u].y; acc[u][2] += v[u].z; acc[u][3] += v[u].w;
+                    acc[u][0] += v[j][u].x; acc[u][1] += v[j][u].y; acc[u][2] += v[j][u].z; acc[u][3] += v[j][u].w;
                 } else {
-                    acc[u][0] += v[u];
+                    acc[u][0] += v[j][u];
                 }
             }
     }
+    if (p.relu) {
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-        if (RELU) {
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int e = 0; e < EV; ++e) acc[u][e] = acc[u][e] > 0.0f ? acc[u][e] : 0.0f;
-        }
+            for (int e = 0; e < EV; ++e) acc[u][e] = fmaxf(acc[u][e], 0.0f);
+    }
     for (uint32_t r = 0; r < p.nrep; ++r) {
         void *d = p.dst[dst0 | p.rep_ids[r]];
 #pragma unroll
@@ -395,16 +401,21 @@ tt_status launch_convert(void *const *dst, const uint8_t *Bl, const void *const 
     return TT_EINVAL;
 }
 
-template <int EV, bool OUT_BF16> static tt_status launch_reduce_e(const ReduceParams &p, uint32_t blocks, int act, int unroll, hipStream_t s)
+template <int EV, bool OUT_BF16, int U> static tt_status launch_reduce_u(const ReduceParams &p, uint32_t blocks, hipStream_t s)
 {
-    if (unroll == 4) {
-        if (act == TT_ACT_RELU) hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, true, 4>), dim3(blocks), dim3(kThreads), 0, s, p);
-        else hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, false, 4>), dim3(blocks), dim3(kThreads), 0, s, p);
-    } else {
-        if (act == TT_ACT_RELU) hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, true, 1>), dim3(blocks), dim3(kThreads), 0, s, p);
-        else hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, false, 1>), dim3(blocks), dim3(kThreads), 0, s, p);
-    }
+    const uint32_t total = p.nred * p.ksplit;
+    if (total >= 8) hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, U, 8>), dim3(blocks), dim3(kThreads), 0, s, p);
+    else if (total == 4) hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, U, 4>), dim3(blocks), dim3(kThreads), 0, s, p);
+    else if (total == 2) hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, U, 2>), dim3(blocks), dim3(kThreads), 0, s, p);
+    else hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, U, 1>), dim3(blocks), dim3(kThreads), 0, s, p);
     return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
+}
+
+template <int EV, bool OUT_BF16> static tt_status launch_reduce_e(const ReduceParams &p, uint32_t blocks, int unroll, hipStream_t s)
+{
+    // with 8 partials per round in flight one vector per lane already keeps the memory system busy
+    if (unroll == 4 && p.nred * p.ksplit < 4) return launch_reduce_u<EV, OUT_BF16, 4>(p, blocks, s);
+    return launch_reduce_u<EV, OUT_BF16, 1>(p, blocks, s);
 }
 
 tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, const float *const *partials,
@@ -444,13 +455,14 @@ tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, cons
     p.nrep = 1u << B.kX;
     p.nred = 1u << Z.kX;
     p.ksplit = (uint32_t)ksplit;
+    p.relu = act == TT_ACT_RELU;
     for (uint32_t r = 0; r < p.nrep; ++r) p.rep_ids[r] = (uint8_t)deposit(r, B.maskX, k);
     for (uint32_t q = 0; q < p.nred; ++q) p.red_ids[q] = (uint8_t)deposit(q, Z.maskX, k);
     const int64_t piece_cv = piece_cols / ev;
     uint64_t piece_vecs = (uint64_t)piece_rows * (uint64_t)piece_cv;
     if (piece_vecs >= (uint64_t(1) << 31)) return TT_EUNSUPPORTED;
     const uint64_t unique_vecs = (uint64_t)rows * (uint64_t)(cols / ev);
-    const int unroll = unique_vecs >= (uint64_t)kThreads * 4 * 256 * 4 ? 4 : 1;
+    const int unroll = (unique_vecs >= (uint64_t)kThreads * 4 * 256 * 4 && ((1u << Z.kX) * (uint32_t)ksplit) < 4) ? 4 : 1;
     p.piece_rows = (uint32_t)piece_rows;
     p.piece_cv = (uint32_t)piece_cv;
     p.pieces_c = (uint32_t)(B.scols / piece_cols);
@@ -465,10 +477,10 @@ tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, cons
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const uint64_t elems = (uint64_t)rows * (uint64_t)cols;
     ProfileScope scope(stream, TT_K_REDUCE, n, rows, cols, (int64_t)out_b, elems * 4u * p.nred * p.ksplit + elems * out_b * p.nrep, 0);
-    if (ev == 4) return out_dtype == TT_BF16 ? launch_reduce_e<4, true>(p, (uint32_t)blocks, act, unroll, s)
-                                              : launch_reduce_e<4, false>(p, (uint32_t)blocks, act, unroll, s);
-    return out_dtype == TT_BF16 ? launch_reduce_e<1, true>(p, (uint32_t)blocks, act, unroll, s)
-                                : launch_reduce_e<1, false>(p, (uint32_t)blocks, act, unroll, s);
+    if (ev == 4) return out_dtype == TT_BF16 ? launch_reduce_e<4, true>(p, (uint32_t)blocks, unroll, s)
+                                              : launch_reduce_e<4, false>(p, (uint32_t)blocks, unroll, s);
+    return out_dtype == TT_BF16 ? launch_reduce_e<1, true>(p, (uint32_t)blocks, unroll, s)
+                                : launch_reduce_e<1, false>(p, (uint32_t)blocks, unroll, s);
 }
 
 } // namespace tt
