@@ -13,6 +13,7 @@
 // No im2col buffer is ever materialised: the gather happens while operand tiles are staged into LDS.
 #include <hip/hip_runtime.h>
 #include <cstdint>
+#include <cstdlib>
 #include "gemm_core.h"
 #include "tt_internal.h"
 
@@ -166,49 +167,51 @@ template <int BM, int BN> __device__ __forceinline__ bool tile_of(const ConvPara
 }
 
 // OP 0: forward, 1: dgrad
-template <int BM, int BN, int DEPTH, bool KMASK, int OP, bool OUT_BF16, bool ONE_TAP>
-__global__ __launch_bounds__(kThreads) void conv_gather_a_kernel(const ConvParams p)
+template <int BM, int BN, int WN, int DEPTH, bool KMASK, int OP, bool OUT_BF16, bool ONE_TAP>
+__global__ __launch_bounds__(WN * 128, WN / 2) void conv_gather_a_kernel(const ConvParams p)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     TileId t;
     if (!tile_of<BM, BN>(p, &t)) return;
     const ConvGeom &g = p.g;
-    GatherKC<core::Slots<BM, true>::value, ONE_TAP> la;
+    constexpr int NT = WN * 128;
+    GatherKC<core::Slots<BM, true, NT>::value, ONE_TAP> la;
     la.base = reinterpret_cast<const char *>(p.A[t.shard]);
     la.R = g.R; la.S = g.S;
     la.rows = p.M; la.K = p.K;
     if (OP == 0) { la.IH = g.H; la.IW = g.W; la.OH = g.P; la.OW = g.Q; la.off = -g.pad; la.sgn = 1; la.Ch = g.Cs; }
     else         { la.IH = g.P; la.IW = g.Q; la.OH = g.H; la.OW = g.W; la.off = g.pad;  la.sgn = -1; la.Ch = g.Ks; }
     if constexpr (OP == 0) {
-        core::DenseKC<core::Slots<BN, true>::value> lb;
+        core::DenseKC<core::Slots<BN, true, NT>::value> lb;
         lb.base = reinterpret_cast<const char *>(p.B[t.shard]);
         lb.ld = p.K; lb.rows = p.N; lb.K = p.K;
-        core::tile_product<BM, BN, 2, 2, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
+        core::tile_product<BM, BN, 2, WN, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
     } else {
-        FilterRC<core::Slots<BN, false>::value> lb;
+        FilterRC<core::Slots<BN, false, NT>::value> lb;
         lb.base = reinterpret_cast<const char *>(p.B[t.shard]);
         lb.RS = g.R * g.S; lb.Cs = g.Cs; lb.Ks = g.Ks; lb.rows = p.N; lb.K = p.K;
-        core::tile_product<BM, BN, 2, 2, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
+        core::tile_product<BM, BN, 2, WN, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
     }
 }
 
-template <int BM, int BN, int DEPTH, bool KMASK, bool OUT_BF16>
-__global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const ConvParams p)
+template <int BM, int BN, int WN, int DEPTH, bool KMASK, bool OUT_BF16>
+__global__ __launch_bounds__(WN * 128, WN / 2) void conv_wgrad_kernel(const ConvParams p)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     TileId t;
     if (!tile_of<BM, BN>(p, &t)) return;
     const ConvGeom &g = p.g;
-    core::DenseRC<core::Slots<BM, false>::value> la; // dY shard [(n,p,q)][ko]: rows ko contiguous
+    constexpr int NT = WN * 128;
+    core::DenseRC<core::Slots<BM, false, NT>::value> la; // dY shard [(n,p,q)][ko]: rows ko contiguous
     la.base = reinterpret_cast<const char *>(p.A[t.shard]);
     la.ld = g.Ks; la.rows = p.M; la.K = p.K;
-    GatherRC<core::Slots<BN, false>::value> lb;
+    GatherRC<core::Slots<BN, false, NT>::value> lb;
     lb.base = reinterpret_cast<const char *>(p.B[t.shard]);
     lb.H = g.H; lb.W = g.W; lb.P = g.P; lb.Q = g.Q; lb.S = g.S; lb.pad = g.pad; lb.Cs = g.Cs; lb.rows = p.N; lb.K = p.K;
-    core::tile_product<BM, BN, 2, 2, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, false, smem);
+    core::tile_product<BM, BN, 2, WN, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, false, smem);
 }
 
-template <typename Kern> tt_status launch(Kern kern, size_t smem, ConvParams &p, int BM, int BN, int count, hipStream_t s)
+template <typename Kern> tt_status launch(Kern kern, size_t smem, ConvParams &p, int BM, int BN, int threads, int count, hipStream_t s)
 {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
         return TT_EDEVICE;
@@ -218,21 +221,38 @@ template <typename Kern> tt_status launch(Kern kern, size_t smem, ConvParams &p,
     if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
     p.total = (int32_t)total;
     p.per_xcd = (int32_t)((total + kXcds - 1) / kXcds);
-    hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * kXcds), dim3(kThreads), smem, s, p);
+    hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * kXcds), dim3(threads), smem, s, p);
     return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
+}
+
+// Tile choice as for the dense products: 256 x 256 with eight waves when the launch has enough tiles, else 256 x 128
+// or 128 x 128 with four waves.  TT_CONV_TILE=0|1|2 overrides (tuning aid).
+int conv_tile(int64_t M, int64_t N, int count)
+{
+    static const int forced = [] { const char *e = std::getenv("TT_CONV_TILE"); return e ? std::atoi(e) : -1; }();
+    if (forced >= 0 && forced <= 2) return forced;
+    const int64_t big = ((M + 255) / 256) * ((N + 255) / 256) * count;
+    if (M > 128 && N > 128 && big >= 128) return 2;
+    return M > 128 ? 0 : 1;
 }
 
 template <int OP, bool OUT_BF16, bool ONE_TAP> tt_status launch_gather_a_t(ConvParams &p, int count, hipStream_t s)
 {
     const bool kmask = p.K % core::BK != 0;
-    if (p.M > 128) {
+    const int tile = conv_tile(p.M, p.N, count);
+    if (tile == 2) {
+        constexpr size_t sm = core::smem_bytes<256, 256>();
+        return kmask ? launch(conv_gather_a_kernel<256, 256, 4, 1, true, OP, OUT_BF16, ONE_TAP>, sm, p, 256, 256, 512, count, s)
+                     : launch(conv_gather_a_kernel<256, 256, 4, 1, false, OP, OUT_BF16, ONE_TAP>, sm, p, 256, 256, 512, count, s);
+    }
+    if (tile == 0) {
         constexpr size_t sm = core::smem_bytes<256, 128>();
-        return kmask ? launch(conv_gather_a_kernel<256, 128, 2, true, OP, OUT_BF16, ONE_TAP>, sm, p, 256, 128, count, s)
-                     : launch(conv_gather_a_kernel<256, 128, 2, false, OP, OUT_BF16, ONE_TAP>, sm, p, 256, 128, count, s);
+        return kmask ? launch(conv_gather_a_kernel<256, 128, 2, 2, true, OP, OUT_BF16, ONE_TAP>, sm, p, 256, 128, 256, count, s)
+                     : launch(conv_gather_a_kernel<256, 128, 2, 2, false, OP, OUT_BF16, ONE_TAP>, sm, p, 256, 128, 256, count, s);
     }
     constexpr size_t sm = core::smem_bytes<128, 128>();
-    return kmask ? launch(conv_gather_a_kernel<128, 128, 1, true, OP, OUT_BF16, ONE_TAP>, sm, p, 128, 128, count, s)
-                 : launch(conv_gather_a_kernel<128, 128, 1, false, OP, OUT_BF16, ONE_TAP>, sm, p, 128, 128, count, s);
+    return kmask ? launch(conv_gather_a_kernel<128, 128, 2, 1, true, OP, OUT_BF16, ONE_TAP>, sm, p, 128, 128, 256, count, s)
+                 : launch(conv_gather_a_kernel<128, 128, 2, 1, false, OP, OUT_BF16, ONE_TAP>, sm, p, 128, 128, 256, count, s);
 }
 
 template <int OP, bool OUT_BF16> tt_status launch_gather_a(ConvParams &p, int count, hipStream_t s)
@@ -245,14 +265,22 @@ template <int OP, bool OUT_BF16> tt_status launch_gather_a(ConvParams &p, int co
 template <bool OUT_BF16> tt_status launch_wgrad(ConvParams &p, int count, hipStream_t s)
 {
     const bool kmask = p.K % core::BK != 0;
-    if (p.M > 128) {
+    // the pixel-walking gather of the weight gradient measured slower with the eight-wave tile: keep four waves
+    int tile = conv_tile(p.M, p.N, count);
+    if (tile == 2 && !std::getenv("TT_CONV_TILE")) tile = 0;
+    if (tile == 2) {
+        constexpr size_t sm = core::smem_bytes<256, 256>();
+        return kmask ? launch(conv_wgrad_kernel<256, 256, 4, 1, true, OUT_BF16>, sm, p, 256, 256, 512, count, s)
+                     : launch(conv_wgrad_kernel<256, 256, 4, 1, false, OUT_BF16>, sm, p, 256, 256, 512, count, s);
+    }
+    if (tile == 0) {
         constexpr size_t sm = core::smem_bytes<256, 128>();
-        return kmask ? launch(conv_wgrad_kernel<256, 128, 2, true, OUT_BF16>, sm, p, 256, 128, count, s)
-                     : launch(conv_wgrad_kernel<256, 128, 2, false, OUT_BF16>, sm, p, 256, 128, count, s);
+        return kmask ? launch(conv_wgrad_kernel<256, 128, 2, 2, true, OUT_BF16>, sm, p, 256, 128, 256, count, s)
+                     : launch(conv_wgrad_kernel<256, 128, 2, 2, false, OUT_BF16>, sm, p, 256, 128, 256, count, s);
     }
     constexpr size_t sm = core::smem_bytes<128, 128>();
-    return kmask ? launch(conv_wgrad_kernel<128, 128, 1, true, OUT_BF16>, sm, p, 128, 128, count, s)
-                 : launch(conv_wgrad_kernel<128, 128, 1, false, OUT_BF16>, sm, p, 128, 128, count, s);
+    return kmask ? launch(conv_wgrad_kernel<128, 128, 2, 1, true, OUT_BF16>, sm, p, 128, 128, 256, count, s)
+                 : launch(conv_wgrad_kernel<128, 128, 2, 1, false, OUT_BF16>, sm, p, 128, 128, 256, count, s);
 }
 
 bool aligned16(const void *const *ptrs, int n)
