@@ -138,7 +138,7 @@ inline int pick_ksplit(int64_t M, int64_t N, int64_t K, int count, int dtype, bo
     }
     const int64_t blocks = ((M + 255) / 256) * ((N + 255) / 256) * count; // 256 x 256 tiles, one per CU
     int s = 1;
-    while (blocks * s < 256 && s < 8 && K / (2 * s) >= 512 && count * 2 * s <= kMaxShards) s *= 2;
+    while (blocks * s < 200 && s < 8 && K / (2 * s) >= 512 && count * 2 * s <= kMaxShards) s *= 2;
     return s;
 }
 
