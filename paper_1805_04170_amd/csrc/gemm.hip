@@ -8,6 +8,7 @@
 #include <cstdlib>
 #include <type_traits>
 #include "gemm_core.h"
+#include "gemm_core2.h"
 #include "tt_internal.h"
 
 namespace tt {
@@ -55,6 +56,50 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN / 4) * (DEPTH == 0 ? (BM == 
     lb.base = reinterpret_cast<const char *>(p.B[shard]) + (size_t)kbeg * (B_KC ? 2 : 2 * (size_t)p.ldb);
     lb.ld = p.ldb; lb.rows = p.N; lb.K = klen;
     core::tile_product<BM, BN, WM, WN, DEPTH, KMASK, OUT_BF16, VEC>(la, lb, p.C[vshard], p.ldc, p.M, p.N, klen, tm * BM, tn * BN, p.relu != 0, smem);
+}
+
+// second engine: operand tiles loaded straight into LDS, 256 x 256 tiles, eight waves
+template <bool A_KC, bool B_KC, bool OUT_BF16, bool VEC>
+__global__ __launch_bounds__(core2::kThreads2, 2) void gemm_bf16_v2_kernel(const GemmParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem2[];
+    const int logical = core::logical_block(p.per_xcd, p.total);
+    if (logical < 0) return;
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int vshard = logical / tiles;
+    const int t = logical - vshard * tiles;
+    const int tm = t % p.tiles_m, tn = t / p.tiles_m;
+    const int shard = vshard / p.ksplit;
+    const int kbeg = (vshard - shard * p.ksplit) * p.kchunk;
+    const int klen = p.K - kbeg < p.kchunk ? p.K - kbeg : p.kchunk;
+    using LA = std::conditional_t<A_KC, core2::DenseKC2, core2::DenseRC2>;
+    using LB = std::conditional_t<B_KC, core2::DenseKC2, core2::DenseRC2>;
+    LA la;
+    la.base = reinterpret_cast<const char *>(p.A[shard]) + (size_t)kbeg * (A_KC ? 2 : 2 * (size_t)p.lda);
+    la.ld = p.lda; la.rows = p.M; la.K = klen;
+    LB lb;
+    lb.base = reinterpret_cast<const char *>(p.B[shard]) + (size_t)kbeg * (B_KC ? 2 : 2 * (size_t)p.ldb);
+    lb.ld = p.ldb; lb.rows = p.N; lb.K = klen;
+    core2::tile_product2<OUT_BF16, VEC>(la, lb, p.C[vshard], p.ldc, p.M, p.N, klen, tm * 256, tn * 256, p.relu != 0, smem2);
+}
+
+template <bool A_KC, bool B_KC, bool OUT_BF16, bool VEC> tt_status launch_v2(GemmParams &p, int count, hipStream_t s)
+{
+    auto kern = gemm_bf16_v2_kernel<A_KC, B_KC, OUT_BF16, VEC>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)core2::kSmemBytes) != hipSuccess)
+            return TT_EDEVICE;
+        configured = true;
+    }
+    p.tiles_m = (p.M + 255) / 256;
+    p.tiles_n = (p.N + 255) / 256;
+    int64_t total = (int64_t)p.tiles_m * p.tiles_n * count * p.ksplit;
+    if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
+    p.total = (int32_t)total;
+    p.per_xcd = (int32_t)((total + kXcds - 1) / kXcds);
+    hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * kXcds), dim3(core2::kThreads2), core2::kSmemBytes, s, p);
+    return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
 }
 
 // ---------------------------------------------------------------- generic kernel (fp32, or any unaligned shape)
@@ -162,7 +207,7 @@ tt_status launch_mfma_cfg(GemmParams &p, int count, hipStream_t s)
 int pick_tile(int64_t M, int64_t N, int64_t K, int count)
 {
     static const int forced = [] { const char *e = std::getenv("TT_GEMM_TILE"); return e ? std::atoi(e) : -1; }();
-    if (forced >= 0 && forced <= 5) return forced;
+    if ((forced >= 0 && forced <= 5) || forced == 8) return forced;
     const int64_t big = ((M + 255) / 256) * ((N + 255) / 256) * count;
     if (M > 128 && N > 128 && big >= 128) return 5;
     return (M > 128 && K >= 1024) ? 0 : 1;
@@ -181,6 +226,8 @@ template <bool KMASK, bool A_KC, bool B_KC, bool OUT_BF16, bool VEC> tt_status l
 
 template <bool A_KC, bool B_KC, bool OUT_BF16, bool VEC> tt_status launch_mfma_kmask(GemmParams &p, int count, hipStream_t s)
 {
+    if (pick_tile(p.M, p.N, p.ksplit > 1 ? p.kchunk : p.K, count * p.ksplit) == 8 && p.M >= 8 && p.N >= 8)
+        return launch_v2<A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
     return p.K % core::BK ? launch_mfma_tile<true, A_KC, B_KC, OUT_BF16, VEC>(p, count, s)
                           : launch_mfma_tile<false, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
 }
