@@ -204,6 +204,7 @@ tt_status launch_mfma_cfg(GemmParams &p, int count, hipStream_t s)
 //   0: 256 x 128, four waves, two K tiles prefetched in registers: long K loops with few column tiles.
 //   1: 128 x 128, four waves, up to two workgroups per CU: small products and short K loops.
 //   2, 3, 4: 256 x 256 four-wave, 256 x 128 and 128 x 128 single-LDS-buffer variants kept for experiments.
+//   8: 256 x 256, eight waves, second engine (gemm_core2.h): tiles loaded straight into LDS.
 int pick_tile(int64_t M, int64_t N, int64_t K, int count)
 {
     static const int forced = [] { const char *e = std::getenv("TT_GEMM_TILE"); return e ? std::atoi(e) : -1; }();
@@ -226,7 +227,11 @@ template <bool KMASK, bool A_KC, bool B_KC, bool OUT_BF16, bool VEC> tt_status l
 
 template <bool A_KC, bool B_KC, bool OUT_BF16, bool VEC> tt_status launch_mfma_kmask(GemmParams &p, int count, hipStream_t s)
 {
-    if (pick_tile(p.M, p.N, p.ksplit > 1 ? p.kchunk : p.K, count * p.ksplit) == 8 && p.M >= 8 && p.N >= 8)
+    // Where the eight-wave 256 x 256 tile is chosen, the engine that loads tiles straight into LDS measured faster for
+    // every layout but NN (A K-contiguous, B row-contiguous), which stays on the register-staged engine.
+    const int tile = pick_tile(p.M, p.N, p.ksplit > 1 ? p.kchunk : p.K, count * p.ksplit);
+    const bool nn = A_KC && !B_KC;
+    if ((tile == 8 || (tile == 5 && !nn && !std::getenv("TT_GEMM_TILE"))) && p.M >= 8 && p.N >= 8)
         return launch_v2<A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
     return p.K % core::BK ? launch_mfma_tile<true, A_KC, B_KC, OUT_BF16, VEC>(p, count, s)
                           : launch_mfma_tile<false, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
