@@ -75,6 +75,13 @@ def test_fp32(ta, tb):
     check(2, 70, 130, 65, ta, tb, "f32", "f32", True, 38)
 
 
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_bf16_large_launch_eight_wave_tiles(ta, tb):
+    # enough 256 x 256 tiles for the eight-wave kernels (both tile engines, chosen by layout), ragged M, N and K
+    check(8, 1000, 1016, 200, ta, tb, "bf16", "bf16", True, 39)
+    check(8, 1024, 1024, 192, ta, tb, "bf16", "f32", False, 40)
+
+
 def test_k_zero_and_empty():
     C = [torch.full((8, 8), 5.0, dtype=torch.float32, device=DEV)]
     A = [torch.zeros((8, 1), dtype=torch.bfloat16, device=DEV)]
