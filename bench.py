@@ -308,6 +308,16 @@ def main():
                 "TFLOPs": (a["flops"] / (a["ms"] / a["launches"] * 1e-3) / 1e12) if a["flops"] else None,
                 "GBps": a["bytes"] / (a["ms"] / a["launches"] * 1e-3) / 1e9} for a in agg]
 
+    # partial-sum reduce headline: the reduction launch that moves the most bytes in this step
+    red = [a for a in agg if a["kernel"] == "reduce"]
+    reduce_line = None
+    if red:
+        rb = max(red, key=lambda a: a["bytes"])
+        rb_ms = rb["ms"] / rb["launches"]
+        reduce_line = {"rows": rb["d0"], "cols": rb["d1"], "bytes": rb["bytes"], "avg_ms": rb_ms,
+                       "GBps": rb["bytes"] / (rb_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                       "frac": rb["bytes"] / (rb_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+
     # retile headline: the largest tensor of the workload between two non-replicated tilings
     rows, cols = (cfg.widths[0], cfg.widths[1]) if not is_conv else (cfg.K * cfg.R * cfg.S, cfg.C)
     ka = cfg.k
@@ -320,12 +330,18 @@ def main():
     dst = [torch.zeros((sr, sc), dtype=tdt, device="cuda:0") for _ in range(1 << ka)]
     for _ in range(3):
         tt.tt_retile(dst, B, src, A, rows, cols, esz)
-    tt.tt_profile_begin()
-    for _ in range(20):
+    # back-to-back launches between one pair of HIP events on the launch stream
+    n_rt = 50
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(n_rt):
         tt.tt_retile(dst, B, src, A, rows, cols, esz)
-    rrec = tt.tt_profile_end()
-    r_ms = sum(r["ms"] for r in rrec) / len(rrec)
-    r_gbs = rrec[0]["bytes"] / (r_ms * 1e-3) / 1e9
+    ev1.record()
+    torch.cuda.synchronize()
+    r_ms = ev0.elapsed_time(ev1) / n_rt
+    r_bytes = 2 * rows * cols * esz
+    r_gbs = r_bytes / (r_ms * 1e-3) / 1e9
+    rrec = [{"bytes": r_bytes}]
     retile = {"tensor": "W_1 %dx%d %s" % (rows, cols, cfg.dtype), "from": A, "to": B, "bytes": rrec[0]["bytes"],
               "avg_ms": r_ms, "GBps": r_gbs, "peak": PEAK_HBM_GBS, "frac": r_gbs / PEAK_HBM_GBS}
     del src, dst
@@ -345,6 +361,7 @@ def main():
         "frac_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "roofline": roofline,
         "retile": retile,
+        "reduce": reduce_line,
         "breakdown_ms_per_step": {"products": gemm_ms, "conversions_and_reductions": conv_ms},
         "kernels": kernels,
     }
