@@ -377,10 +377,10 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
                         f32x4 x = *reinterpret_cast<const f32x4 *>(sp), y = *reinterpret_cast<const f32x4 *>(sp + 4);
                         u32x4 o = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(y[0], y[1]),
                                    pack_bf16x2(y[2], y[3])};
-                        *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(Cv) + (size_t)row * ldc + col) = o;
+                        __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(Cv) + (size_t)row * ldc + col));
                     } else {
-                        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(Cv) + (size_t)row * ldc + col) =
-                            *reinterpret_cast<const f32x4 *>(sp);
+                        __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(sp),
+                                                    reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(Cv) + (size_t)row * ldc + col));
                     }
                 }
             }
