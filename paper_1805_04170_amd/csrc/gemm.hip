@@ -41,7 +41,8 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN / 4) * (DEPTH == 0 ? (BM == 
     const int tiles = p.tiles_m * p.tiles_n;
     const int vshard = logical / tiles;
     const int t = logical - vshard * tiles;
-    const int tm = t % p.tiles_m, tn = t / p.tiles_m;
+    int tm, tn;
+    core::grouped_tile(t, p.tiles_m, p.tiles_n, &tm, &tn);
     const int shard = vshard / p.ksplit;
     const int kbeg = (vshard - shard * p.ksplit) * p.kchunk;
     const int klen = p.K - kbeg < p.kchunk ? p.K - kbeg : p.kchunk;
@@ -68,7 +69,8 @@ __global__ __launch_bounds__(core2::kThreads2, 2) void gemm_bf16_v2_kernel(const
     const int tiles = p.tiles_m * p.tiles_n;
     const int vshard = logical / tiles;
     const int t = logical - vshard * tiles;
-    const int tm = t % p.tiles_m, tn = t / p.tiles_m;
+    int tm, tn;
+    core::grouped_tile(t, p.tiles_m, p.tiles_n, &tm, &tn);
     const int shard = vshard / p.ksplit;
     const int kbeg = (vshard - shard * p.ksplit) * p.kchunk;
     const int klen = p.K - kbeg < p.kchunk ? p.K - kbeg : p.kchunk;

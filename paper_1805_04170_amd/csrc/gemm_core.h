@@ -399,5 +399,19 @@ __device__ __forceinline__ int logical_block(int per_xcd, int total)
     return logical < total ? logical : -1;
 }
 
+// Tile order inside one shard: column tiles are taken in groups of four; inside a group the row tiles run slowest and
+// the group's columns fastest.  Workgroups that run at the same time then share a few column tiles of B and a few row
+// tiles of A, and the A tiles are still in L2 when the next column group comes round.
+__device__ __forceinline__ void grouped_tile(int t, int tiles_m, int tiles_n, int *tm, int *tn)
+{
+    constexpr int G = 4;
+    const int per_group = tiles_m * G;
+    const int g = t / per_group;
+    const int r = t - g * per_group;
+    const int width = tiles_n - g * G < G ? tiles_n - g * G : G;
+    *tm = r / width;
+    *tn = g * G + (r - *tm * width);
+}
+
 } // namespace core
 } // namespace tt
