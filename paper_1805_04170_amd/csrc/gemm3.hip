@@ -1,0 +1,97 @@
+// Shard products on the persistent, software-pipelined MFMA engine (gemm_core3.h): kernels and launcher.
+// One launch covers all shards (Sec. 5.2 step 2 of arXiv 1805.04170: every device runs the same sub-operator on its
+// own tiles); the grid is one workgroup per CU and each workgroup walks its share of the 256 x 256 output tiles.
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include <cstdlib>
+#include "gemm_core3.h"
+#include "tt_internal.h"
+
+namespace tt {
+namespace {
+
+template <int BK, int NS, bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED>
+__global__ __launch_bounds__(core3::kThreads3, 2) void gemm_bf16_v3_kernel(const core3::Params3 p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem3[];
+    core3::run_tiles<BK, NS, A_KC, B_KC, OUT_BF16, STAGED>(p, smem3);
+}
+
+int cu_count()
+{
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+        return cus;
+    }();
+    return n;
+}
+
+template <int BK, int NS, bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED>
+tt_status launch_cfg(core3::Params3 &p, hipStream_t s)
+{
+    auto kern = gemm_bf16_v3_kernel<BK, NS, A_KC, B_KC, OUT_BF16, STAGED>;
+    constexpr size_t smem = core3::smem_bytes3<BK, NS, STAGED>();
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return TT_EDEVICE;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((uint32_t)p.wg_per_xcd * core::kXcds), dim3(core3::kThreads3), smem, s, p);
+    return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
+}
+
+template <bool A_KC, bool B_KC> tt_status launch_layout(core3::Params3 &p, int out_dtype, bool vec, hipStream_t s)
+{
+    // bf16 results with 16-byte rows: staged epilogue (ring + 18 KB).  Everything else (fp32 partial sums, odd pitches)
+    // stores element-wise from registers.  Ring: two stages of 64 (TT_V3_RING=324: four stages of 32; tuning aid).
+    static const int ring = [] { const char *e = std::getenv("TT_V3_RING"); return e ? std::atoi(e) : 642; }();
+    const bool bf = out_dtype == TT_BF16;
+    if (ring == 324) {
+        if (bf && vec) return launch_cfg<32, 4, A_KC, B_KC, true, true>(p, s);
+        return bf ? launch_cfg<32, 4, A_KC, B_KC, true, false>(p, s) : launch_cfg<32, 4, A_KC, B_KC, false, false>(p, s);
+    }
+    if (bf && vec) return launch_cfg<64, 2, A_KC, B_KC, true, true>(p, s);
+    return bf ? launch_cfg<64, 2, A_KC, B_KC, true, false>(p, s) : launch_cfg<64, 2, A_KC, B_KC, false, false>(p, s);
+}
+
+} // namespace
+
+tt_status launch_gemm_v3(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
+                         int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool a_kc, bool b_kc, int out_dtype, int relu,
+                         bool vec, int ksplit, int64_t kchunk, void *stream)
+{
+    // what the kernel assumes
+    if (K <= 0 || K % 64 || (ksplit > 1 && kchunk % 64) || M < 8 || N < 8) return TT_EUNSUPPORTED;
+    if (count * ksplit > 64 || count < 1) return TT_EUNSUPPORTED;
+    if ((!a_kc && M % 8) || (!b_kc && N % 8)) return TT_EUNSUPPORTED;
+    if (M * K >= (int64_t(1) << 31) || K * N >= (int64_t(1) << 31)) return TT_EUNSUPPORTED; // 32-bit byte offsets
+    core3::Params3 p;
+    for (int i = 0; i < 64; ++i) {
+        p.A[i] = i < count ? A[i] : nullptr;
+        p.B[i] = i < count ? B[i] : nullptr;
+        p.C[i] = i < count * ksplit ? C[i] : nullptr;
+    }
+    p.M = (int32_t)M; p.N = (int32_t)N; p.K = (int32_t)K;
+    p.lda = (int32_t)lda; p.ldb = (int32_t)ldb; p.ldc = (int32_t)ldc;
+    p.tiles_m = (int32_t)((M + core3::BM3 - 1) / core3::BM3);
+    p.tiles_n = (int32_t)((N + core3::BN3 - 1) / core3::BN3);
+    const int64_t total = (int64_t)p.tiles_m * p.tiles_n * count * ksplit;
+    if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
+    p.total = (int32_t)total;
+    p.per_xcd = (int32_t)((total + core::kXcds - 1) / core::kXcds);
+    const int per_xcd_cus = cu_count() / core::kXcds > 0 ? cu_count() / core::kXcds : 1;
+    p.wg_per_xcd = p.per_xcd < per_xcd_cus ? p.per_xcd : per_xcd_cus;
+    p.relu = relu;
+    p.ksplit = ksplit;
+    p.kchunk = (int32_t)(ksplit > 1 ? kchunk : K);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (a_kc && b_kc) return launch_layout<true, true>(p, out_dtype, vec, s);
+    if (a_kc && !b_kc) return launch_layout<true, false>(p, out_dtype, vec, s);
+    if (!a_kc && !b_kc) return launch_layout<false, false>(p, out_dtype, vec, s);
+    return launch_layout<false, true>(p, out_dtype, vec, s);
+}
+
+} // namespace tt

@@ -62,9 +62,14 @@ struct DenseRC2 {
 
 __device__ __forceinline__ void load_chunk_to_lds(const void *g, char *lds_wave_base)
 {
-    // every lane supplies its own global address; the 64 chunks land at lds_wave_base + lane * 16
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+    // Every lane supplies its own global address; the 64 chunks land at lds_wave_base + lane * 16 (M0 holds the
+    // wave-uniform LDS base).  Written as inline assembly on purpose: for the builtin form the compiler's wait-count
+    // pass assumes that any later LDS read may alias the incoming data and puts s_waitcnt vmcnt(0) in front of the next
+    // fragment read, which turns the prefetch of tile kt+1 into a blocking load.  Here the waits are the explicit
+    // s_waitcnt vmcnt(..) + barrier pairs of the main loop.  (s_nop: one wait state between the write of M0 and its use.)
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_wave_base);
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "{m0}"(lds_addr), "v"(g) : "memory");
 }
 
 // issue the loads of one operand tile (ROWS x 64) into lds

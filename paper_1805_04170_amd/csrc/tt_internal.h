@@ -113,6 +113,12 @@ tt_status launch_gemm(int count, const void *const *A, const void *const *B, voi
                       int64_t K, int trans_a, int trans_b, int in_dtype, int out_dtype, int act, int ksplit,
                       void *stream);
 
+// Persistent software-pipelined MFMA engine (gemm3.hip); bf16 operands.  a_kc / b_kc: the operand's rows (m / n) have
+// K contiguous.  TT_EUNSUPPORTED when the shape does not meet the kernel's assumptions (the caller falls back).
+tt_status launch_gemm_v3(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
+                         int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool a_kc, bool b_kc, int out_dtype, int relu,
+                         bool vec, int ksplit, int64_t kchunk, void *stream);
+
 // Convolution shard products (conv.hip).  op TT_OP_FWD: A = X shards, B = filter shards, C = Y shards;
 // TT_OP_DGRAD: A = dY, B = filters, C = dX;  TT_OP_WGRAD: A = dY, B = X, C = dW.  Ns images, Cs input channels and
 // Ks output channels per shard; bf16 operands.

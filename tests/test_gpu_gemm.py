@@ -82,6 +82,16 @@ def test_bf16_large_launch_eight_wave_tiles(ta, tb):
     check(8, 1024, 1024, 192, ta, tb, "bf16", "f32", False, 40)
 
 
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+@pytest.mark.parametrize("out_dt", ["bf16", "f32"])
+def test_bf16_persistent_engine(ta, tb, out_dt):
+    # K a multiple of 64 and more 256 x 256 tiles than CUs: the persistent pipelined engine, several output tiles per
+    # workgroup (prefetch runs across tile boundaries), ragged M and N, K loops of one, two and five tiles
+    check(8, 1544, 1528, 128, ta, tb, "bf16", out_dt, True, 42)
+    check(8, 1032, 1544, 64, ta, tb, "bf16", out_dt, False, 43)
+    check(3, 2056, 1800, 320, ta, tb, "bf16", out_dt, False, 44)
+
+
 def test_k_zero_and_empty():
     C = [torch.full((8, 8), 5.0, dtype=torch.float32, device=DEV)]
     A = [torch.zeros((8, 1), dtype=torch.bfloat16, device=DEV)]
