@@ -5,6 +5,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include "gemm_core3.h"
+#include "gemm_core4.h"
 #include "tt_internal.h"
 
 namespace tt {
@@ -15,6 +16,47 @@ __global__ __launch_bounds__(core3::kThreads3, 2) void gemm_bf16_v3_kernel(const
 {
     extern __shared__ __attribute__((aligned(16))) char smem3[];
     core3::run_tiles<BK, NS, A_KC, B_KC, OUT_BF16, STAGED>(p, smem3);
+}
+
+// 256 x 128 tiles, four waves, two workgroups per CU (gemm_core4.h); one tile per workgroup
+template <bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED>
+__global__ __launch_bounds__(core4::kThreads4, 2) void gemm_bf16_v4_kernel(const core3::Params3 p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem4[];
+    const int logical = core::logical_block(p.per_xcd, p.total);
+    if (logical < 0) return;
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int vshard = logical / tiles;
+    const int t = logical - vshard * tiles;
+    int tm, tn;
+    core::grouped_tile(t, p.tiles_m, p.tiles_n, &tm, &tn);
+    const int shard = vshard / p.ksplit;
+    const int kbeg = (vshard - shard * p.ksplit) * p.kchunk;
+    const int klen = p.K - kbeg < p.kchunk ? p.K - kbeg : p.kchunk;
+    const char *abase = reinterpret_cast<const char *>(p.A[shard]) + (size_t)kbeg * (A_KC ? 2 : 2 * (size_t)p.lda);
+    const char *bbase = reinterpret_cast<const char *>(p.B[shard]) + (size_t)kbeg * (B_KC ? 2 : 2 * (size_t)p.ldb);
+    core4::tile_product4<A_KC, B_KC, OUT_BF16, STAGED>(abase, p.lda, bbase, p.ldb, p.C[vshard], p.ldc, p.M, p.N, klen,
+                                                       tm * core4::BM4, tn * core4::BN4, p.relu != 0, smem4);
+}
+
+template <bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED> tt_status launch_cfg4(core3::Params3 &p, hipStream_t s)
+{
+    auto kern = gemm_bf16_v4_kernel<A_KC, B_KC, OUT_BF16, STAGED>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)core4::kSmem4) != hipSuccess)
+            return TT_EDEVICE;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * core::kXcds), dim3(core4::kThreads4), core4::kSmem4, s, p);
+    return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
+}
+
+template <bool A_KC, bool B_KC> tt_status launch_layout4(core3::Params3 &p, int out_dtype, bool vec, hipStream_t s)
+{
+    const bool bf = out_dtype == TT_BF16;
+    if (bf && vec) return launch_cfg4<A_KC, B_KC, true, true>(p, s);
+    return bf ? launch_cfg4<A_KC, B_KC, true, false>(p, s) : launch_cfg4<A_KC, B_KC, false, false>(p, s);
 }
 
 int cu_count()
@@ -58,6 +100,40 @@ template <bool A_KC, bool B_KC> tt_status launch_layout(core3::Params3 &p, int o
 }
 
 } // namespace
+
+tt_status launch_gemm_v4(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
+                         int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool a_kc, bool b_kc, int out_dtype, int relu,
+                         bool vec, int ksplit, int64_t kchunk, void *stream)
+{
+    // what the kernel assumes
+    if (K <= 0 || K % core4::BK4 || (ksplit > 1 && kchunk % core4::BK4) || M < 8 || N < 8) return TT_EUNSUPPORTED;
+    if (count * ksplit > 64 || count < 1) return TT_EUNSUPPORTED;
+    if ((!a_kc && M % 8) || (!b_kc && N % 8)) return TT_EUNSUPPORTED;
+    if (M * K >= (int64_t(1) << 31) || K * N >= (int64_t(1) << 31)) return TT_EUNSUPPORTED; // 32-bit byte offsets
+    core3::Params3 p;
+    for (int i = 0; i < 64; ++i) {
+        p.A[i] = i < count ? A[i] : nullptr;
+        p.B[i] = i < count ? B[i] : nullptr;
+        p.C[i] = i < count * ksplit ? C[i] : nullptr;
+    }
+    p.M = (int32_t)M; p.N = (int32_t)N; p.K = (int32_t)K;
+    p.lda = (int32_t)lda; p.ldb = (int32_t)ldb; p.ldc = (int32_t)ldc;
+    p.tiles_m = (int32_t)((M + core4::BM4 - 1) / core4::BM4);
+    p.tiles_n = (int32_t)((N + core4::BN4 - 1) / core4::BN4);
+    const int64_t total = (int64_t)p.tiles_m * p.tiles_n * count * ksplit;
+    if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
+    p.total = (int32_t)total;
+    p.per_xcd = (int32_t)((total + core::kXcds - 1) / core::kXcds);
+    p.wg_per_xcd = p.per_xcd;
+    p.relu = relu;
+    p.ksplit = ksplit;
+    p.kchunk = (int32_t)(ksplit > 1 ? kchunk : K);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (a_kc && b_kc) return launch_layout4<true, true>(p, out_dtype, vec, s);
+    if (a_kc && !b_kc) return launch_layout4<true, false>(p, out_dtype, vec, s);
+    if (!a_kc && !b_kc) return launch_layout4<false, false>(p, out_dtype, vec, s);
+    return launch_layout4<false, true>(p, out_dtype, vec, s);
+}
 
 tt_status launch_gemm_v3(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
                          int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool a_kc, bool b_kc, int out_dtype, int relu,

@@ -119,6 +119,11 @@ tt_status launch_gemm_v3(int count, const void *const *A, const void *const *B, 
                          int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool a_kc, bool b_kc, int out_dtype, int relu,
                          bool vec, int ksplit, int64_t kchunk, void *stream);
 
+// Same contract for the 256 x 128 engine with two workgroups per CU (gemm_core4.h); K a multiple of 32.
+tt_status launch_gemm_v4(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
+                         int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool a_kc, bool b_kc, int out_dtype, int relu,
+                         bool vec, int ksplit, int64_t kchunk, void *stream);
+
 // Convolution shard products (conv.hip).  op TT_OP_FWD: A = X shards, B = filter shards, C = Y shards;
 // TT_OP_DGRAD: A = dY, B = filters, C = dX;  TT_OP_WGRAD: A = dY, B = X, C = dW.  Ns images, Cs input channels and
 // Ks output channels per shard; bf16 operands.

@@ -92,6 +92,16 @@ def test_bf16_persistent_engine(ta, tb, out_dt):
     check(3, 2056, 1800, 320, ta, tb, "bf16", out_dt, False, 44)
 
 
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+@pytest.mark.parametrize("out_dt", ["bf16", "f32"])
+def test_bf16_two_workgroups_per_cu_engine(ta, tb, out_dt):
+    # launches with few 256 x 256 tiles, K a multiple of 32: the 256 x 128 engine (three-stage ring of 32-deep K tiles);
+    # ragged M and N, K loops of 3 (the ring is deeper than one of the loops is long) and 16 tiles
+    check(2, 520, 520, 96, ta, tb, "bf16", out_dt, True, 45)
+    check(8, 256, 1024, 512, ta, tb, "bf16", out_dt, False, 46)
+    check(1, 136, 264, 32, ta, tb, "bf16", out_dt, False, 47)
+
+
 def test_k_zero_and_empty():
     C = [torch.full((8, 8), 5.0, dtype=torch.float32, device=DEV)]
     A = [torch.zeros((8, 1), dtype=torch.bfloat16, device=DEV)]
