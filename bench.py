@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--conv-split", default="planner", choices=["planner", "batch", "out_channel"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
+    ap.add_argument("--overlap", action="store_true",
+                    help="weight-gradient products on a second stream (tt_fc_backward_overlapped); default: one stream, "
+                         "which measured faster on the batch-256 workloads, whose large products are all bound by HBM")
     return ap.parse_args()
 
 
@@ -99,6 +102,7 @@ class Chain:
                                                       f[1], f[2]))
         self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
         self.ws_bytes = need
+        self.aux = None  # second stream for the weight-gradient products (set by main unless --no-overlap)
 
     def step(self):
         tt = self.tt
@@ -106,9 +110,10 @@ class Chain:
             tt.tt_fc_forward(self.layers[l - 1], self.b, self.k, self.dt, self.tx[l - 1], self.tw[l - 1], self.tx[l],
                              self.forms[l - 1][0], self.x[l - 1], self.W[l - 1], self.x[l], self.ws)
         for l in range(self.L, 0, -1):
-            tt.tt_fc_backward(self.layers[l - 1], self.b, self.k, self.dt, self.tx[l - 1], self.tw[l - 1], self.tx[l],
-                              self.tg[l], self.tg[l - 1], self.forms[l - 1][1], self.forms[l - 1][2], self.x[l - 1],
-                              self.W[l - 1], self.x[l], self.g[l], self.g[l - 1], self.dW[l - 1], self.ws)
+            tt.tt_fc_backward_overlapped(self.layers[l - 1], self.b, self.k, self.dt, self.tx[l - 1], self.tw[l - 1],
+                                         self.tx[l], self.tg[l], self.tg[l - 1], self.forms[l - 1][1],
+                                         self.forms[l - 1][2], self.x[l - 1], self.W[l - 1], self.x[l], self.g[l],
+                                         self.g[l - 1], self.dW[l - 1], self.ws, aux_stream=self.aux)
 
 
 class ConvLayerBench:
@@ -258,6 +263,8 @@ def main():
     else:
         chain = Chain(cfg, tt, torch)
     K, W = args.steps, args.warmup
+    if not is_conv and args.overlap:
+        chain.aux = torch.cuda.Stream()
 
     for _ in range(max(W, 1)):
         chain.step()
@@ -282,7 +289,9 @@ def main():
     ms_per_step = elapsed * 1e3 / K
     tflops = cfg.flops() / (elapsed / K) / 1e12
 
-    # per-kernel durations: eager pass, HIP events around every launch on the launch stream
+    # per-kernel durations: eager pass on ONE stream (so that durations do not overlap), HIP events around every launch
+    if not is_conv:
+        chain.aux = None
     tt.tt_profile_begin()
     for _ in range(K):
         chain.step()
@@ -357,7 +366,8 @@ def main():
             "%s: N=%d C=%d K=%d %dx%d %dx%d pad %d, k=%d (%d shards), %s split" % (
                 cfg.name, cfg.N, cfg.C, cfg.K, cfg.H, cfg.W, cfg.R, cfg.S, cfg.pad, cfg.k, 1 << cfg.k, args.conv_split)),
             "tiling_x": chain.tx, "tiling_g": chain.tg, "tiling_w": chain.tw, "plan_cost_elems": chain.plan_cost,
-            "timed": "hip graph replay" if graph is not None else "eager launches"},
+            "timed": "hip graph replay" if graph is not None else "eager launches",
+            "streams": 2 if (not is_conv and args.overlap) else 1},
         "frac_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "roofline": roofline,
         "retile": retile,

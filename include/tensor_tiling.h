@@ -186,6 +186,18 @@ tt_status tt_fc_backward(const tt_layer *layer, int64_t batch, int k, int dtype,
                          const void *const *Y, const void *const *dY, void *const *dX, void *const *dW,
                          void *workspace, size_t ws_bytes, void *stream);
 
+/* tt_fc_backward with the two products overlapped: the weight-gradient product (with its conversions) is enqueued
+ * on aux_stream once G exists and runs beside the dX product on stream; the call makes aux_stream wait for stream's
+ * earlier work and stream wait for the weight gradient before it returns, so callers keep ordering everything on
+ * stream alone (and may capture stream into a HIP graph: aux_stream joins and leaves the capture inside the call).
+ * Both streams must have default priority.  aux_stream NULL or equal to stream: same as tt_fc_backward.
+ * The workspace need is that of tt_fc_backward (the two products never share scratch inside one call). */
+tt_status tt_fc_backward_overlapped(const tt_layer *layer, int64_t batch, int k, int dtype, tt_tiling tX, tt_tiling tW,
+                                    tt_tiling tY, tt_tiling tdY, tt_tiling tdX, const uint8_t *forms_dgrad,
+                                    const uint8_t *forms_wgrad, const void *const *X, const void *const *W,
+                                    const void *const *Y, const void *const *dY, void *const *dX, void *const *dW,
+                                    void *workspace, size_t ws_bytes, void *stream, void *aux_stream);
+
 /* Convolution layer (layouts in tt_layer).  Supported cuts per product: F1 (batch), F2 (output channels for
  * forward, input channels for dgrad; out-channel / in-channel grid for wgrad), F3 (reduction split). */
 tt_status tt_conv_workspace_bytes(const tt_layer *layer, int64_t batch, int k, int dtype, int op, tt_tiling tX,

@@ -25,7 +25,7 @@ STATUS_NAMES = {0: "TT_OK", 1: "TT_EINVAL", 2: "TT_EINFEASIBLE", 3: "TT_EUNSUPPO
 EXPORTS = [
     "tt_strerror", "tt_shard_shape", "tt_plan_chain", "tt_plan_eval", "tt_plan_k", "tt_plan_layers", "tt_plan_cost",
     "tt_plan_delta", "tt_plan_tiling", "tt_plan_forms", "tt_plan_free", "tt_retile", "tt_retile_gate", "tt_reduce",
-    "tt_shard_gemm", "tt_fc_workspace_bytes", "tt_fc_forward", "tt_fc_backward", "tt_conv_workspace_bytes",
+    "tt_shard_gemm", "tt_fc_workspace_bytes", "tt_fc_forward", "tt_fc_backward", "tt_fc_backward_overlapped", "tt_conv_workspace_bytes",
     "tt_conv_forward", "tt_conv_backward", "tt_profile_begin", "tt_profile_end", "tt_profile_get",
 ]
 KERNEL_NAMES = ["convert", "gate", "reduce", "gemm_nn", "gemm_nt", "gemm_tn", "gemm_tt", "gemm_generic", "conv_fwd",
@@ -105,6 +105,7 @@ def lib():
         L.tt_conv_forward.argtypes = fwd_args
         L.tt_fc_backward.argtypes = bwd_args
         L.tt_conv_backward.argtypes = bwd_args
+        L.tt_fc_backward_overlapped.argtypes = bwd_args + [ctypes.c_void_p]
         L.tt_profile_end.argtypes = [ctypes.POINTER(ctypes.c_int)]
         L.tt_profile_get.argtypes = [ctypes.c_int, ctypes.POINTER(tt_kernel_record)]
         _lib = L
@@ -162,7 +163,8 @@ def ptrs(shards):
 
 def _stream(stream):
     if stream is not None:
-        return ctypes.c_void_p(int(stream))
+        # a raw stream handle, or a torch.cuda.Stream
+        return ctypes.c_void_p(int(getattr(stream, "cuda_stream", stream)))
     import torch
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -340,6 +342,15 @@ def tt_fc_backward(lay, batch, k, dtype, tX, tW, tY, tdY, tdX, forms_dgrad, form
                    workspace=None, stream=None):
     _backward(lib().tt_fc_backward, "tt_fc_backward", lay, batch, k, dtype, tX, tW, tY, tdY, tdX, forms_dgrad,
               forms_wgrad, X, W, Y, dY, dX, dW, workspace, stream)
+
+
+def tt_fc_backward_overlapped(lay, batch, k, dtype, tX, tW, tY, tdY, tdX, forms_dgrad, forms_wgrad, X, W, Y, dY, dX, dW,
+                              workspace=None, stream=None, aux_stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().tt_fc_backward_overlapped(
+        ctypes.byref(lay), batch, k, _dtype(dtype), tiling(tX), tiling(tW), tiling(tY), tiling(tdY), _t_or(tdX, tX),
+        forms(forms_dgrad), forms(forms_wgrad), ptrs(X), ptrs(W), ptrs(Y), ptrs(dY), ptrs(dX), ptrs(dW), wp, wb,
+        _stream(stream), _stream(aux_stream) if aux_stream is not None else None), "tt_fc_backward_overlapped")
 
 
 def tt_conv_forward(lay, batch, k, dtype, tX, tW, tY, form_seq, X, W, Y, workspace=None, stream=None):

@@ -137,8 +137,10 @@ inline int pick_ksplit(int64_t M, int64_t N, int64_t K, int count, int dtype, bo
         if (f >= 1 && K / f >= 256 && count * f <= kMaxShards) return f;
     }
     const int64_t blocks = ((M + 255) / 256) * ((N + 255) / 256) * count; // 256 x 256 tiles, one per CU
+    // chunks stay at least 512 deep, except where the launch would otherwise occupy under a quarter of the CUs (the
+    // 1000-wide last layer): there chunks down to 192 still pay for the extra partial sums
     int s = 1;
-    while (blocks * s < 200 && s < 8 && K / (2 * s) >= 512 && count * 2 * s <= kMaxShards) s *= 2;
+    while (blocks * s < 200 && s < 8 && K / (2 * s) >= (blocks * s < 64 ? 192 : 512) && count * 2 * s <= kMaxShards) s *= 2;
     return s;
 }
 

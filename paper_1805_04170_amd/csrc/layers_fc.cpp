@@ -1,6 +1,7 @@
 // Fully-connected layer under a k-cut tiling: forward x_l = f(x_{l-1} W_l) and backward
 // dC/dx_{l-1} = df(dC/dx_l) W_l^T, dC/dW_l = x_{l-1}^T df(dC/dx_l) (Sec. 2.1 of arXiv 1805.04170), each product run
 // in the three phases of Sec. 4.2.1 / Sec. 5.2.
+#include <hip/hip_runtime.h>
 #include "exec_common.h"
 
 namespace tt {
@@ -16,6 +17,45 @@ struct FcArgs {
     void *const *Yout, *const *dX, *const *dW;
     bool with_dx;
     void *stream;
+    void *aux = nullptr; // optional second stream: the weight-gradient product runs there, beside the dX product
+};
+
+// Fork / join between the caller's two streams.  The events live per host thread and are made once; recording one
+// again replaces its earlier use, which is what each call wants.
+struct StreamFork {
+    hipStream_t main = nullptr, side = nullptr;
+    bool forked = false;
+    static bool events(hipEvent_t *fork_ev, hipEvent_t *join_ev)
+    {
+        static thread_local hipEvent_t ev[2] = {nullptr, nullptr};
+        for (int i = 0; i < 2; ++i)
+            if (!ev[i] && hipEventCreateWithFlags(&ev[i], hipEventDisableTiming) != hipSuccess) return false;
+        *fork_ev = ev[0];
+        *join_ev = ev[1];
+        return true;
+    }
+    // work enqueued on side after this call starts after everything enqueued on main so far
+    tt_status fork(void *main_stream, void *side_stream)
+    {
+        main = reinterpret_cast<hipStream_t>(main_stream);
+        side = reinterpret_cast<hipStream_t>(side_stream);
+        hipEvent_t f, j;
+        if (!events(&f, &j)) return TT_EDEVICE;
+        if (hipEventRecord(f, main) != hipSuccess || hipStreamWaitEvent(side, f, 0) != hipSuccess) return TT_EDEVICE;
+        forked = true;
+        return TT_OK;
+    }
+    // work enqueued on main after this call starts after everything enqueued on side so far
+    tt_status join()
+    {
+        if (!forked) return TT_OK;
+        forked = false;
+        hipEvent_t f, j;
+        if (!events(&f, &j)) return TT_EDEVICE;
+        if (hipEventRecord(j, side) != hipSuccess || hipStreamWaitEvent(main, j, 0) != hipSuccess) return TT_EDEVICE;
+        return TT_OK;
+    }
+    ~StreamFork() { (void)join(); } // error paths: never leave the side stream dangling (it may be under capture)
 };
 
 tt_status check_common(const FcArgs &a)
@@ -90,34 +130,31 @@ tt_status backward(const FcArgs &a, Workspace &ws)
     Sharded G = dY;
     bool gated = !relu;
 
+    // dX = G W^T : M = b, K = n_out, N = n_in; second operand is W transposed
+    uint8_t fd[TT_MAX_K];
+    Sharded Ga_d;
+    tt_tiling aW_d;
+    int d1 = 0, d2 = 0, d3 = 0;
     if (a.with_dx) {
-        // dX = G W^T : M = b, K = n_out, N = n_in; second operand is W transposed
-        uint8_t f[TT_MAX_K];
         const tt_tiling tWt = transpose_tiling(a.tW, k);
-        st = pick_forms(a.forms_a, f, k, {b, no, 1}, {no, ni, 1}, {b, ni, 1}, b, no, ni, a.tdY, tWt, a.tdX);
+        st = pick_forms(a.forms_a, fd, k, {b, no, 1}, {no, ni, 1}, {b, ni, 1}, b, no, ni, a.tdY, tWt, a.tdX);
         if (st != TT_OK) return st;
         tt_tiling aG, aWt;
-        aligned_tilings(f, k, &aG, &aWt, nullptr);
-        const tt_tiling aW = transpose_tiling(aWt, k); // expressed on W as stored (n_in x n_out)
-        int k1, k2, k3;
-        form_counts(f, k, &k1, &k2, &k3);
-        Sharded Ga, Wa;
-        if ((st = prepare_operand(G, aG, k, esz, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga)) != TT_OK) return st;
-        if (!gated) { G = Ga; gated = true; }
-        if ((st = prepare_operand(W, aW, k, esz, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
-        OutputPlan op;
-        const int64_t Ms = b >> k1, Ns = ni >> k2, Ks = no >> k3;
-        const int ksplit = pick_ksplit(Ms, Ns, Ks, n, a.dtype, Ks % 8 == 0, Ks % 8 == 0);
-        if ((st = plan_output(f, a.tdX, a.dX, b, ni, k, a.dtype, TT_ACT_NONE, ws, &op, ksplit)) != TT_OK) return st;
-        if (!ws.dry) {
-            // W shard is (n_in/..) x (n_out/..) row-major = N x K: trans_b
-            st = launch_gemm(n, Ga.ptr, Wa.ptr, op.gemm_out, Ms, Ns, Ks, 0, 1, a.dtype, op.gemm_dtype, op.gemm_act, ksplit,
-                             a.stream);
-            if (st != TT_OK) return st;
-            if ((st = finish_output(op, a.tdX, a.dX, b, ni, k, a.dtype, TT_ACT_NONE, a.stream)) != TT_OK) return st;
-        }
+        aligned_tilings(fd, k, &aG, &aWt, nullptr);
+        aW_d = transpose_tiling(aWt, k); // expressed on W as stored (n_in x n_out)
+        form_counts(fd, k, &d1, &d2, &d3);
+        if ((st = prepare_operand(G, aG, k, esz, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga_d)) != TT_OK) return st;
+        if (!gated) { G = Ga_d; gated = true; }
     }
-    {
+
+    // With a second stream the weight gradient is enqueued there, after G exists, and runs beside the dX product.
+    StreamFork fk;
+    void *wstream = a.stream;
+    if (a.aux && a.aux != a.stream && !ws.dry) {
+        if ((st = fk.fork(a.stream, a.aux)) != TT_OK) return st;
+        wstream = a.aux;
+    }
+    auto wgrad = [&]() -> tt_status {
         // dW = X^T G : M = n_in, K = b, N = n_out; first operand is X transposed; dW stored like W
         uint8_t f[TT_MAX_K];
         const tt_tiling tXt = transpose_tiling(a.tX, k);
@@ -129,19 +166,46 @@ tt_status backward(const FcArgs &a, Workspace &ws)
         int k1, k2, k3;
         form_counts(f, k, &k1, &k2, &k3);
         Sharded Xa, Ga;
-        if ((st = prepare_operand(X, aX, k, esz, nullptr, a.dtype, ws, a.stream, &Xa)) != TT_OK) return st;
-        if ((st = prepare_operand(G, aG, k, esz, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga)) != TT_OK) return st;
+        if ((st = prepare_operand(X, aX, k, esz, nullptr, a.dtype, ws, wstream, &Xa)) != TT_OK) return st;
+        if ((st = prepare_operand(G, aG, k, esz, gated ? nullptr : &Y, a.dtype, ws, wstream, &Ga)) != TT_OK) return st;
         OutputPlan op;
         if ((st = plan_output(f, a.tW, a.dW, ni, no, k, a.dtype, TT_ACT_NONE, ws, &op)) != TT_OK) return st;
         if (!ws.dry) {
             // X shard is (b/..) x (n_in/..) row-major = K x M: trans_a
             st = launch_gemm(n, Xa.ptr, Ga.ptr, op.gemm_out, ni >> k1, no >> k2, b >> k3, 1, 0, a.dtype, op.gemm_dtype,
-                             op.gemm_act, 1, a.stream);
+                             op.gemm_act, 1, wstream);
             if (st != TT_OK) return st;
-            if ((st = finish_output(op, a.tW, a.dW, ni, no, k, a.dtype, TT_ACT_NONE, a.stream)) != TT_OK) return st;
+            if ((st = finish_output(op, a.tW, a.dW, ni, no, k, a.dtype, TT_ACT_NONE, wstream)) != TT_OK) return st;
         }
+        return TT_OK;
+    };
+    auto dgrad = [&]() -> tt_status {
+        if (!a.with_dx) return TT_OK;
+        Sharded Wa;
+        if ((st = prepare_operand(W, aW_d, k, esz, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
+        OutputPlan op;
+        const int64_t Ms = b >> d1, Ns = ni >> d2, Ks = no >> d3;
+        const int ksplit = pick_ksplit(Ms, Ns, Ks, n, a.dtype, Ks % 8 == 0, Ks % 8 == 0);
+        if ((st = plan_output(fd, a.tdX, a.dX, b, ni, k, a.dtype, TT_ACT_NONE, ws, &op, ksplit)) != TT_OK) return st;
+        if (!ws.dry) {
+            // W shard is (n_in/..) x (n_out/..) row-major = N x K: trans_b
+            st = launch_gemm(n, Ga_d.ptr, Wa.ptr, op.gemm_out, Ms, Ns, Ks, 0, 1, a.dtype, op.gemm_dtype, op.gemm_act, ksplit,
+                             a.stream);
+            if (st != TT_OK) return st;
+            if ((st = finish_output(op, a.tdX, a.dX, b, ni, k, a.dtype, TT_ACT_NONE, a.stream)) != TT_OK) return st;
+        }
+        return TT_OK;
+    };
+    // One stream: dX product first, then the weight gradient.  Two streams: the weight gradient is enqueued first so
+    // that it is already running on the side stream while the dX product is being launched.
+    if (fk.forked) {
+        if ((st = wgrad()) != TT_OK) return st;
+        if ((st = dgrad()) != TT_OK) return st;
+    } else {
+        if ((st = dgrad()) != TT_OK) return st;
+        if ((st = wgrad()) != TT_OK) return st;
     }
-    return TT_OK;
+    return fk.join();
 }
 
 bool null_in(const void *const *p, int n)
@@ -196,6 +260,13 @@ extern "C" tt_status tt_fc_forward(const tt_layer *layer, int64_t batch, int k, 
     return tt::forward(a, ws);
 }
 
+extern "C" tt_status tt_fc_backward_overlapped(const tt_layer *layer, int64_t batch, int k, int dtype, tt_tiling tX,
+                                               tt_tiling tW, tt_tiling tY, tt_tiling tdY, tt_tiling tdX,
+                                               const uint8_t *forms_dgrad, const uint8_t *forms_wgrad,
+                                               const void *const *X, const void *const *W, const void *const *Y,
+                                               const void *const *dY, void *const *dX, void *const *dW, void *workspace,
+                                               size_t ws_bytes, void *stream, void *aux_stream);
+
 extern "C" tt_status tt_fc_backward(const tt_layer *layer, int64_t batch, int k, int dtype, tt_tiling tX, tt_tiling tW,
                                     tt_tiling tY, tt_tiling tdY, tt_tiling tdX, const uint8_t *forms_dgrad,
                                     const uint8_t *forms_wgrad, const void *const *X, const void *const *W,
@@ -204,6 +275,27 @@ extern "C" tt_status tt_fc_backward(const tt_layer *layer, int64_t batch, int k,
 {
     tt::FcArgs a{layer, batch, k, dtype, tX, tW, tY, tdY, tdX, forms_dgrad, forms_wgrad, X, W, Y, dY, nullptr, dX, dW,
                  dX != nullptr, stream};
+    tt_status st = tt::check_common(a);
+    if (st != TT_OK) return st;
+    const int n = 1 << k;
+    if (tt::null_in(X, n) || tt::null_in(W, n) || tt::null_in(dY, n) || tt::null_in(const_cast<const void *const *>(dW), n)) return TT_EINVAL;
+    if (layer->act == TT_ACT_RELU && tt::null_in(Y, n)) return TT_EINVAL;
+    if (dX && tt::null_in(const_cast<const void *const *>(dX), n)) return TT_EINVAL;
+    tt::Workspace ws;
+    if ((st = tt::bind_workspace(ws, workspace, ws_bytes)) != TT_OK) return st;
+    return tt::backward(a, ws);
+}
+
+extern "C" tt_status tt_fc_backward_overlapped(const tt_layer *layer, int64_t batch, int k, int dtype, tt_tiling tX,
+                                               tt_tiling tW, tt_tiling tY, tt_tiling tdY, tt_tiling tdX,
+                                               const uint8_t *forms_dgrad, const uint8_t *forms_wgrad,
+                                               const void *const *X, const void *const *W, const void *const *Y,
+                                               const void *const *dY, void *const *dX, void *const *dW, void *workspace,
+                                               size_t ws_bytes, void *stream, void *aux_stream)
+{
+    tt::FcArgs a{layer, batch, k, dtype, tX, tW, tY, tdY, tdX, forms_dgrad, forms_wgrad, X, W, Y, dY, nullptr, dX, dW,
+                 dX != nullptr, stream};
+    a.aux = aux_stream;
     tt_status st = tt::check_common(a);
     if (st != TT_OK) return st;
     const int n = 1 << k;

@@ -107,6 +107,53 @@ def test_three_cuts_ragged_width_and_skip_dx():
     run_layer(64, 1000, 40, 3, "bf16", True, "rCr", "CRC", "CrC", "CrC", "RCR", "232", "323", "212", 82)
 
 
+def _backward_once(fn, lay, b, k, dt, t, forms, Xs, Ws, Ys, dYs, ni, no, **kw):
+    dXs = alloc_shards(b, ni, t["dX"], tdtype(dt), fill=float("nan"))
+    dWs = alloc_shards(ni, no, t["W"], tdtype(dt), fill=float("nan"))
+    nb = tt.tt_fc_workspace_bytes(lay, b, k, dt, tt.TT_OP_DGRAD, t["X"], t["W"], t["Y"], t["dY"], t["dX"], forms[0], forms[1])
+    ws = workspace(nb)
+    fn(lay, b, k, dt, t["X"], t["W"], t["Y"], t["dY"], t["dX"], forms[0], forms[1], Xs, Ws, Ys, dYs, dXs, dWs, ws, **kw)
+    return dXs, dWs, ws
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_backward_overlapped_equals_backward(relu):
+    # the two-stream variant must produce the very same bits, eagerly and as a captured graph replayed several times
+    b, ni, no, k, dt = 64, 512, 384, 3, "bf16"
+    t = dict(X="CCr", W="RRC", Y="CCC", dY="CrC", dX="CCr")
+    forms = ("233", "112")
+    lay = tt.layer("fc", "relu" if relu else "none", ni, no)
+    X = to_store(normal_f32(90, 0, (b, ni), 1.0), dt)
+    W = to_store(normal_f32(90, 1, (ni, no), 0.05), dt)
+    Y = to_store(normal_f32(90, 3, (b, no), 1.0), dt)
+    dY = to_store(normal_f32(90, 2, (b, no), 1.0), dt)
+    Xs, Ws, Ys, dYs = (shards_to_dev(a, tt_, True) for a, tt_ in ((X, t["X"]), (W, t["W"]), (Y, t["Y"]), (dY, t["dY"])))
+    ref_dX, ref_dW, _ = _backward_once(tt.tt_fc_backward, lay, b, k, dt, t, forms, Xs, Ws, Ys, dYs, ni, no)
+    torch.cuda.synchronize()
+    aux = torch.cuda.Stream()
+    got_dX, got_dW, _ = _backward_once(tt.tt_fc_backward_overlapped, lay, b, k, dt, t, forms, Xs, Ws, Ys, dYs, ni, no, aux_stream=aux)
+    torch.cuda.synchronize()
+    for g, r in zip(got_dX + got_dW, ref_dX + ref_dW):
+        assert torch.equal(g.view(torch.int16), r.view(torch.int16))
+    # captured: outputs and workspace allocated outside the capture, work launched on the capturing stream
+    dXs = alloc_shards(b, ni, t["dX"], tdtype(dt), fill=float("nan"))
+    dWs = alloc_shards(ni, no, t["W"], tdtype(dt), fill=float("nan"))
+    ws = workspace(tt.tt_fc_workspace_bytes(lay, b, k, dt, tt.TT_OP_DGRAD, t["X"], t["W"], t["Y"], t["dY"], t["dX"], forms[0], forms[1]))
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        tt.tt_fc_backward_overlapped(lay, b, k, dt, t["X"], t["W"], t["Y"], t["dY"], t["dX"], forms[0], forms[1], Xs, Ws, Ys,
+                                     dYs, dXs, dWs, ws, aux_stream=aux)
+    for rep in range(3):
+        for d in dXs + dWs:
+            d.fill_(float("nan"))                                 # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for g, r in zip(dXs + dWs, ref_dX + ref_dW):
+            assert torch.equal(g.view(torch.int16), r.view(torch.int16)), rep
+
+
 def test_uneven_and_bad_workspace_are_refused():
     lay = tt.layer("fc", "none", 10, 6)
     x = [torch.zeros(8, dtype=torch.bfloat16, device=DEV)] * 4
