@@ -11,11 +11,11 @@
 namespace tt {
 namespace {
 
-template <int BK, int NS, bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED>
+template <int BK, int NS, bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED, bool ILV>
 __global__ __launch_bounds__(core3::kThreads3, 2) void gemm_bf16_v3_kernel(const core3::Params3 p)
 {
     extern __shared__ __attribute__((aligned(16))) char smem3[];
-    core3::run_tiles<BK, NS, A_KC, B_KC, OUT_BF16, STAGED>(p, smem3);
+    core3::run_tiles<BK, NS, A_KC, B_KC, OUT_BF16, STAGED, ILV>(p, smem3);
 }
 
 // 256 x 128 tiles, four waves, two workgroups per CU (gemm_core4.h); one tile per workgroup
@@ -70,10 +70,10 @@ int cu_count()
     return n;
 }
 
-template <int BK, int NS, bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED>
+template <int BK, int NS, bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED, bool ILV = false>
 tt_status launch_cfg(core3::Params3 &p, hipStream_t s)
 {
-    auto kern = gemm_bf16_v3_kernel<BK, NS, A_KC, B_KC, OUT_BF16, STAGED>;
+    auto kern = gemm_bf16_v3_kernel<BK, NS, A_KC, B_KC, OUT_BF16, STAGED, ILV>;
     constexpr size_t smem = core3::smem_bytes3<BK, NS, STAGED>();
     static bool configured = false;
     if (!configured) {
@@ -95,7 +95,12 @@ template <bool A_KC, bool B_KC> tt_status launch_layout(core3::Params3 &p, int o
         if (bf && vec) return launch_cfg<32, 4, A_KC, B_KC, true, true>(p, s);
         return bf ? launch_cfg<32, 4, A_KC, B_KC, true, false>(p, s) : launch_cfg<32, 4, A_KC, B_KC, false, false>(p, s);
     }
-    if (bf && vec) return launch_cfg<64, 2, A_KC, B_KC, true, true>(p, s);
+    // short K loops (the weight gradients at batch 256): loads issued between the k-steps, see run_tiles
+    // Loads issued between the k-steps (see run_tiles) measured faster for the products with bf16 results (the weight
+    // gradients: short K loops) and slower or equal for those that write fp32 partial sums (long K loops), so only the
+    // former use it.  (TT_V3_ILV=0: never; tuning aid.)
+    static const bool ilv = [] { const char *e = std::getenv("TT_V3_ILV"); return !e || std::atoi(e) != 0; }();
+    if (bf && vec) return ilv ? launch_cfg<64, 2, A_KC, B_KC, true, true, true>(p, s) : launch_cfg<64, 2, A_KC, B_KC, true, true>(p, s);
     return bf ? launch_cfg<64, 2, A_KC, B_KC, true, false>(p, s) : launch_cfg<64, 2, A_KC, B_KC, false, false>(p, s);
 }
 

@@ -141,10 +141,8 @@ template <int BK, bool KC, bool IS_A> struct Feeder {
         if (live) bind(p, t);
     }
 
-    // Fetch the current K tile into the stage at LDS address lds (wave-uniform), then move on.  Past the end of the
-    // list the last K tile is fetched again (into a stage nobody reads), so every item issues the same number of loads
-    // and the wait count of the main loop stays constant.
-    __device__ __forceinline__ void issue_and_advance(const Params3 &p, uint32_t lds)
+    // Fetch chunk i (of NL) of the current K tile into the stage at LDS address lds (wave-uniform).
+    __device__ __forceinline__ void issue_one(int i, uint32_t lds) const
     {
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         // the base is wave-uniform by construction; say so, or the "s" operand may be handed a vector register pair
@@ -153,11 +151,15 @@ template <int BK, bool KC, bool IS_A> struct Feeder {
         const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b64);
         const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b64 >> 32));
         const uint64_t sbase = ((uint64_t)b_hi << 32) | (uint64_t)b_lo;
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const uint32_t dst = lds + (wave * 64u + (uint32_t)i * kThreads3) * 16u;
-            asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff[i]), "s"(sbase), "{m0}"(dst) : "memory");
-        }
+        const uint32_t dst = lds + (wave * 64u + (uint32_t)i * kThreads3) * 16u;
+        asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff[i]), "s"(sbase), "{m0}"(dst) : "memory");
+    }
+
+    // Move on to the next K tile.  Past the end of the list the last K tile stays current and is fetched again (into a
+    // stage nobody reads), so every item issues the same number of loads and the wait count of the main loop stays
+    // constant.
+    __device__ __forceinline__ void advance(const Params3 &p)
+    {
         if (!live) return;
         if (kt + 1 < nk) {
             ++kt;
@@ -171,6 +173,13 @@ template <int BK, bool KC, bool IS_A> struct Feeder {
         } else {
             live = false; // keep pointing at the last K tile
         }
+    }
+
+    __device__ __forceinline__ void issue_and_advance(const Params3 &p, uint32_t lds)
+    {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) issue_one(i, lds);
+        advance(p);
     }
 };
 
@@ -187,7 +196,7 @@ template <int BK, bool KC> __device__ __forceinline__ bf16x8 read_frag3(const ch
     }
 }
 
-template <int BK, int NS, bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED>
+template <int BK, int NS, bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED, bool ILV>
 __device__ __forceinline__ void run_tiles(const Params3 &p, char *smem)
 {
     static_assert(NS >= 2 && (BK == 32 || BK == 64), "ring shape");
@@ -233,15 +242,28 @@ __device__ __forceinline__ void run_tiles(const Params3 &p, char *smem)
         for (int kt = 0; kt < nk; ++kt) {
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(W)); // this wave's chunks of the item have landed
             __syncthreads();                           // everyone's have; everyone has finished reading the previous item
-            fa.issue_and_advance(p, lds0 + (uint32_t)is * STB); // into the stage of the previous item
-            fb.issue_and_advance(p, lds0 + (uint32_t)is * STB + OPB);
+            const uint32_t lds_next = lds0 + (uint32_t)is * STB; // item kt + D goes into the stage of the previous item
             is = is + 1 == NS ? 0 : is + 1;
             const char *As = smem + cs * STB, *Bs = As + OPB;
             cs = cs + 1 == NS ? 0 : cs + 1;
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_iglp_opt(1);
+            if constexpr (!ILV) {
+                fa.issue_and_advance(p, lds_next);
+                fb.issue_and_advance(p, lds_next + OPB);
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_iglp_opt(1);
+            }
+            static_assert(loads_per_op<BK>() == BK / 16, "one chunk of each operand per k-step");
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
+                if constexpr (ILV) {
+                    // Fetch spread over the k-steps of the item: a wave that issues all its loads at once sits in the
+                    // issue queue until the memory pipeline has taken them and only then starts to multiply.  Pays for
+                    // short K loops (measured: K = 256); for long ones the compiler's own interleaving of fragment
+                    // reads and MFMAs (iglp_opt), which the fences here switch off, is worth more.
+                    fa.issue_one(ks, lds_next);
+                    fb.issue_one(ks, lds_next + OPB);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 bf16x8 af[TM], bf[TN];
 #pragma unroll
                 for (int i = 0; i < TM; ++i) af[i] = read_frag3<BK, A_KC>(As, wm0 + i * 32, ks, lane);
@@ -252,6 +274,11 @@ __device__ __forceinline__ void run_tiles(const Params3 &p, char *smem)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+                if constexpr (ILV) __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (ILV) {
+                fa.advance(p);
+                fb.advance(p);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
