@@ -364,8 +364,8 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
                     if (relu) v = fmaxf(v, 0.0f);
                     strip[(8 * (e >> 2) + (lane >> 5) * 4 + (e & 3)) * SLD + j * 32 + (lane & 31)] = v;
                 }
-            // wave-private data: only this wave's own LDS writes have to land before it reads them back
-            __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0)
+            // Wave-private data: LDS operations of one wave execute in order, so the reads below see the writes above and the
+            // next strip's writes cannot overtake them; no wait is needed, only a fence for the compiler's scheduler.
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int rr = 0; rr < 32; rr += RPI) {
@@ -384,7 +384,6 @@ __device__ __forceinline__ void tile_product(LA &la, LB &lb, void *Cv, int ldc, 
                     }
                 }
             }
-            __builtin_amdgcn_s_waitcnt(0xc07f);
             __builtin_amdgcn_wave_barrier();
         }
     }

@@ -196,7 +196,6 @@ __device__ __forceinline__ void tile_product2(const LA &la, const LB &lb, void *
                     if (relu) v = fmaxf(v, 0.0f);
                     strip[(8 * (e >> 2) + row_l + (e & 3)) * SLD + j * 32 + col_l] = v;
                 }
-            __builtin_amdgcn_s_waitcnt(0xc07f);
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int rr = 0; rr < 32; rr += RPI) {
@@ -215,7 +214,6 @@ __device__ __forceinline__ void tile_product2(const LA &la, const LB &lb, void *
                     }
                 }
             }
-            __builtin_amdgcn_s_waitcnt(0xc07f);
             __builtin_amdgcn_wave_barrier();
         }
     }

@@ -204,8 +204,8 @@ __device__ __forceinline__ void tile_product4(const char *abase, int lda, const 
                             d[0] = (uint16_t)(pk & 0xffffu);
                             d[ELD] = (uint16_t)(pk >> 16);
                         }
-                // wave-private data: only this wave's own LDS writes have to land before it reads them back
-                __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0)
+                // Wave-private data: LDS operations of one wave execute in order, so the reads below see the writes above and the
+                // next strip's writes cannot overtake them; no wait is needed, only a fence for the compiler's scheduler.
                 __builtin_amdgcn_wave_barrier();
 #pragma unroll
                 for (int v = 0; v < 2; ++v) {
@@ -215,7 +215,6 @@ __device__ __forceinline__ void tile_product4(const char *abase, int lda, const 
                     if (row < M && col < N) // N is a multiple of 8 on this path: a vector is all in or all out
                         __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(Cs + (size_t)row * ldc + col));
                 }
-                __builtin_amdgcn_s_waitcnt(0xc07f);
                 __builtin_amdgcn_wave_barrier();
             }
     }
