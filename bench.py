@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vgg16_fc",
-                    choices=["vgg16_fc", "alexnet_fc", "wide_mlp", "tiny_mlp", "vgg16_conv4"])
+                    choices=["vgg16_fc", "alexnet_fc", "wide_mlp", "tiny_mlp", "vgg16_conv4", "shape_study"])
     ap.add_argument("--conv-split", default="planner", choices=["planner", "batch", "out_channel"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
@@ -238,6 +238,45 @@ def cpu_baseline(cfg):
             "sample": "1 full untiled fwd+bwd step of %s in fp64 numpy (%.1f GFLOP, %.2f s)" % (cfg.name, cfg.flops() / 1e9, dt)}
 
 
+def shape_study(args, tt, torch):
+    """Sec. 6.3 / Table 1 of the paper asked again on one MI355X: a 4-layer MLP with 8K x 8K weights, one step untiled
+    (k = 0) against the same step cut into 8 shards under the planner's tiling, all shards on this GPU.  Same flops."""
+    from synthetic.configs import FcChain
+    paper = {512: (0.31, 0.19), 1024: (0.56, 0.39), 2048: (1.13, 0.73)}  # seconds per batch, the paper's GPU and fp32
+    rows = []
+    for b in (512, 1024, 2048):
+        res = {}
+        for k in (0, 3):
+            cfg = FcChain("mlp4_8k", b, (8192,) * 5, k, "bf16", 0.01, 1006)
+            chain = Chain(cfg, tt, torch)
+            for _ in range(max(args.warmup, 1)):
+                chain.step()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                chain.step()
+            graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            res[k] = dict(ms=ms, tflops=cfg.flops() / (ms * 1e-3) / 1e12, tiling_w=chain.tw, tiling_x=chain.tx,
+                          plan_cost_elems=chain.plan_cost)
+            del chain, graph
+            torch.cuda.empty_cache()
+        rows.append({"batch": b, "untiled_ms": res[0]["ms"], "tiled_ms": res[3]["ms"],
+                     "untiled_TFLOPs": res[0]["tflops"], "tiled_TFLOPs": res[3]["tflops"],
+                     "tiled_over_untiled_time": res[3]["ms"] / res[0]["ms"], "tiling_w": res[3]["tiling_w"],
+                     "tiling_x": res[3]["tiling_x"], "paper_untiled_s": paper[b][0], "paper_tiled_s": paper[b][1],
+                     "paper_tiled_over_untiled_time": paper[b][1] / paper[b][0]})
+    print(json.dumps({"metric": "fwd+bwd time per batch of a 4-layer 8K x 8K MLP: untiled vs cut into 8 shards on one GPU",
+                      "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16",
+                      "data": "synthetic", "config": {"workload": "shape_study: 8192->8192 x4, k=0 vs k=3 planner EXACT"},
+                      "rows": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -251,8 +290,11 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     tt.binding.lib()
-    cfg = CONFIGS[args.workload]
     torch.cuda.set_device(0)
+    if args.workload == "shape_study":
+        shape_study(args, tt, torch)
+        return
+    cfg = CONFIGS[args.workload]
     is_conv = not hasattr(cfg, "widths")
     if is_conv:
         chain = ConvLayerBench(cfg, tt, torch, args.conv_split)
