@@ -88,7 +88,14 @@ tt_status tt_shard_shape(int64_t rows, int64_t cols, tt_tiling t, int k, int64_t
  * products per layer  F_l: x_l = x_{l-1} W_l,  B_l: g_{l-1} = g_l W_l^T,  G_l: dW_l = x_{l-1}^T g_l,
  * with dW_l stored in the tiling of W_l.  Cost of a product = Eq. 2 per cut (conversion cost = area needed
  * for the local product minus area already held, Sec. 4.2.1), the area at cut j being the stored tile left by
- * cuts 0..j-1, summed as sum_j 2^j delta_j (Theorem 1) and minimised over feasible form sequences. */
+ * cuts 0..j-1, summed as sum_j 2^j delta_j (Theorem 1) and minimised over feasible form sequences.
+ * Chains may mix layer kinds the way AlexNet and VGG do (Sec. 6): convolutions first, then fully-connected layers.
+ *  - A convolution whose H x W is smaller than the P x Q of the convolution before it: a pooling (or striding) stage
+ *    lies between them; it works per image and per channel, moves nothing under any tiling (element-wise functions,
+ *    Eq. 1 / Sec. 4.5), and the tensor between the layers is charged at the size the later layer reads.
+ *  - A fully-connected layer after a convolution with K output channels: n_in = K * pixels (pixels <= what the
+ *    convolution or the pooling after it left) is the flattened image; a column cut of that tensor is a channel cut.
+ *  - Convolution after fully-connected: TT_EUNSUPPORTED.  Dimension mismatches: TT_EINVAL. */
 
 typedef struct tt_plan tt_plan; /* opaque, host memory, freed by tt_plan_free */
 

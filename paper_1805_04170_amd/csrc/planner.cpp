@@ -129,6 +129,15 @@ struct Chain {
     int64_t wmult[TT_MAX_LAYERS + 1];
 };
 
+// Whole networks (Sec. 6: AlexNet and VGG are convolution layers followed by fully-connected ones):
+//  - convolution after convolution with a SMALLER image than the previous layer produced: a pooling / striding stage in
+//    between.  It works per image and per channel, so like the other element-wise functions (Eq. 1, Sec. 4.5) it moves
+//    nothing under any tiling; the tensor between the two layers is charged at the size the next layer reads;
+//  - fully-connected after convolution: the flattening of (channels x pixels) per image.  The tensor keeps its channel
+//    count as the cuttable column dimension (a column cut is a channel cut, as for the convolution that produced it)
+//    and its pixels per channel as the area multiplier; the layer is the convolution whose filter covers the whole
+//    image (weights: channels x n_out, times pixels).  n_in must be channels x pixels, pixels at most what the
+//    convolution (or the pooling after it) left.
 tt_status make_chain(const tt_layer *layers, int n_layers, int64_t batch, Chain *c)
 {
     if (!layers || n_layers < 1 || n_layers > TT_MAX_LAYERS || batch <= 0) return TT_EINVAL;
@@ -138,17 +147,30 @@ tt_status make_chain(const tt_layer *layers, int n_layers, int64_t batch, Chain 
         const tt_layer &y = layers[l];
         if (y.n_in <= 0 || y.n_out <= 0) return TT_EINVAL;
         if (y.kind != TT_FC && y.kind != TT_CONV2D) return TT_EINVAL;
-        if (l > 0 && y.n_in != layers[l - 1].n_out) return TT_EINVAL;
-        if (l > 0 && y.kind != layers[l - 1].kind) return TT_EUNSUPPORTED; // conv -> fc flatten is not modelled
+        const bool after_conv = l > 0 && layers[l - 1].kind == TT_CONV2D;
+        if (l > 0 && y.kind == TT_CONV2D && !after_conv) return TT_EUNSUPPORTED; // fc -> conv is not modelled
         int64_t in_mult = 1, out_mult = 1, w_mult = 1;
         if (y.kind == TT_CONV2D) {
+            if (l > 0 && y.n_in != layers[l - 1].n_out) return TT_EINVAL;
             if (y.H <= 0 || y.W <= 0 || y.R <= 0 || y.S <= 0 || y.pad < 0) return TT_EINVAL;
             int64_t P = y.H + 2 * y.pad - y.R + 1, Q = y.W + 2 * y.pad - y.S + 1;
             if (P <= 0 || Q <= 0) return TT_EINVAL;
             in_mult = y.H * y.W;
             out_mult = P * Q;
             w_mult = y.R * y.S;
-            if (l > 0 && c->xmult[l] != in_mult) return TT_EINVAL;
+            if (l > 0) {
+                if (in_mult > c->xmult[l]) return TT_EINVAL; // nothing here enlarges an image
+                c->xmult[l] = in_mult;                       // pooled in between: charged at the size this layer reads
+            }
+        } else if (after_conv) {
+            const int64_t ch = layers[l - 1].n_out;
+            if (y.n_in % ch) return TT_EINVAL;
+            const int64_t pixels = y.n_in / ch;
+            if (pixels > c->xmult[l]) return TT_EINVAL;
+            c->xmult[l] = pixels;
+            w_mult = pixels;
+        } else if (l > 0 && y.n_in != layers[l - 1].n_out) {
+            return TT_EINVAL;
         }
         if (l == 0) { c->width[0] = y.n_in; c->xmult[0] = in_mult; }
         c->width[l + 1] = y.n_out;

@@ -150,6 +150,81 @@ def test_conv_chain_plan():
     assert p.cost == ref[0] and p.w() == ["r", "r"] and p.x() == ["R"] * 3      # large images: data parallel wins
 
 
+def conv_layer(c, k_, hw, rs, pad):
+    return tt.layer("conv", "none", c, k_, H=hw, W=hw, R=rs, S=rs, pad=pad)
+
+
+def test_mixed_chain_flatten_and_pooling_against_oracle():
+    # conv (4 -> 8 channels, 8 x 8) | pool to 4 x 4 | conv (8 -> 6, 4 x 4) | flatten | fc (6*16 -> 10) | fc (10 -> 4)
+    layers = [conv_layer(4, 8, 8, 3, 1), conv_layer(8, 6, 4, 3, 1), tt.layer("fc", "none", 96, 10), tt.layer("fc", "none", 10, 4)]
+    # the same graph written out for the oracle: cuttable widths, area multipliers of x_0..x_L and of W_1..W_L
+    # (x_1 is charged at the pooled size, x_2 at 16 pixels per channel, the first fc weight is 6 x 10 times 16 pixels)
+    chain = oc.make_chain(8, [4, 8, 6, 10, 4], xmult=[64, 16, 16, 1, 1], wmult=[0, 9, 9, 16, 1])
+    for k in (1, 2):
+        p = tt.tt_plan_chain(layers, 8, k)
+        cost, forms, delta = oc.chain_cost(chain, k, p.x(), p.g(), p.w())     # the oracle prices the planner's tiling
+        assert cost == p.cost and delta == [p.delta(j) for j in range(k)]
+        rec = tt.tt_plan_chain(layers, 8, k, tt.TT_PLAN_RECURSIVE)
+        assert rec.cost == oc.recursive(chain, k)[0] and rec.cost >= p.cost
+    # one cut: the planner's optimum is the oracle's exhaustive optimum over the whole mixed graph (9^... tilings)
+    sub = layers[1:3]
+    sub_chain = oc.make_chain(8, [8, 6, 10], xmult=[16, 16, 1], wmult=[0, 9, 16])
+    for k in (1, 2):
+        assert tt.tt_plan_chain(sub, 8, k).cost == oc.bruteforce(sub_chain, k)[0]
+    # flatten + fc is the convolution whose filter covers the whole image
+    as_conv = [conv_layer(8, 6, 4, 3, 1), conv_layer(6, 10, 4, 4, 0)]
+    assert tt.tt_plan_chain(sub, 8, 2).cost == tt.tt_plan_chain(as_conv, 8, 2).cost
+
+
+def alexnet_layers():
+    # public AlexNet layer dimensions (single tower); stride and pooling appear as the smaller image the next layer reads
+    return [conv_layer(3, 96, 227, 11, 0), conv_layer(96, 256, 27, 5, 2), conv_layer(256, 384, 13, 3, 1),
+            conv_layer(384, 384, 13, 3, 1), conv_layer(384, 256, 13, 3, 1), tt.layer("fc", "none", 9216, 4096),
+            tt.layer("fc", "none", 4096, 4096), tt.layer("fc", "none", 4096, 1000)]
+
+
+def vgg16_layers():
+    cfg = [(3, 64, 224), (64, 64, 224), (64, 128, 112), (128, 128, 112), (128, 256, 56), (256, 256, 56), (256, 256, 56),
+           (256, 512, 28), (512, 512, 28), (512, 512, 28), (512, 512, 14), (512, 512, 14), (512, 512, 14)]
+    return [conv_layer(c, k_, hw, 3, 1) for c, k_, hw in cfg] + [tt.layer("fc", "none", 25088, 4096),
+                                                                 tt.layer("fc", "none", 4096, 4096), tt.layer("fc", "none", 4096, 1000)]
+
+
+def pinned_cost(layers, b, k, x_letter, g_letter, w_letter):
+    L = len(layers)
+    return tt.tt_plan_eval(layers, b, k, [x_letter * k] * (L + 1), [g_letter * k] * (L + 1), [w_letter * k] * L)[0]
+
+
+@pytest.mark.parametrize("net", [alexnet_layers, vgg16_layers])
+def test_whole_network_plans_and_the_batch_size_crossover(net):
+    layers, k = net(), 3
+    costs = {}
+    for b in (32, 256, 2048):
+        p = tt.tt_plan_chain(layers, b, k)
+        # a returned tiling re-prices to the returned cost, and Algorithm 1 can only be worse
+        assert tt.tt_plan_eval(layers, b, k, p.x(), p.g(), p.w())[0] == p.cost
+        assert tt.tt_plan_chain(layers, b, k, tt.TT_PLAN_RECURSIVE).cost >= p.cost
+        data = pinned_cost(layers, b, k, "R", "R", "r")      # data parallelism: batch cut, weights replicated
+        costs[b] = (p.cost, data)
+        assert p.cost <= data
+    # data parallelism moves weight gradients, not activations (Sec. 2.2): its cost hardly depends on the batch (it is not
+    # exactly constant: Eq. 2 takes the cheapest form per product, and for small batches that is not always F1)
+    assert costs[32][1] <= costs[256][1] <= costs[2048][1] <= 1.3 * costs[32][1]
+    # the gain of the optimum over data parallelism shrinks as the batch grows (Sec. 6.1: larger batches favour
+    # data parallelism) ...
+    gain = {b: costs[b][1] / costs[b][0] for b in costs}
+    assert gain[32] > gain[256] > gain[2048] >= 1.0
+    # ... and the convolution layers, with their large images, are data parallel in the optimum already: every
+    # activation and gradient among them is cut along the batch only, forward products run as F1 (Sec. 6.1: "with the
+    # larger image size, data parallelism has better performance than model parallelism")
+    p = tt.tt_plan_chain(layers, 256, k)
+    n_conv = sum(1 for lay in layers if lay.kind == tt.TT_CONV2D)
+    assert all(t == "RRR" for t in p.x()[:n_conv]) and all(t == "RRR" for t in p.g()[:n_conv])
+    assert all(p.forms(l, tt.TT_OP_FWD) == "111" for l in range(1, n_conv + 1))
+    # the fully-connected tail is not: its first weight matrix is cut, never replicated
+    assert "r" not in p.w()[n_conv]
+
+
 def test_planner_argument_errors():
     with pytest.raises(tt.TilingError) as e:
         tt.tt_plan_chain(fc_layers([8, 8]), 8, 7)
@@ -157,6 +232,15 @@ def test_planner_argument_errors():
     with pytest.raises(tt.TilingError) as e:
         tt.tt_plan_chain([tt.layer("fc", "none", 8, 4), tt.layer("fc", "none", 5, 4)], 8, 1)
     assert e.value.status == 1
+    with pytest.raises(tt.TilingError) as e:                    # flatten must be channels x pixels
+        tt.tt_plan_chain([conv_layer(4, 8, 4, 3, 1), tt.layer("fc", "none", 8 * 16 + 1, 4)], 8, 1)
+    assert e.value.status == 1
+    with pytest.raises(tt.TilingError) as e:                    # an image cannot grow between layers
+        tt.tt_plan_chain([conv_layer(4, 8, 4, 3, 1), conv_layer(8, 8, 8, 3, 1)], 8, 1)
+    assert e.value.status == 1
+    with pytest.raises(tt.TilingError) as e:                    # convolution after fully-connected
+        tt.tt_plan_chain([tt.layer("fc", "none", 8, 16), conv_layer(16, 8, 1, 1, 0)], 8, 1)
+    assert e.value.status == 3
     with pytest.raises(tt.TilingError) as e:
         tt.tt_plan_chain(fc_layers([8, 8]), 8, 5, tt.TT_PLAN_EXACT)
     assert e.value.status == 3
