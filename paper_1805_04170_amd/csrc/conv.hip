@@ -211,6 +211,66 @@ __global__ __launch_bounds__(WN * 128, WN / 2) void conv_wgrad_kernel(const Conv
     core::tile_product<BM, BN, 2, WN, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, false, smem);
 }
 
+// Filters [Ks][R][S][Cs] -> [Cs][R][S][Ks] with the taps reversed: with these the gradient w.r.t. the input IS a forward
+// convolution of dY (padding R - 1 - pad), so it runs on the forward kernel, whose two operands are both K-contiguous
+// (the dedicated kernel has to transpose the filters in registers on their way to LDS and measured 25 % slower).
+struct FlipParams {
+    const void *src[kMaxShards];
+    void *dst[kMaxShards];
+    int32_t Ks, RS, Cs;
+};
+__global__ __launch_bounds__(256) void filter_flip_kernel(const FlipParams p)
+{
+    const int shard = blockIdx.y;
+    const int idx = blockIdx.x * 256 + threadIdx.x; // (ko block of 8, tap, c), c fastest: the 2-byte reads coalesce over c
+    const int total = p.Cs * p.RS * (p.Ks / 8);
+    if (idx >= total) return;
+    const int c = idx % p.Cs, rest = idx / p.Cs;
+    const int t = rest % p.RS, kb = rest / p.RS;
+    const uint16_t *src = reinterpret_cast<const uint16_t *>(p.src[shard]);
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t lo = src[((size_t)(kb * 8 + 2 * j) * p.RS + (p.RS - 1 - t)) * p.Cs + c];
+        const uint32_t hi = src[((size_t)(kb * 8 + 2 * j + 1) * p.RS + (p.RS - 1 - t)) * p.Cs + c];
+        w[j] = lo | (hi << 16);
+    }
+    const u32x4 o = {w[0], w[1], w[2], w[3]};
+    *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(p.dst[shard]) + ((size_t)c * p.RS + t) * p.Ks + kb * 8) = o;
+}
+
+// the same for channel counts that are multiples of 64: a workgroup turns one 64 (ko) x 64 (c) block of one tap around in
+// LDS, so both the reads (128 contiguous bytes of c) and the writes (128 contiguous bytes of ko) coalesce
+__global__ __launch_bounds__(256) void filter_flip_tiled_kernel(const FlipParams p)
+{
+    __shared__ uint16_t tile[64][64 + 8];
+    const int shard = blockIdx.y;
+    const int cb_n = p.Cs / 64, kb_n = p.Ks / 64;
+    int b = blockIdx.x;
+    const int cb = b % cb_n; b /= cb_n;
+    const int kb = b % kb_n;
+    const int t = b / kb_n;
+    const uint16_t *src = reinterpret_cast<const uint16_t *>(p.src[shard]);
+    uint16_t *dst = reinterpret_cast<uint16_t *>(p.dst[shard]);
+    const int tid = threadIdx.x, row = tid >> 3, cv = (tid & 7) * 8; // 32 rows x 8 vectors per pass
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int ko = kb * 64 + row + 32 * h;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(src + ((size_t)ko * p.RS + (p.RS - 1 - t)) * p.Cs + cb * 64 + cv);
+        *reinterpret_cast<u32x4 *>(&tile[row + 32 * h][cv]) = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int c = row + 32 * h; // output row: channel c of the block, 8 consecutive ko per lane
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = (uint32_t)tile[cv + 2 * j][c] | ((uint32_t)tile[cv + 2 * j + 1][c] << 16);
+        const u32x4 o = {w[0], w[1], w[2], w[3]};
+        *reinterpret_cast<u32x4 *>(dst + ((size_t)(cb * 64 + c) * p.RS + t) * p.Ks + kb * 64 + cv) = o;
+    }
+}
+
 template <typename Kern> tt_status launch(Kern kern, size_t smem, ConvParams &p, int BM, int BN, int threads, int count, hipStream_t s)
 {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
@@ -298,7 +358,7 @@ bool aligned16(const void *const *ptrs, int n)
 // Shard geometry: Ns images, Cs input channels, Ks output channels per shard.
 tt_status launch_conv(int op, int count, const void *const *A, const void *const *B, void *const *C, int64_t Ns,
                       int64_t Cs, int64_t Ks, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad, int out_dtype,
-                      int act, void *stream)
+                      int act, void *stream, void *const *flip_ws)
 {
     if (!A || !B || !C || count < 1 || count > kMaxShards) return TT_EINVAL;
     if (Ns <= 0 || Cs <= 0 || Ks <= 0 || H <= 0 || W <= 0 || R <= 0 || S <= 0 || pad < 0) return TT_EINVAL;
@@ -339,6 +399,28 @@ tt_status launch_conv(int op, int count, const void *const *A, const void *const
     ProfileScope scope(stream, kclass, count, M, N, K, bytes * (uint64_t)count,
                        2ull * (uint64_t)M * (uint64_t)N * (uint64_t)K * (uint64_t)count);
     if (op == TT_OP_FWD) return obf ? launch_gather_a<0, true>(p, count, s) : launch_gather_a<0, false>(p, count, s);
+    if (op == TT_OP_DGRAD && flip_ws && R == S && pad <= R - 1 && !std::getenv("TT_CONV_DGRAD_DIRECT")) {
+        // as a forward convolution of dY (P x Q images, Ks channels) with the flipped filters, padding R - 1 - pad;
+        // M, N, K of the implicit GEMM are the same
+        FlipParams f;
+        for (int i = 0; i < kMaxShards; ++i) {
+            if (i < count && (!flip_ws[i] || (reinterpret_cast<uintptr_t>(flip_ws[i]) & 15))) return TT_EINVAL;
+            f.src[i] = i < count ? B[i] : nullptr;
+            f.dst[i] = i < count ? flip_ws[i] : nullptr;
+            p.B[i] = i < count ? flip_ws[i] : nullptr;
+        }
+        f.Ks = (int32_t)Ks; f.RS = (int32_t)(R * S); f.Cs = (int32_t)Cs;
+        if (Cs % 64 == 0 && Ks % 64 == 0) {
+            hipLaunchKernelGGL(filter_flip_tiled_kernel, dim3((uint32_t)((Cs / 64) * (Ks / 64) * R * S), (uint32_t)count), dim3(256), 0, s, f);
+        } else {
+            const int64_t threads = Cs * R * S * (Ks / 8);
+            hipLaunchKernelGGL(filter_flip_kernel, dim3((uint32_t)((threads + 255) / 256), (uint32_t)count), dim3(256), 0, s, f);
+        }
+        if (hipGetLastError() != hipSuccess) return TT_EDEVICE;
+        p.g = ConvGeom{(int32_t)Ns, (int32_t)P, (int32_t)Q, (int32_t)H, (int32_t)W, (int32_t)R, (int32_t)S,
+                       (int32_t)(R - 1 - pad), (int32_t)Ks, (int32_t)Cs};
+        return obf ? launch_gather_a<0, true>(p, count, s) : launch_gather_a<0, false>(p, count, s);
+    }
     if (op == TT_OP_DGRAD) return obf ? launch_gather_a<1, true>(p, count, s) : launch_gather_a<1, false>(p, count, s);
     return obf ? launch_wgrad<true>(p, count, s) : launch_wgrad<false>(p, count, s);
 }

@@ -130,9 +130,14 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
         if ((st = prepare_operand(W, aWt, k, 2, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
         OutputPlan op;
         if ((st = plan_output(f, a.tdX, a.dX, d.N * hw, d.C, k, a.dtype, TT_ACT_NONE, ws, &op)) != TT_OK) return st;
+        // scratch for the flipped filters of every shard (the dX product then runs as a forward convolution of dY)
+        void *flip[kMaxShards];
+        const size_t fbytes = (size_t)(d.K >> k3) * (size_t)rs * (size_t)(d.C >> k2) * 2;
+        for (int s = 0; s < n; ++s) flip[s] = ws.take(fbytes);
+        if (ws.overflow) return TT_EWORKSPACE;
         if (!ws.dry) {
             st = launch_conv(TT_OP_DGRAD, n, Ga.ptr, Wa.ptr, op.gemm_out, d.N >> k1, d.C >> k2, d.K >> k3, d.H, d.W, d.R, d.S,
-                             d.pad, op.gemm_dtype, TT_ACT_NONE, a.stream);
+                             d.pad, op.gemm_dtype, TT_ACT_NONE, a.stream, flip);
             if (st != TT_OK) return st;
             if ((st = finish_output(op, a.tdX, a.dX, d.N * hw, d.C, k, a.dtype, TT_ACT_NONE, a.stream)) != TT_OK) return st;
         }

@@ -127,9 +127,11 @@ tt_status launch_gemm_v4(int count, const void *const *A, const void *const *B, 
 // Convolution shard products (conv.hip).  op TT_OP_FWD: A = X shards, B = filter shards, C = Y shards;
 // TT_OP_DGRAD: A = dY, B = filters, C = dX;  TT_OP_WGRAD: A = dY, B = X, C = dW.  Ns images, Cs input channels and
 // Ks output channels per shard; bf16 operands.
+// flip_ws (TT_OP_DGRAD only, optional): per shard a 16-byte aligned scratch buffer of the filter shard's size; when
+// given (and R == S, pad <= R - 1) the filters are flipped into it and the product runs on the forward kernel.
 tt_status launch_conv(int op, int count, const void *const *A, const void *const *B, void *const *C, int64_t Ns,
                       int64_t Cs, int64_t Ks, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad, int out_dtype,
-                      int act, void *stream);
+                      int act, void *stream, void *const *flip_ws = nullptr);
 
 // ---- optional kernel timing (profile.cpp).  A scope object brackets one launch with two events when the calling
 // thread has recording switched on; otherwise it does nothing.
