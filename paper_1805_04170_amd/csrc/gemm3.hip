@@ -97,10 +97,12 @@ template <bool A_KC, bool B_KC> tt_status launch_layout(core3::Params3 &p, int o
     }
     // short K loops (the weight gradients at batch 256): loads issued between the k-steps, see run_tiles
     // Loads issued between the k-steps (see run_tiles) measured faster for the products with bf16 results (the weight
-    // gradients: short K loops) and slower or equal for those that write fp32 partial sums (long K loops), so only the
-    // former use it.  (TT_V3_ILV=0: never; tuning aid.)
+    // gradients: short K loops) ...  (TT_V3_ILV=0: never; tuning aid.)
     static const bool ilv = [] { const char *e = std::getenv("TT_V3_ILV"); return !e || std::atoi(e) != 0; }();
     if (bf && vec) return ilv ? launch_cfg<64, 2, A_KC, B_KC, true, true, true>(p, s) : launch_cfg<64, 2, A_KC, B_KC, true, true>(p, s);
+    // ... and, among the products that write fp32 partial sums, for the NN layout (B read with LDS transpose reads)
+    if constexpr (A_KC && !B_KC)
+        if (!bf && ilv) return launch_cfg<64, 2, A_KC, B_KC, false, false, true>(p, s);
     return bf ? launch_cfg<64, 2, A_KC, B_KC, true, false>(p, s) : launch_cfg<64, 2, A_KC, B_KC, false, false>(p, s);
 }
 
