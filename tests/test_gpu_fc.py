@@ -154,6 +154,51 @@ def test_backward_overlapped_equals_backward(relu):
             assert torch.equal(g.view(torch.int16), r.view(torch.int16)), rep
 
 
+def test_whole_step_as_replayed_graph_equals_eager():
+    # what bench.py times: one forward + backward step of a planned chain captured into a HIP graph and replayed; every
+    # replay must reproduce the eager step bit for bit (eager work and synchronisations between the replays)
+    from synthetic.configs import FcChain
+    cfg = FcChain("graph_small", 256, (2048, 1024, 1024, 1000), 3, "bf16", 0.02, 2006)
+    plan = plan_for(cfg)
+    dt, k, b, L = cfg.dtype, cfg.k, cfg.batch, cfg.n_layers
+    x0, Ws, gL = chain_tensors(cfg)
+    tx, tg, tw = plan.x(), plan.g(), plan.w()
+    layers = [tt.layer("fc", "relu" if cfg.act(l) else "none", cfg.widths[l - 1], cfg.widths[l]) for l in range(1, L + 1)]
+    xs = [shards_to_dev(x0, tx[0], True)] + [alloc_shards(b, cfg.widths[l], tx[l], torch.bfloat16, fill=float("nan")) for l in range(1, L + 1)]
+    gs = [alloc_shards(b, cfg.widths[l], tg[l], torch.bfloat16, fill=float("nan")) for l in range(L)] + [shards_to_dev(gL, tg[L], True)]
+    wsh = [shards_to_dev(Ws[l], tw[l], True) for l in range(L)]
+    dws = [alloc_shards(cfg.widths[l], cfg.widths[l + 1], tw[l], torch.bfloat16, fill=float("nan")) for l in range(L)]
+    need = 256
+    for l in range(1, L + 1):
+        f = [plan.forms(l, op) for op in range(3)]
+        need = max(need, tt.tt_fc_workspace_bytes(layers[l - 1], b, k, dt, tt.TT_OP_FWD, tx[l - 1], tw[l - 1], tx[l], forms_a=f[0]),
+                   tt.tt_fc_workspace_bytes(layers[l - 1], b, k, dt, tt.TT_OP_DGRAD, tx[l - 1], tw[l - 1], tx[l], tg[l], tg[l - 1], f[1], f[2]))
+    ws = workspace(need)
+
+    def step():
+        for l in range(1, L + 1):
+            tt.tt_fc_forward(layers[l - 1], b, k, dt, tx[l - 1], tw[l - 1], tx[l], plan.forms(l, tt.TT_OP_FWD), xs[l - 1], wsh[l - 1], xs[l], ws)
+        for l in range(L, 0, -1):
+            tt.tt_fc_backward(layers[l - 1], b, k, dt, tx[l - 1], tw[l - 1], tx[l], tg[l], tg[l - 1], plan.forms(l, tt.TT_OP_DGRAD),
+                              plan.forms(l, tt.TT_OP_WGRAD), xs[l - 1], wsh[l - 1], xs[l], gs[l], gs[l - 1], dws[l - 1], ws)
+
+    outputs = [t for l in range(1, L + 1) for t in xs[l]] + [t for l in range(L) for t in gs[l]] + [t for l in range(L) for t in dws[l]]
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outputs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in outputs:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, r in zip(outputs, ref):
+            assert torch.equal(t.view(torch.int16), r.view(torch.int16)), rep
+
+
 def test_uneven_and_bad_workspace_are_refused():
     lay = tt.layer("fc", "none", 10, 6)
     x = [torch.zeros(8, dtype=torch.bfloat16, device=DEV)] * 4
