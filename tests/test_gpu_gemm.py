@@ -90,6 +90,8 @@ def test_bf16_persistent_engine(ta, tb, out_dt):
     check(8, 1544, 1528, 128, ta, tb, "bf16", out_dt, True, 42)
     check(8, 1032, 1544, 64, ta, tb, "bf16", out_dt, False, 43)
     check(3, 2056, 1800, 320, ta, tb, "bf16", out_dt, False, 44)
+    # three output tiles per workgroup and a K loop of four tiles: a full tile's write-out rides along the next one
+    check(8, 2056, 2312, 256, ta, tb, "bf16", out_dt, True, 48)
 
 
 @pytest.mark.parametrize("ta,tb", LAYOUTS)
