@@ -11,6 +11,8 @@ Modules
   execute  - aligned forms, per-shard execution, reduction       (Sec. 4.2.1, Sec. 5.2)
   cost     - conversion costs, Eq. (2), Algorithm 1, brute force (Sec. 4.2-4.3; C code in cost.c)
   naive_comm - the closed-form volumes of the worked MLP example (Sec. 2.2)
+  graph    - cost and exhaustive search on a general dataflow graph: d-dimensional tensors, contractions,
+             element-wise and batch-only operators (Sec. 4.5)
 
 Parity pins: every function here is pinned by tests/test_oracle_*.py except
 the k>1 cost model, whose only pins are closed forms, the k=1 physical traffic
