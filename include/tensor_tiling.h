@@ -152,6 +152,48 @@ tt_status tt_retile_gate(void *const *dst, tt_tiling B, const void *const *src, 
 tt_status tt_reduce(void *const *dst, tt_tiling B, int out_dtype, const float *const *partials,
                     const uint8_t *forms, int k, int64_t rows, int64_t cols, int act, void *stream);
 
+/* ------------------------------------------------- planner, general graphs
+ * The tiling search on any dataflow graph (Sec. 4.2.2: operators organised into breadth-first levels, Eqs. 4-5 over
+ * the tensors shared by adjacent levels; Sec. 4.3: Algorithm 1; Sec. 4.5: tensors with up to four dimensions - one
+ * basic tiling per dimension plus replication - and operators other than products).  Host only.
+ * A letter is a dimension index (the cut that halves it) or TT_LETTER_REP; a k-cut tiling is k letters, cut 0 first.
+ * Cost model and readings as for tt_plan_chain (letters R and C there are dimensions 0 and 1 here).
+ *   tensor: ndim, shape, same_as = index of an EARLIER tensor of the same shape whose tiling it shares (a weight
+ *           gradient is stored like its weight), or -1.
+ *   operator kinds and their aligned forms:
+ *     TT_GOP_CONTRACT     z = x (.) y, in = {x, y}; m = {dim of x, dim of z} kept from x, n = {dim of y, dim of z} kept
+ *                         from y, kk = {dim of x, dim of y} contracted.  Form 0: x cut along m, y replicated, z cut
+ *                         along m;  1: x replicated, y cut along n, z cut along n;  2: both cut along kk, z partial sums.
+ *                         x.y: m {0,0} n {1,1} kk {1,0};  x.y^T: n {0,1} kk {1,1};  x^T.y: m {1,0} kk {0,0};
+ *                         convolution X[N,C,H,W] * W[K,C,R,S] -> Y[N,K,P,Q]: m {0,0} n {0,1} kk {1,1}.
+ *     TT_GOP_ELEMENTWISE  1..4 inputs and the output of one shape; form d: every operand cut along dimension d.
+ *     TT_GOP_BATCH        any other operator: every operand cut along dimension 0 (equal extents there).
+ * pins: NULL, or n_tensors * k letters; a tensor whose first letter is TT_LETTER_FREE is left to the search.
+ * mode TT_PLAN_EXACT: minimum over every joint assignment of k-cut sequences, found by minimising the tensors out
+ * one at a time (TT_EUNSUPPORTED when every order would need a cost table of more than 2^24 entries);
+ * TT_PLAN_RECURSIVE: Algorithm 1, each cut by the level-by-level dynamic program (cost = sum_j 2^j delta_j, forms
+ * chosen cut by cut; TT_EUNSUPPORTED when a level has more than 2^28 joint one-cut states).
+ * Errors: TT_EINVAL (malformed graph or letters), TT_EINFEASIBLE (no tiling with even cuts), TT_ENOMEM. */
+enum { TT_GRAPH_MAX_DIMS = 4, TT_GRAPH_MAX_INPUTS = 4, TT_GRAPH_MAX_TENSORS = 4096, TT_GRAPH_MAX_OPS = 4096 };
+enum { TT_LETTER_REP = 255, TT_LETTER_FREE = 253 };
+enum { TT_GOP_CONTRACT = 0, TT_GOP_ELEMENTWISE = 1, TT_GOP_BATCH = 2 };
+typedef struct { int32_t ndim; int32_t same_as; int64_t shape[4]; } tt_graph_tensor;
+typedef struct { int32_t kind, n_in; int32_t in[4]; int32_t out; int32_t m[2], n[2], kk[2]; } tt_graph_op;
+typedef struct tt_graph_plan tt_graph_plan; /* opaque; host memory owned by the library until tt_graph_plan_free */
+tt_status tt_plan_graph(const tt_graph_tensor *tensors, int n_tensors, const tt_graph_op *ops, int n_ops, int k,
+                        uint32_t mode, const uint8_t *pins, tt_graph_plan **out);
+/* cost of given tilings (n_tensors * k letters; tensors stored alike must agree); delta_out (k) and forms_out
+ * (n_ops * k, the cheapest feasible form sequence of every operator) may be NULL */
+tt_status tt_graph_eval(const tt_graph_tensor *tensors, int n_tensors, const tt_graph_op *ops, int n_ops, int k,
+                        const uint8_t *letters, uint64_t *cost_elems, uint64_t *delta_out, uint8_t *forms_out);
+uint64_t tt_graph_plan_cost(const tt_graph_plan *p);
+uint64_t tt_graph_plan_delta(const tt_graph_plan *p, int cut);
+int tt_graph_plan_levels(const tt_graph_plan *p);              /* number of breadth-first levels */
+int tt_graph_plan_level_of(const tt_graph_plan *p, int op);     /* level of an operator */
+tt_status tt_graph_plan_tiling(const tt_graph_plan *p, int tensor, uint8_t *letters_out /* k */);
+tt_status tt_graph_plan_forms(const tt_graph_plan *p, int op, uint8_t *forms_out /* k */);
+void tt_graph_plan_free(tt_graph_plan *p);
+
 /* --------------------------------------------------------- shard products */
 
 /* 2^k (or any count of) independent products C_s = op(A_s) op(B_s) of identical shape in one launch

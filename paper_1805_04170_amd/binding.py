@@ -27,7 +27,11 @@ EXPORTS = [
     "tt_plan_delta", "tt_plan_tiling", "tt_plan_forms", "tt_plan_free", "tt_retile", "tt_retile_gate", "tt_reduce",
     "tt_shard_gemm", "tt_fc_workspace_bytes", "tt_fc_forward", "tt_fc_backward", "tt_fc_backward_overlapped", "tt_conv_workspace_bytes",
     "tt_conv_forward", "tt_conv_backward", "tt_profile_begin", "tt_profile_end", "tt_profile_get",
+    "tt_plan_graph", "tt_graph_eval", "tt_graph_plan_cost", "tt_graph_plan_delta", "tt_graph_plan_levels",
+    "tt_graph_plan_level_of", "tt_graph_plan_tiling", "tt_graph_plan_forms", "tt_graph_plan_free",
 ]
+TT_LETTER_REP, TT_LETTER_FREE = 255, 253
+TT_GOP_CONTRACT, TT_GOP_ELEMENTWISE, TT_GOP_BATCH = 0, 1, 2
 KERNEL_NAMES = ["convert", "gate", "reduce", "gemm_nn", "gemm_nt", "gemm_tn", "gemm_tt", "gemm_generic", "conv_fwd",
                 "conv_dgrad", "conv_wgrad"]
 
@@ -40,6 +44,15 @@ class TilingError(RuntimeError):
 
 class tt_tiling(ctypes.Structure):
     _fields_ = [("cut", ctypes.c_uint8 * TT_MAX_K)]
+
+
+class tt_graph_tensor(ctypes.Structure):
+    _fields_ = [("ndim", ctypes.c_int32), ("same_as", ctypes.c_int32), ("shape", ctypes.c_int64 * 4)]
+
+
+class tt_graph_op(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("n_in", ctypes.c_int32), ("in_", ctypes.c_int32 * 4), ("out", ctypes.c_int32),
+                ("m", ctypes.c_int32 * 2), ("n", ctypes.c_int32 * 2), ("kk", ctypes.c_int32 * 2)]
 
 
 class tt_kernel_record(ctypes.Structure):
@@ -85,6 +98,20 @@ def lib():
         L.tt_plan_forms.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, _u8p]
         L.tt_plan_free.argtypes = [ctypes.c_void_p]
         L.tt_plan_free.restype = None
+        gtp, gop = ctypes.POINTER(tt_graph_tensor), ctypes.POINTER(tt_graph_op)
+        L.tt_plan_graph.argtypes = [gtp, ctypes.c_int, gop, ctypes.c_int, ctypes.c_int, ctypes.c_uint32, _u8p,
+                                    ctypes.POINTER(ctypes.c_void_p)]
+        L.tt_graph_eval.argtypes = [gtp, ctypes.c_int, gop, ctypes.c_int, ctypes.c_int, _u8p, _u64p, _u64p, _u8p]
+        L.tt_graph_plan_cost.argtypes = [ctypes.c_void_p]
+        L.tt_graph_plan_cost.restype = ctypes.c_uint64
+        L.tt_graph_plan_delta.argtypes = [ctypes.c_void_p, ctypes.c_int]
+        L.tt_graph_plan_delta.restype = ctypes.c_uint64
+        L.tt_graph_plan_levels.argtypes = [ctypes.c_void_p]
+        L.tt_graph_plan_level_of.argtypes = [ctypes.c_void_p, ctypes.c_int]
+        L.tt_graph_plan_tiling.argtypes = [ctypes.c_void_p, ctypes.c_int, _u8p]
+        L.tt_graph_plan_forms.argtypes = [ctypes.c_void_p, ctypes.c_int, _u8p]
+        L.tt_graph_plan_free.argtypes = [ctypes.c_void_p]
+        L.tt_graph_plan_free.restype = None
         L.tt_retile.argtypes = [_vpp, tt_tiling, _vpp, tt_tiling, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
                                 ctypes.c_int, ctypes.c_void_p]
         L.tt_retile_gate.argtypes = [_vpp, tt_tiling, _vpp, tt_tiling, _vpp, tt_tiling, ctypes.c_int, ctypes.c_int64,
@@ -259,6 +286,92 @@ def tt_plan_eval(layers, batch, k, x, g, w):
     _check(lib().tt_plan_eval(_layers(layers), L, batch, k, xa, ga, wa, ctypes.byref(cost), delta, fo), "tt_plan_eval")
     f = [["".join("123"[fo[(l * 3 + op) * k + j]] for j in range(k)) for op in range(3)] for l in range(L)]
     return cost.value, [delta[j] for j in range(k)], f
+
+
+# ----------------------------------------------------- planner, general graphs
+
+def graph_tensor(shape, same_as=-1):
+    t = tt_graph_tensor()
+    t.ndim, t.same_as = len(shape), same_as
+    for d, n in enumerate(shape):
+        t.shape[d] = n
+    return t
+
+
+def graph_op(kind, ins, out, m=(0, 0), n=(0, 0), kk=(0, 0)):
+    o = tt_graph_op()
+    o.kind, o.n_in, o.out = kind, len(ins), out
+    for i, v in enumerate(ins):
+        o.in_[i] = v
+    o.m[0], o.m[1], o.n[0], o.n[1], o.kk[0], o.kk[1] = m[0], m[1], n[0], n[1], kk[0], kk[1]
+    return o
+
+
+def _graph_letters(tilings, n_tensors, k):
+    """tilings: {tensor: sequence of k letters (dimension index or 'r')}; tensors left out are free"""
+    buf = (ctypes.c_uint8 * max(n_tensors * k, 1))(*([TT_LETTER_FREE] * max(n_tensors * k, 1)))
+    for i, t in (tilings or {}).items():
+        assert len(t) == k
+        for j, l in enumerate(t):
+            buf[i * k + j] = TT_LETTER_REP if l == "r" else int(l)
+    return buf
+
+
+class GraphPlan:
+    """Owner of a tt_graph_plan; accessors mirror the C ones (letters come back as dimension indices or 'r')."""
+
+    def __init__(self, handle, k):
+        self._h, self.k = handle, k
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib().tt_graph_plan_free(self._h)
+            self._h = None
+
+    @property
+    def cost(self):
+        return lib().tt_graph_plan_cost(self._h)
+
+    def delta(self, cut):
+        return lib().tt_graph_plan_delta(self._h, cut)
+
+    @property
+    def n_levels(self):
+        return lib().tt_graph_plan_levels(self._h)
+
+    def level_of(self, op):
+        return lib().tt_graph_plan_level_of(self._h, op)
+
+    def tiling(self, tensor):
+        buf = (ctypes.c_uint8 * max(self.k, 1))()
+        _check(lib().tt_graph_plan_tiling(self._h, tensor, buf), "tt_graph_plan_tiling")
+        return tuple("r" if buf[j] == TT_LETTER_REP else int(buf[j]) for j in range(self.k))
+
+    def forms(self, op):
+        buf = (ctypes.c_uint8 * max(self.k, 1))()
+        _check(lib().tt_graph_plan_forms(self._h, op, buf), "tt_graph_plan_forms")
+        return [int(buf[j]) for j in range(self.k)]
+
+
+def tt_plan_graph(tensors, ops, k, mode=TT_PLAN_EXACT, pins=None):
+    ta = (tt_graph_tensor * len(tensors))(*tensors)
+    oa = (tt_graph_op * len(ops))(*ops)
+    h = ctypes.c_void_p()
+    _check(lib().tt_plan_graph(ta, len(tensors), oa, len(ops), k, mode,
+                               _graph_letters(pins, len(tensors), k) if pins else None, ctypes.byref(h)), "tt_plan_graph")
+    return GraphPlan(h, k)
+
+
+def tt_graph_eval(tensors, ops, k, tilings):
+    """Returns (cost, delta[k], forms[op][k])."""
+    ta = (tt_graph_tensor * len(tensors))(*tensors)
+    oa = (tt_graph_op * len(ops))(*ops)
+    cost = ctypes.c_uint64()
+    delta = (ctypes.c_uint64 * max(k, 1))()
+    fo = (ctypes.c_uint8 * max(len(ops) * k, 1))()
+    _check(lib().tt_graph_eval(ta, len(tensors), oa, len(ops), k, _graph_letters(tilings, len(tensors), k),
+                               ctypes.byref(cost), delta, fo), "tt_graph_eval")
+    return cost.value, [delta[j] for j in range(k)], [[fo[q * k + j] for j in range(k)] for q in range(len(ops))]
 
 
 # --------------------------------------------------------------- conversions

@@ -1,0 +1,270 @@
+"""The library's tiling search on general dataflow graphs (host code; no GPU) against oracle/graph.py."""
+import random
+
+import pytest
+
+import paper_1805_04170_amd as tt
+from oracle import graph as og
+from oracle import cost as oc
+
+KIND = {"contract": tt.TT_GOP_CONTRACT, "elementwise": tt.TT_GOP_ELEMENTWISE, "batch": tt.TT_GOP_BATCH}
+
+
+def to_lib(tensors, ops):
+    T = [tt.graph_tensor(t["shape"], -1 if t.get("same_as") is None else t["same_as"]) for t in tensors]
+    O = []
+    for op in ops:
+        if op["kind"] == "contract":
+            O.append(tt.graph_op(KIND["contract"], op["ins"], op["out"], m=op["m"], n=op["n"], kk=op["k"]))
+        else:
+            O.append(tt.graph_op(KIND[op["kind"]], op["ins"], op["out"]))
+    return T, O
+
+
+def full_tilings(tensors, t):
+    """{variable: tiling} -> a tiling for every tensor (members of a same_as group repeat their root's)"""
+    return {i: t[og.root(tensors, i)] for i in range(len(tensors))}
+
+
+def random_net(rnd, batch_choices=(8, 12, 6, 16), width_choices=(4, 6, 8, 10, 16), max_layers=3, four_d=False):
+    """a small training graph: an MLP with optional residual adds and activation nodes, its backward pass, a batch-only
+    loss at the end.  Graph description only."""
+    T, ops = [], []
+
+    def new(shape, same=None):
+        T.append({"shape": tuple(shape), "same_as": same})
+        return len(T) - 1
+
+    b = rnd.choice(batch_choices)
+    L = rnd.randint(1, max_layers)
+    widths = [rnd.choice(width_choices)]
+    x = [new((b, widths[0]))]
+    ws = []
+    acts = []
+    for l in range(L):
+        res = rnd.random() < 0.4
+        widths.append(widths[-1] if res else rnd.choice(width_choices))
+        w = new((widths[-2], widths[-1]))
+        ws.append(w)
+        h = new((b, widths[-1]))
+        ops.append(og.matmul(x[-1], w, h))
+        if res:
+            h2 = new((b, widths[-1]))
+            ops.append({"kind": "elementwise", "ins": [h, x[-1]], "out": h2})
+            h = h2
+        if rnd.random() < 0.5:
+            h2 = new((b, widths[-1]))
+            ops.append({"kind": "elementwise", "ins": [h], "out": h2})
+            h = h2
+        acts.append((x[-1], h))
+        x.append(h)
+    target = new((b, 1))
+    loss_grad = new((b, widths[-1]))
+    ops.append({"kind": "batch", "ins": [x[-1], target], "out": loss_grad})
+    g = loss_grad
+    for l in reversed(range(L)):
+        xin, _ = acts[l]
+        dw = new(T[ws[l]]["shape"], ws[l])
+        ops.append(og.matmul(xin, g, dw, ta=True))
+        gi = new(T[xin]["shape"])
+        ops.append(og.matmul(g, ws[l], gi, tb=True))
+        g = gi
+    return T, ops
+
+
+def random_tilings(rnd, tensors, k):
+    """mostly tilings whose cuts are even (the operators may still find no feasible form), sometimes any letters"""
+    t = {}
+    for v in og.variables(tensors):
+        if rnd.random() < 0.9:
+            t[v] = rnd.choice(og.feasible_tilings(tensors[v], k))
+        else:
+            t[v] = tuple(rnd.choice(og.letters_of(tensors[v])) for _ in range(k))
+    return t
+
+
+@pytest.mark.parametrize("k", [1, 2, 3])
+def test_eval_equals_the_oracle_on_random_graphs(k):
+    rnd = random.Random(500 + k)
+    seen_inf = seen_fin = 0
+    for trial in range(60):
+        tensors, ops = random_net(rnd)
+        T, O = to_lib(tensors, ops)
+        t = random_tilings(rnd, tensors, k)
+        want = og.graph_cost(tensors, ops, k, t)
+        if want == og.INF:
+            seen_inf += 1
+            with pytest.raises(tt.TilingError) as e:
+                tt.tt_graph_eval(T, O, k, full_tilings(tensors, t))
+            assert e.value.status == 2
+            continue
+        seen_fin += 1
+        cost, delta, forms = tt.tt_graph_eval(T, O, k, full_tilings(tensors, t))
+        assert cost == want
+        assert sum(d << j for j, d in enumerate(delta)) == cost
+        # the reported forms price every operator at its minimum
+        for q, op in enumerate(ops):
+            c, f = og.op_cost(op, tensors, t, k, want_forms=True)
+            assert list(forms[q]) == list(f) or _forms_cost(op, tensors, t, k, forms[q]) == c
+    assert seen_fin > 10 and (k == 1 or seen_inf > 0)
+
+
+def _forms_cost(op, tensors, t, k, seq):
+    ids = [og.root(tensors, i) for i in op["ins"]] + [og.root(tensors, op["out"])]
+    areas = [og.tile_areas(tensors[i]["shape"], t[i]) for i in ids]
+    fl = og.forms_of(op, tensors)
+    total = 0
+    for j, f in enumerate(seq):
+        a_in, a_out, _ = fl[f]
+        c = sum(og.conv_cost(t[ids[q]][j], a_in[q], areas[q][j]) for q in range(len(a_in)))
+        total += (c + og.conv_cost(a_out, t[ids[-1]][j], areas[-1][j])) << j
+    return total
+
+
+def test_four_dimensional_tensors_and_convolutions():
+    # conv -> relu -> conv with the backward products; activations [N,C,H,W], filters [K,C,R,S]
+    rnd = random.Random(9)
+    N, H, R = 8, 4, 3
+    c0, c1, c2 = 4, 6, 8
+    T = lambda shape, same=None: {"shape": shape, "same_as": same}
+    tensors = [T((N, c0, H, H)), T((c1, c0, R, R)), T((N, c1, H, H)), T((N, c1, H, H)), T((c2, c1, R, R)), T((N, c2, H, H)),
+               T((N, c2, H, H)), T((c2, c1, R, R), 4), T((N, c1, H, H)), T((N, c1, H, H)), T((c1, c0, R, R), 1)]
+    conv = lambda x, w, y: {"kind": "contract", "ins": [x, w], "out": y, "m": (0, 0), "n": (0, 1), "k": (1, 1)}
+    dgrad = lambda dy, w, dx: {"kind": "contract", "ins": [dy, w], "out": dx, "m": (0, 0), "n": (1, 1), "k": (1, 0)}
+    wgrad = lambda x, dy, dw: {"kind": "contract", "ins": [x, dy], "out": dw, "m": (1, 1), "n": (1, 0), "k": (0, 0)}
+    ops = [conv(0, 1, 2), {"kind": "elementwise", "ins": [2], "out": 3}, conv(3, 4, 5),
+           wgrad(3, 6, 7), dgrad(6, 4, 8), {"kind": "elementwise", "ins": [8, 2], "out": 9}, wgrad(0, 9, 10)]
+    Tl, Ol = to_lib(tensors, ops)
+    for k in (1, 2):
+        for trial in range(40):
+            t = random_tilings(rnd, tensors, k)
+            want = og.graph_cost(tensors, ops, k, t)
+            if want == og.INF:
+                continue
+            assert tt.tt_graph_eval(Tl, Ol, k, full_tilings(tensors, t))[0] == want
+    plan = tt.tt_plan_graph(Tl, Ol, 1)
+    t = {v: plan.tiling(v) for v in og.variables(tensors)}
+    assert og.graph_cost(tensors, ops, 1, t) == plan.cost
+    # data parallelism (every activation cut along the batch, filters replicated) is one candidate: 2 |W| per filter
+    dp = {v: (("r",) if v in (1, 4) else (0,)) for v in og.variables(tensors)}
+    assert og.graph_cost(tensors, ops, 1, dp) == 2 * (c1 * c0 * R * R + c2 * c1 * R * R)
+    assert plan.cost <= og.graph_cost(tensors, ops, 1, dp)
+
+
+@pytest.mark.parametrize("k,max_layers", [(1, 2), (2, 1)])
+def test_exact_search_equals_exhaustive_search(k, max_layers):
+    rnd = random.Random(40 + k)
+    done = 0
+    while done < (8 if k == 1 else 5):
+        tensors, ops = random_net(rnd, max_layers=max_layers)
+        var = og.variables(tensors)
+        # the exhaustive search is plain Python: leave about 2 * 10^4 joint assignments free, pin the other tensors
+        free = list(var)
+        rnd.shuffle(free)
+        pins = {}
+        while (3 ** k) ** len(free) > 2e4:
+            v = free.pop()
+            pins[v] = rnd.choice(og.feasible_tilings(tensors[v], k))
+        if k == 1 and pins:
+            continue
+        done += 1
+        T, O = to_lib(tensors, ops)
+        want, arg = og.bruteforce(tensors, ops, k, pins)
+        if want == og.INF:
+            with pytest.raises(tt.TilingError) as e:
+                tt.tt_plan_graph(T, O, k, tt.TT_PLAN_EXACT, pins=pins)
+            assert e.value.status == 2
+            continue
+        plan = tt.tt_plan_graph(T, O, k, tt.TT_PLAN_EXACT, pins=pins)
+        assert plan.cost == want
+        t = {v: plan.tiling(v) for v in var}
+        assert og.graph_cost(tensors, ops, k, t) == want           # the returned tiling really costs that
+        for v, p in pins.items():
+            assert t[v] == tuple(p)
+        for i in range(len(tensors)):                                # stored-alike tensors report the same tiling
+            assert plan.tiling(i) == t[og.root(tensors, i)]
+        assert sum(plan.delta(j) << j for j in range(k)) == plan.cost
+        assert tt.tt_plan_graph(T, O, k, tt.TT_PLAN_EXACT).cost <= want     # fewer pins can only be cheaper
+
+
+@pytest.mark.parametrize("k", [1, 2, 3])
+def test_recursive_search_is_a_valid_run_of_algorithm_1(k):
+    rnd = random.Random(70 + k)
+    done = 0
+    while done < 6:
+        # (the batch-only loss node halves the batch at every cut: keep it divisible by 2^k)
+        tensors, ops = random_net(rnd, batch_choices=(8, 16, 24), max_layers=2)
+        if 3 ** len(og.variables(tensors)) > 3e4:
+            continue
+        done += 1
+        T, O = to_lib(tensors, ops)
+        plan = tt.tt_plan_graph(T, O, k, tt.TT_PLAN_RECURSIVE)
+        t = {v: plan.tiling(v) for v in og.variables(tensors)}
+        forms = [plan.forms(q) for q in range(len(ops))]
+        deltas = [plan.delta(j) for j in range(k)]
+        assert og.greedy_is_valid(tensors, ops, k, t, forms, deltas)
+        assert plan.cost == sum(d << j for j, d in enumerate(deltas))           # Theorem 1
+        assert og.graph_cost(tensors, ops, k, t) <= plan.cost                     # free form sequences can only be cheaper
+        if (3 ** k) ** len(og.variables(tensors)) <= 3e5:
+            assert plan.cost >= og.bruteforce(tensors, ops, k)[0]
+        if k == 1:
+            assert plan.cost == tt.tt_plan_graph(T, O, 1, tt.TT_PLAN_EXACT).cost
+
+
+def test_layer_chain_as_a_graph_matches_the_chain_planner():
+    # the VGG-16 classifier at batch 256, three cuts: the graph search walks 27^5 joint states per level and must land on
+    # the chain planner's optimum (different code, same model); Algorithm 1 likewise
+    batch, widths, k = 256, [25088, 4096, 4096, 1000], 3
+    layers = [tt.layer("fc", n_in=widths[i], n_out=widths[i + 1]) for i in range(3)]
+    tensors, ops, idx = og.mlp_graph(batch, widths)
+    T, O = to_lib(tensors, ops)
+    chain = tt.tt_plan_chain(layers, batch, k, tt.TT_PLAN_EXACT)
+    graph = tt.tt_plan_graph(T, O, k, tt.TT_PLAN_EXACT)
+    assert graph.cost == chain.cost
+    # Algorithm 1: the first cut's optimum is unique; later cuts depend on which of several equally cheap first cuts
+    # was taken, so the two searches may part ways there (each is checked against the oracle on small graphs)
+    chain_r = tt.tt_plan_chain(layers, batch, k, tt.TT_PLAN_RECURSIVE)
+    graph_r = tt.tt_plan_graph(T, O, k, tt.TT_PLAN_RECURSIVE)
+    assert graph_r.delta(0) == chain_r.delta(0)
+    assert graph_r.cost == sum(graph_r.delta(j) << j for j in range(k)) >= graph.cost
+    # levels: operators that share a tensor sit in the same or in adjacent levels
+    graph = tt.tt_plan_graph(T, O, 1)
+    for a in range(len(ops)):
+        for b in range(a):
+            sa = {og.root(tensors, i) for i in ops[a]["ins"] + [ops[a]["out"]]}
+            sb = {og.root(tensors, i) for i in ops[b]["ins"] + [ops[b]["out"]]}
+            if sa & sb:
+                assert abs(graph.level_of(a) - graph.level_of(b)) <= 1
+    assert graph.n_levels == 1 + max(graph.level_of(q) for q in range(len(ops)))
+
+
+def test_disconnected_graph_and_errors():
+    # two independent products: levels continue over the components, costs add
+    T = [tt.graph_tensor((8, 6)), tt.graph_tensor((6, 4)), tt.graph_tensor((8, 4)),
+         tt.graph_tensor((10, 2)), tt.graph_tensor((2, 6)), tt.graph_tensor((10, 6))]
+    mm = dict(m=(0, 0), n=(1, 1), kk=(1, 0))
+    O = [tt.graph_op(tt.TT_GOP_CONTRACT, [0, 1], 2, **mm), tt.graph_op(tt.TT_GOP_CONTRACT, [3, 4], 5, **mm)]
+    p = tt.tt_plan_graph(T, O, 2)
+    assert p.cost == 0 and p.n_levels == 2
+    pins = {2: ("r", "r"), 5: ("r", "r")}
+    p = tt.tt_plan_graph(T, O, 2, pins=pins)
+    a = tt.tt_plan_graph(T[:3], O[:1], 2, pins={2: ("r", "r")}).cost
+    Tb = [tt.graph_tensor((10, 2)), tt.graph_tensor((2, 6)), tt.graph_tensor((10, 6))]
+    b = tt.tt_plan_graph(Tb, [tt.graph_op(tt.TT_GOP_CONTRACT, [0, 1], 2, **mm)], 2, pins={2: ("r", "r")}).cost
+    assert p.cost == a + b and a > 0 and b > 0
+
+    def status(fn):
+        with pytest.raises(tt.TilingError) as e:
+            fn()
+        return e.value.status
+
+    assert status(lambda: tt.tt_plan_graph(T, [tt.graph_op(tt.TT_GOP_CONTRACT, [0, 4], 2, **mm)], 1)) == 1   # extents differ
+    assert status(lambda: tt.tt_plan_graph(T, [tt.graph_op(tt.TT_GOP_ELEMENTWISE, [0, 1], 2)], 1)) == 1       # shapes differ
+    assert status(lambda: tt.tt_plan_graph(T, [tt.graph_op(7, [0], 2)], 1)) == 1
+    assert status(lambda: tt.tt_plan_graph([tt.graph_tensor((8, 6), same_as=0)], O[:1], 1)) == 1               # same_as itself
+    assert status(lambda: tt.tt_plan_graph(T, O, 1, pins={0: (5,)})) == 1                                      # no such dimension
+    assert status(lambda: tt.tt_graph_eval(T, O, 1, {0: (0,)})) == 1                                           # tilings missing
+    odd = [tt.graph_tensor((3, 5)), tt.graph_tensor((3, 5))]
+    assert status(lambda: tt.tt_plan_graph(odd, [tt.graph_op(tt.TT_GOP_BATCH, [0], 1)], 1)) == 2               # nothing even to cut
+    wide = [tt.graph_tensor((64, 64)) for _ in range(5)]
+    assert status(lambda: tt.tt_plan_graph(wide, [tt.graph_op(tt.TT_GOP_ELEMENTWISE, [0, 1, 2, 3], 4)], 6)) == 3  # 729^5 states
