@@ -419,7 +419,8 @@ template <int EV, bool OUT_BF16, int U> static tt_status launch_reduce_u(const R
 template <int EV, bool OUT_BF16> static tt_status launch_reduce_e(const ReduceParams &p, uint32_t blocks, int unroll, hipStream_t s)
 {
     // with 8 partials per round in flight one vector per lane already keeps the memory system busy
-    if (unroll == 4 && p.nred * p.ksplit < 4) return launch_reduce_u<EV, OUT_BF16, 4>(p, blocks, s);
+    if (unroll == 4) return launch_reduce_u<EV, OUT_BF16, 4>(p, blocks, s);
+    if (unroll == 2) return launch_reduce_u<EV, OUT_BF16, 2>(p, blocks, s);
     return launch_reduce_u<EV, OUT_BF16, 1>(p, blocks, s);
 }
 
@@ -467,7 +468,17 @@ tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, cons
     uint64_t piece_vecs = (uint64_t)piece_rows * (uint64_t)piece_cv;
     if (piece_vecs >= (uint64_t(1) << 31)) return TT_EUNSUPPORTED;
     const uint64_t unique_vecs = (uint64_t)rows * (uint64_t)(cols / ev);
-    const int unroll = (unique_vecs >= (uint64_t)kThreads * 4 * 256 * 4 && ((1u << Z.kX) * (uint32_t)ksplit) < 4) ? 4 : 1;
+    // Vectors per lane, measured on MI355X (256 x 1000 .. 512 x 8192 outputs, 2 .. 16 partial sums): one below 128 K
+    // vectors (more workgroups matter more than loads in flight), two up to a million; above that two for one or two
+    // partial sums, four for four (16 loads in flight per lane), one for eight or more (already eight in flight).
+    const uint32_t n_part = (1u << Z.kX) * (uint32_t)ksplit;
+    int unroll = 1;
+    if (unique_vecs >= (uint64_t)1 << 20) unroll = n_part >= 8 ? 1 : (n_part == 4 ? 4 : 2);
+    else if (unique_vecs >= (uint64_t)1 << 17) unroll = 2;
+    if (const char *e = std::getenv("TT_RED_U")) { // tuning aid: 1, 2, 4
+        const int u = std::atoi(e);
+        if (u == 1 || u == 2 || u == 4) unroll = u;
+    }
     p.piece_rows = (uint32_t)piece_rows;
     p.piece_cv = (uint32_t)piece_cv;
     p.pieces_c = (uint32_t)(B.scols / piece_cols);
