@@ -308,7 +308,9 @@ template <typename V, int GATE> tt_status launch_convert_v(const ConvertParams &
     if (p.unroll == 16) hipLaunchKernelGGL((convert_kernel<V, GATE, 16>), dim3(blocks), dim3(kThreads), 0, s, p);
     else if (p.unroll == 8) hipLaunchKernelGGL((convert_kernel<V, GATE, 8>), dim3(blocks), dim3(kThreads), 0, s, p);
     else if (p.unroll == 4) hipLaunchKernelGGL((convert_kernel<V, GATE, 4>), dim3(blocks), dim3(kThreads), 0, s, p);
-    else hipLaunchKernelGGL((convert_kernel<V, GATE, 1>), dim3(blocks), dim3(kThreads), 0, s, p);
+    else if (p.unroll == 2) hipLaunchKernelGGL((convert_kernel<V, GATE, 2>), dim3(blocks), dim3(kThreads), 0, s, p);
+    else if (p.unroll == 1) hipLaunchKernelGGL((convert_kernel<V, GATE, 1>), dim3(blocks), dim3(kThreads), 0, s, p);
+    else return TT_EINVAL; // the grid was sized for p.unroll vectors per lane: no other kernel may run on it
     return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
 }
 
@@ -329,8 +331,10 @@ template <int GATE> tt_status launch_convert_g(int vbytes, const ConvertParams &
 // is small.
 static int pick_unroll(uint64_t total_vecs)
 {
-    // measured on the 205 MB weight: 4 vectors per lane 5.78 TB/s, 8: 5.68, 16: 5.33
-    if (total_vecs >= (uint64_t)kThreads * 4 * 256 * 4) return 4;
+    // measured on the 205 MB weight: 4 vectors per lane 5.78 TB/s, 8: 5.68, 16: 5.33; on 8 MB activations (512 K
+    // vectors) 4 per lane is 30 % faster than 1, on 2 MB ones (128 K vectors) 2 per lane equal to 1 and 4 slower
+    if (total_vecs >= (uint64_t)1 << 19) return 4;
+    if (total_vecs >= (uint64_t)1 << 17) return 2;
     return 1;
 }
 
@@ -380,7 +384,10 @@ tt_status launch_convert(void *const *dst, const uint8_t *Bl, const void *const 
     const int64_t piece_cv = piece_cols / vec_elems;
     const uint64_t unique_vecs = (uint64_t)rows * (uint64_t)(cols / vec_elems);
     p.unroll = (uint32_t)pick_unroll(unique_vecs);
-    if (const char *e = std::getenv("TT_CVT_U")) p.unroll = (uint32_t)std::atoi(e); // tuning aid: 1, 4, 8, 16
+    if (const char *e = std::getenv("TT_CVT_U")) { // tuning aid: 1, 2, 4, 8, 16
+        const int u = std::atoi(e);
+        if (u == 1 || u == 2 || u == 4 || u == 8 || u == 16) p.unroll = (uint32_t)u;
+    }
     p.piece_rows = (uint32_t)piece_rows;
     p.piece_cv = (uint32_t)piece_cv;
     p.pieces_c = (uint32_t)(B.scols / piece_cols);

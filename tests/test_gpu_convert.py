@@ -95,6 +95,28 @@ def test_retile_full_size_weight():
         del src, dst
 
 
+@pytest.mark.parametrize("rows,cols", [(512, 4096), (1024, 8192), (520, 1032)])
+def test_retile_and_gate_medium_tensors(rows, cols):
+    # activation-sized tensors (2 and 8 M elements and a ragged one): the launches with two and four vectors per lane
+    # and a tail of partly filled workgroups
+    rng = np.random.default_rng(rows)
+    T = rng.integers(0, 1 << 16, size=(rows, cols), dtype=np.uint16)
+    for A, B in [("RC", "CR"), ("RRC", "Crr"), ("rC", "RR")]:
+        run_retile(T, A, B, 2)
+    v = rng.standard_normal((rows, cols)).astype(np.float32)
+    m = rng.standard_normal((rows, cols)).astype(np.float32)
+    V, Mk = to_bf16_bits(v), to_bf16_bits(m)
+    want_full = np.where(bf16_bits_to_f32(Mk) > 0, V, np.zeros_like(V))
+    for A, Am, B in [("RC", "CR", "RR"), ("Cr", "RC", "CC")]:
+        src = shards_to_dev(V, A, True)
+        msk = shards_to_dev(Mk, Am, True)
+        dst = alloc_shards(rows, cols, B, torch.bfloat16)
+        tt.tt_retile_gate(dst, B, src, A, msk, Am, rows, cols, "bf16")
+        torch.cuda.synchronize()
+        got = tl.untile(shards_to_np(dst), B, rows, cols)
+        assert np.array_equal(got.view(np.uint16), want_full.view(np.uint16)), (A, Am, B)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_gated_retile(dtype):
     rng = np.random.default_rng(12)
