@@ -26,9 +26,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # WRITE_SIZE runs summarised in profiles/vgg16_fc_step_hbm_traffic_pmc.txt (counters scaled by what the same counters
 # read for the W_1 retile, a copy of known size).  Keyed by workload, kernel and per-shard M x N x K; None if not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "vgg16_fc:gemm_tn:3136x4096x256": int((30.22 + 205.63) * 1e6),
-    "vgg16_fc:gemm_nn:256x4096x3136": int((218.67 + 67.14) * 1e6),
-    "vgg16_fc:gemm_nt:256x3136x4096": int((222.42 + 51.45) * 1e6),
+    "vgg16_fc:gemm_tn:3136x4096x256": int((30.10 + 205.61) * 1e6),
+    "vgg16_fc:gemm_nn:256x4096x3136": int((218.66 + 67.11) * 1e6),
+    "vgg16_fc:gemm_nt:256x3136x4096": int((222.41 + 51.44) * 1e6),
 }
 
 
