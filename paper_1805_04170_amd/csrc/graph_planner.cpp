@@ -469,7 +469,7 @@ tt_status plan_exact(const Graph &g, int k, const std::vector<const uint8_t *> &
             uint64_t aa[kMaxOperands][TT_MAX_K];
             for (int i = 0; i <= o.n_in; ++i) {
                 tt[i] = cand.seq[o.var[i]].data() + (size_t)val[o.var[i]] * k;
-                std::memcpy(aa[i], cand.area[o.var[i]].data() + (size_t)val[o.var[i]] * k, sizeof(uint64_t) * (size_t)k);
+                if (k > 0) std::memcpy(aa[i], cand.area[o.var[i]].data() + (size_t)val[o.var[i]] * k, sizeof(uint64_t) * (size_t)k);
             }
             f.tab[s] = op_cost(o, k, tt, aa, nullptr, nullptr);
         }
@@ -736,14 +736,14 @@ extern "C" int tt_graph_plan_level_of(const tt_graph_plan *p, int op) { return (
 extern "C" tt_status tt_graph_plan_tiling(const tt_graph_plan *p, int tensor, uint8_t *letters_out)
 {
     if (!p || !letters_out || tensor < 0 || tensor >= p->n_tensors) return TT_EINVAL;
-    std::memcpy(letters_out, p->letters.data() + (size_t)tensor * p->k, (size_t)p->k);
+    if (p->k > 0) std::memcpy(letters_out, p->letters.data() + (size_t)tensor * p->k, (size_t)p->k);
     return TT_OK;
 }
 
 extern "C" tt_status tt_graph_plan_forms(const tt_graph_plan *p, int op, uint8_t *forms_out)
 {
     if (!p || !forms_out || op < 0 || op >= p->n_ops) return TT_EINVAL;
-    std::memcpy(forms_out, p->forms.data() + (size_t)op * p->k, (size_t)p->k);
+    if (p->k > 0) std::memcpy(forms_out, p->forms.data() + (size_t)op * p->k, (size_t)p->k);
     return TT_OK;
 }
 
