@@ -168,6 +168,10 @@ tt_status tt_reduce(void *const *dst, tt_tiling B, int out_dtype, const float *c
  *                         convolution X[N,C,H,W] * W[K,C,R,S] -> Y[N,K,P,Q]: m {0,0} n {0,1} kk {1,1}.
  *     TT_GOP_ELEMENTWISE  1..4 inputs and the output of one shape; form d: every operand cut along dimension d.
  *     TT_GOP_BATCH        any other operator: every operand cut along dimension 0 (equal extents there).
+ *     TT_GOP_SAMPLE_CHANNEL  operators that treat every (sample, channel) pair by itself: pooling, the flattening of
+ *                         channel-major images [N,C,H,W] -> [N, C*H*W].  Operands need at least two dimensions, equal
+ *                         extents in dimension 0, extents in dimension 1 that are multiples of the smallest one (the
+ *                         channel count).  Form 0: all cut along dimension 0;  form 1: all cut along dimension 1.
  * pins: NULL, or n_tensors * k letters; a tensor whose first letter is TT_LETTER_FREE is left to the search.
  * mode TT_PLAN_EXACT: minimum over every joint assignment of k-cut sequences, found by minimising the tensors out
  * one at a time (TT_EUNSUPPORTED when every order would need a cost table of more than 2^24 entries);
@@ -176,7 +180,7 @@ tt_status tt_reduce(void *const *dst, tt_tiling B, int out_dtype, const float *c
  * Errors: TT_EINVAL (malformed graph or letters), TT_EINFEASIBLE (no tiling with even cuts), TT_ENOMEM. */
 enum { TT_GRAPH_MAX_DIMS = 4, TT_GRAPH_MAX_INPUTS = 4, TT_GRAPH_MAX_TENSORS = 4096, TT_GRAPH_MAX_OPS = 4096 };
 enum { TT_LETTER_REP = 255, TT_LETTER_FREE = 253 };
-enum { TT_GOP_CONTRACT = 0, TT_GOP_ELEMENTWISE = 1, TT_GOP_BATCH = 2 };
+enum { TT_GOP_CONTRACT = 0, TT_GOP_ELEMENTWISE = 1, TT_GOP_BATCH = 2, TT_GOP_SAMPLE_CHANNEL = 3 };
 typedef struct { int32_t ndim; int32_t same_as; int64_t shape[4]; } tt_graph_tensor;
 typedef struct { int32_t kind, n_in; int32_t in[4]; int32_t out; int32_t m[2], n[2], kk[2]; } tt_graph_op;
 typedef struct tt_graph_plan tt_graph_plan; /* opaque; host memory owned by the library until tt_graph_plan_free */

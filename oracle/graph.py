@@ -22,6 +22,10 @@ Vocabulary
            {"kind": "elementwise", "ins": [...], "out": z}   same shape everywhere; aligned: every operand cut along
                the same dimension (all replicated is redundant computation and not allowed)
            {"kind": "batch", "ins": [...], "out": z}         any other operator: every operand cut along dimension 0
+           {"kind": "sample_channel", "ins": [...], "out": z}  works on every (sample, channel) pair by itself - pooling,
+               the flattening of channel-major images in front of a fully-connected layer: operands may differ in shape
+               beyond dimensions 0 and 1; aligned: all cut along dimension 0, or all along dimension 1 (a cut of the
+               flattened columns is a channel cut as long as the channel count, the smallest extent 1, is even)
 
 Readings (the same as for the layer chain): conversion cost of a tile with A elements over two devices, summed over
 both: same letter 0; between two different cuts A/2; cut -> replicated A; replicated -> anything 0; partial sums ->
@@ -87,6 +91,11 @@ def forms_of(op, tensors):
     if op["kind"] == "elementwise":
         assert all(tensors[i]["shape"] == shape for i in ins)
         return [(tuple(d for _ in ins), d, shape[d]) for d in range(len(shape))]
+    if op["kind"] == "sample_channel":
+        shapes = [tensors[i]["shape"] for i in ins] + [shape]
+        chans = min(sh[1] for sh in shapes)
+        assert all(sh[0] == shape[0] and sh[1] % chans == 0 for sh in shapes)
+        return [(tuple(0 for _ in ins), 0, shape[0]), (tuple(1 for _ in ins), 1, chans)]
     assert op["kind"] == "batch"
     assert all(tensors[i]["shape"][0] == shape[0] for i in ins)
     return [(tuple(0 for _ in ins), 0, shape[0])]

@@ -31,7 +31,7 @@ EXPORTS = [
     "tt_graph_plan_level_of", "tt_graph_plan_tiling", "tt_graph_plan_forms", "tt_graph_plan_free",
 ]
 TT_LETTER_REP, TT_LETTER_FREE = 255, 253
-TT_GOP_CONTRACT, TT_GOP_ELEMENTWISE, TT_GOP_BATCH = 0, 1, 2
+TT_GOP_CONTRACT, TT_GOP_ELEMENTWISE, TT_GOP_BATCH, TT_GOP_SAMPLE_CHANNEL = 0, 1, 2, 3
 KERNEL_NAMES = ["convert", "gate", "reduce", "gemm_nn", "gemm_nt", "gemm_tn", "gemm_tt", "gemm_generic", "conv_fwd",
                 "conv_dgrad", "conv_wgrad"]
 

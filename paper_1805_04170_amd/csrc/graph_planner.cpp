@@ -14,6 +14,8 @@
 //       form 2: x and y cut along k, z = partial sums
 //   element-wise (same shape everywhere): one form per dimension, every operand cut along it
 //   batch-only (any other operator): every operand cut along dimension 0
+//   per sample and channel (pooling; flattening channel-major images): every operand cut along dimension 0, or every
+//       operand along dimension 1 - a column cut of the flattened matrix is a channel cut while the channel count is even
 #include <algorithm>
 #include <cstring>
 #include <limits>
@@ -142,6 +144,23 @@ tt_status build_graph(const tt_graph_tensor *tensors, int n_tensors, const tt_gr
                 o.form[d].out = (uint8_t)d;
                 o.extent[d] = z.shape[d];
             }
+        } else if (s.kind == TT_GOP_SAMPLE_CHANNEL) {
+            int64_t chans = z.ndim >= 2 ? z.shape[1] : 0;
+            for (int i = 0; i < s.n_in; ++i) {
+                const tt_graph_tensor &x = tensors[s.in[i]];
+                if (x.ndim < 2 || z.ndim < 2 || x.shape[0] != z.shape[0]) return TT_EINVAL;
+                chans = std::min(chans, x.shape[1]);
+            }
+            if (chans <= 0 || z.shape[1] % chans) return TT_EINVAL;
+            for (int i = 0; i < s.n_in; ++i)
+                if (tensors[s.in[i]].shape[1] % chans) return TT_EINVAL;
+            o.n_forms = 2;
+            for (int d = 0; d < 2; ++d) {
+                for (int i = 0; i < s.n_in; ++i) o.form[d].in[i] = (uint8_t)d;
+                o.form[d].out = (uint8_t)d;
+            }
+            o.extent[0] = z.shape[0];
+            o.extent[1] = chans;
         } else if (s.kind == TT_GOP_BATCH) {
             for (int i = 0; i < s.n_in; ++i)
                 if (tensors[s.in[i]].shape[0] != z.shape[0]) return TT_EINVAL;

@@ -7,7 +7,8 @@ import paper_1805_04170_amd as tt
 from oracle import graph as og
 from oracle import cost as oc
 
-KIND = {"contract": tt.TT_GOP_CONTRACT, "elementwise": tt.TT_GOP_ELEMENTWISE, "batch": tt.TT_GOP_BATCH}
+KIND = {"contract": tt.TT_GOP_CONTRACT, "elementwise": tt.TT_GOP_ELEMENTWISE, "batch": tt.TT_GOP_BATCH,
+        "sample_channel": tt.TT_GOP_SAMPLE_CHANNEL}
 
 
 def to_lib(tensors, ops):
@@ -149,6 +150,68 @@ def test_four_dimensional_tensors_and_convolutions():
     dp = {v: (("r",) if v in (1, 4) else (0,)) for v in og.variables(tensors)}
     assert og.graph_cost(tensors, ops, 1, dp) == 2 * (c1 * c0 * R * R + c2 * c1 * R * R)
     assert plan.cost <= og.graph_cost(tensors, ops, 1, dp)
+
+
+def small_convnet(N=8, c0=2, c1=4, H=4, R=3, n_out=6):
+    """conv -> pool -> flatten -> fully connected, with the backward pass: the shape of the paper's networks
+    (convolutions in front, fully-connected layers behind) at toy size.  Graph description only."""
+    T = lambda shape, same=None: {"shape": tuple(shape), "same_as": same}
+    P = H // 2
+    names = ["x0", "w1", "y1", "p1", "f1", "w2", "y2", "gy2", "dw2", "gf1", "gp1", "gy1", "dw1"]
+    ix = {s: i for i, s in enumerate(names)}
+    tensors = [T((N, c0, H, H)), T((c1, c0, R, R)), T((N, c1, H, H)), T((N, c1, P, P)), T((N, c1 * P * P)),
+               T((c1 * P * P, n_out)), T((N, n_out)), T((N, n_out)), T((c1 * P * P, n_out), ix["w2"]),
+               T((N, c1 * P * P)), T((N, c1, P, P)), T((N, c1, H, H)), T((c1, c0, R, R), ix["w1"])]
+    sc = lambda a, b: {"kind": "sample_channel", "ins": [a], "out": b}
+    ops = [{"kind": "contract", "ins": [ix["x0"], ix["w1"]], "out": ix["y1"], "m": (0, 0), "n": (0, 1), "k": (1, 1)},
+           sc(ix["y1"], ix["p1"]), sc(ix["p1"], ix["f1"]),
+           og.matmul(ix["f1"], ix["w2"], ix["y2"]),
+           og.matmul(ix["f1"], ix["gy2"], ix["dw2"], ta=True), og.matmul(ix["gy2"], ix["w2"], ix["gf1"], tb=True),
+           sc(ix["gf1"], ix["gp1"]), {"kind": "sample_channel", "ins": [ix["gp1"], ix["y1"]], "out": ix["gy1"]},
+           {"kind": "contract", "ins": [ix["x0"], ix["gy1"]], "out": ix["dw1"], "m": (1, 1), "n": (1, 0), "k": (0, 0)}]
+    return tensors, ops, ix
+
+
+def test_pooling_and_flatten_between_convolution_and_fully_connected():
+    tensors, ops, ix = small_convnet()
+    T, O = to_lib(tensors, ops)
+    rnd = random.Random(3)
+    for k in (1, 2):
+        hits = 0
+        for trial in range(60):
+            t = random_tilings(rnd, tensors, k)
+            want = og.graph_cost(tensors, ops, k, t)
+            if want == og.INF:
+                continue
+            hits += 1
+            assert tt.tt_graph_eval(T, O, k, full_tilings(tensors, t))[0] == want
+        assert hits > 10
+    # data parallelism end to end costs the two gradient all-reduces and nothing at the pooling or the flatten
+    dp = {v: (("r",) if v in (ix["w1"], ix["w2"]) else (0,)) for v in og.variables(tensors)}
+    w1 = 4 * 2 * 3 * 3
+    w2 = 4 * 2 * 2 * 6
+    assert og.graph_cost(tensors, ops, 1, dp) == 2 * (w1 + w2)
+    # the flattened activations cut by columns and the pooled ones by channels are the same cut: no traffic between them
+    mp = dict(dp)
+    for name in ("y1", "p1", "f1", "gf1", "gp1", "gy1"):
+        mp[ix[name]] = (1,)
+    assert og.op_cost(ops[2], tensors, mp, 1) == 0 and og.op_cost(ops[6], tensors, mp, 1) == 0
+    # exhaustive search over the 11 tensors is too much for plain Python at one cut (3 or 5 letters each): pin the 4-D
+    # activations to their batch / channel cuts in turn and search the rest
+    for pins in ({ix["x0"]: (0,), ix["y1"]: (0,), ix["gy1"]: (0,), ix["p1"]: (0,), ix["gp1"]: (0,)},
+                 {ix["x0"]: ("r",), ix["y1"]: (1,), ix["gy1"]: (1,), ix["p1"]: (1,), ix["gp1"]: (1,)}):
+        want, arg = og.bruteforce(tensors, ops, 1, pins)
+        plan = tt.tt_plan_graph(T, O, 1, tt.TT_PLAN_EXACT, pins=pins)
+        assert plan.cost == want
+        assert og.graph_cost(tensors, ops, 1, {v: plan.tiling(v) for v in og.variables(tensors)}) == want
+    free = tt.tt_plan_graph(T, O, 1, tt.TT_PLAN_EXACT)
+    assert free.cost <= want
+    assert tt.tt_plan_graph(T, O, 1, tt.TT_PLAN_RECURSIVE).cost == free.cost
+    # malformed: channel counts that do not divide
+    bad = [tt.graph_tensor((8, 4, 2, 2)), tt.graph_tensor((8, 6))]
+    with pytest.raises(tt.TilingError) as e:
+        tt.tt_plan_graph(bad, [tt.graph_op(tt.TT_GOP_SAMPLE_CHANNEL, [0], 1)], 1)
+    assert e.value.status == 1
 
 
 @pytest.mark.parametrize("k,max_layers", [(1, 2), (2, 1)])

@@ -53,6 +53,26 @@ def test_batch_only_operator_forces_the_batch_cut():
     assert og.graph_cost(small, [{"kind": "batch", "ins": [0], "out": 1}], 2, {0: ("r", "r"), 1: ("r", "r")}) == og.INF
 
 
+def test_sample_channel_operator_is_ghost_minus_held():
+    # a per-(sample, channel) operator with a narrower output (4 x 6 -> 4 x 2: three columns per channel pooled into
+    # one): device d needs the input block of its aligned cut and hands over what the stored output tiling asks for
+    tensors = [{"shape": (4, 6), "same_as": None}, {"shape": (4, 2), "same_as": None}]
+    ops = [{"kind": "sample_channel", "ins": [0], "out": 1}]
+    for li, lo in itertools.product([0, 1, "r"], repeat=2):
+        best = None
+        for dim in (0, 1):
+            cnt = 0
+            for d in range(2):
+                cnt += len(held(4, 6, dim, d) - held(4, 6, li, d))
+                cnt += len(held(4, 2, lo, d) - held(4, 2, dim, d))
+            best = cnt if best is None else min(best, cnt)
+        assert og.graph_cost(tensors, ops, 1, {0: (li,), 1: (lo,)}) == best
+    # one channel left: only the sample cut remains
+    one = [{"shape": (4, 3), "same_as": None}, {"shape": (4, 1), "same_as": None}]
+    assert og.graph_cost(one, ops, 1, {0: (0,), 1: (0,)}) == 0
+    assert [f[2] for f in og.forms_of(ops[0], one)] == [4, 1]
+
+
 def chain_tilings(idx, x, g, w):
     t = {}
     for l, s in enumerate(x):
