@@ -274,6 +274,47 @@ def test_recursive_search_is_a_valid_run_of_algorithm_1(k):
             assert plan.cost == tt.tt_plan_graph(T, O, 1, tt.TT_PLAN_EXACT).cost
 
 
+def permuted(rnd, tensors, ops):
+    """the same graph with operators shuffled and tensors renumbered (a tensor still follows the one it is stored like)"""
+    n = len(tensors)
+    order = list(range(n))
+    rnd.shuffle(order)
+    order.sort(key=lambda i: 0 if tensors[i].get("same_as") is None else 1)   # roots first, so same_as points backwards
+    new_of = {old: new for new, old in enumerate(order)}
+    T = []
+    for old in order:
+        t = tensors[old]
+        T.append({"shape": t["shape"], "same_as": None if t.get("same_as") is None else new_of[og.root(tensors, old)]})
+    O = []
+    for op in ops:
+        o = dict(op)
+        o["ins"] = [new_of[i] for i in op["ins"]]
+        o["out"] = new_of[op["out"]]
+        O.append(o)
+    rnd.shuffle(O)
+    return T, O
+
+
+@pytest.mark.parametrize("k", [1, 2, 3])
+def test_search_does_not_depend_on_the_numbering(k):
+    # the order in which tensors are minimised out, and the root of the breadth-first levels, follow the numbering;
+    # the optimum must not
+    rnd = random.Random(900 + k)
+    for trial in range(12):
+        tensors, ops = random_net(rnd, batch_choices=(8, 16, 24))
+        T, O = to_lib(tensors, ops)
+        exact = tt.tt_plan_graph(T, O, k, tt.TT_PLAN_EXACT).cost
+        first_cut = tt.tt_plan_graph(T, O, k, tt.TT_PLAN_RECURSIVE).delta(0) if k else 0
+        for _ in range(3):
+            tp, op = permuted(rnd, tensors, ops)
+            Tp, Op = to_lib(tp, op)
+            assert tt.tt_plan_graph(Tp, Op, k, tt.TT_PLAN_EXACT).cost == exact
+            assert tt.tt_plan_graph(Tp, Op, k, tt.TT_PLAN_RECURSIVE).delta(0) == first_cut
+        # more cuts never cost less: every k-cut plan contains a (k-1)-cut plan (drop the last cut) that is no dearer
+        if k > 1:
+            assert exact >= tt.tt_plan_graph(T, O, k - 1, tt.TT_PLAN_EXACT).cost
+
+
 def test_layer_chain_as_a_graph_matches_the_chain_planner():
     # the VGG-16 classifier at batch 256, three cuts: the graph search walks 27^5 joint states per level and must land on
     # the chain planner's optimum (different code, same model); Algorithm 1 likewise
