@@ -331,6 +331,12 @@ def test_layer_chain_as_a_graph_matches_the_chain_planner():
     graph_r = tt.tt_plan_graph(T, O, k, tt.TT_PLAN_RECURSIVE)
     assert graph_r.delta(0) == chain_r.delta(0)
     assert graph_r.cost == sum(graph_r.delta(j) << j for j in range(k)) >= graph.cost
+    # the small chain on which Algorithm 1 is not optimal (batch 48, 24 -> 32 -> 112, two cuts): same two figures as the
+    # chain planner and the chain oracle
+    small, small_ops, _ = og.mlp_graph(48, [24, 32, 112])
+    Ts, Os = to_lib(small, small_ops)
+    assert tt.tt_plan_graph(Ts, Os, 2, tt.TT_PLAN_EXACT).cost == 8704
+    assert tt.tt_plan_graph(Ts, Os, 2, tt.TT_PLAN_RECURSIVE).cost == 9984
     # levels: operators that share a tensor sit in the same or in adjacent levels
     graph = tt.tt_plan_graph(T, O, 1)
     for a in range(len(ops)):
