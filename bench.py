@@ -238,6 +238,17 @@ def cpu_baseline(cfg):
             "sample": "1 full untiled fwd+bwd step of %s in fp64 numpy (%.1f GFLOP, %.2f s)" % (cfg.name, cfg.flops() / 1e9, dt)}
 
 
+def counted_cross_shard_elems(tt, cfg, chain, is_conv):
+    """What the step's conversions and reductions really move between shards (flat count, block by block), next to the
+    planner's cost, which is the paper's recursive model of the same traffic; the two are equal at one cut only."""
+    if is_conv or any(f is None for layer_forms in chain.forms for f in layer_forms):
+        return None
+    try:
+        return tt.fc_step_cross_elems(list(cfg.widths), cfg.batch, cfg.k, chain.tx, chain.tg, chain.tw, chain.forms)
+    except Exception:  # a report line must not take the measurement down
+        return None
+
+
 def shape_study(args, tt, torch):
     """Sec. 6.3 / Table 1 of the paper asked again on one MI355X: a 4-layer MLP with 8K x 8K weights, one step untiled
     (k = 0) against the same step cut into 8 shards under the planner's tiling, all shards on this GPU.  Same flops."""
@@ -419,6 +430,7 @@ def main():
             "%s: N=%d C=%d K=%d %dx%d %dx%d pad %d, k=%d (%d shards), %s split" % (
                 cfg.name, cfg.N, cfg.C, cfg.K, cfg.H, cfg.W, cfg.R, cfg.S, cfg.pad, cfg.k, 1 << cfg.k, args.conv_split)),
             "tiling_x": chain.tx, "tiling_g": chain.tg, "tiling_w": chain.tw, "plan_cost_elems": chain.plan_cost,
+            "counted_cross_shard_elems": counted_cross_shard_elems(tt, cfg, chain, is_conv),
             "timed": "hip graph replay" if graph is not None else "eager launches",
             "streams": 2 if (not is_conv and args.overlap) else 1},
         "frac_mfma_peak": tflops / PEAK_BF16_TFLOPS,

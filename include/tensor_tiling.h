@@ -152,6 +152,23 @@ tt_status tt_retile_gate(void *const *dst, tt_tiling B, const void *const *src, 
 tt_status tt_reduce(void *const *dst, tt_tiling B, int out_dtype, const float *const *partials,
                     const uint8_t *forms, int k, int64_t rows, int64_t cols, int act, void *stream);
 
+/* ---------------------------------------------- what an execution really moves
+ * Elements that cross from one shard to another (Sec. 4.2.1: a device fetches the part of its tile under the new tiling
+ * that it does not hold under the old one; with the third aligned form it fetches the other devices' partial sums of the
+ * elements it is to store).  Counted block by block over the 2^k shards; host arithmetic, no device work.
+ * For k = 1 the count of a product equals its cost under tt_plan_eval; for k > 1 the planner's cost is the paper's
+ * recursive model and the two differ - callers report them side by side.
+ * tt_conversion_cross_elems: a stored tensor of rows x cols going from tiling `from` to tiling `to`.
+ * tt_product_cross_elems: Z = X Y (M x K times K x N) under stored tilings tX, tY, tZ and a form sequence (k entries,
+ *   TT_F1..TT_F3): elems[0] input conversion of X, elems[1] of Y, elems[2] output conversion or partial-sum reduction.
+ *   mult_*: elements per matrix entry (1 for fully-connected layers; pixels per channel entry / filter taps for
+ *   convolutions, whose image and filter extents are never cut).
+ * Errors: TT_EINVAL, TT_EINFEASIBLE (uneven cut, or M, N, K not divisible as the forms ask). */
+tt_status tt_conversion_cross_elems(int64_t rows, int64_t cols, tt_tiling from, tt_tiling to, int k, uint64_t *elems);
+tt_status tt_product_cross_elems(int64_t M, int64_t K, int64_t N, tt_tiling tX, tt_tiling tY, tt_tiling tZ,
+                                 const uint8_t *forms, int k, uint64_t mult_x, uint64_t mult_y, uint64_t mult_z,
+                                 uint64_t *elems /* [3] */);
+
 /* ------------------------------------------------- planner, general graphs
  * The tiling search on any dataflow graph (Sec. 4.2.2: operators organised into breadth-first levels, Eqs. 4-5 over
  * the tensors shared by adjacent levels; Sec. 4.3: Algorithm 1; Sec. 4.5: tensors with up to four dimensions - one

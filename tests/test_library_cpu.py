@@ -10,6 +10,7 @@ import pytest
 
 import paper_1805_04170_amd as tt
 from oracle import cost as oc
+from oracle import execute as ex
 from oracle import tiling as tl
 from synthetic import CONFIGS
 
@@ -275,3 +276,88 @@ def test_workspace_query_runs_on_host():
     n = tt.tt_fc_workspace_bytes(lay, 16, 2, "bf16", tt.TT_OP_FWD, "CC", "RR", "RR", forms_a="33")
     assert n == 4 * 16 * 32 * 4                               # four fp32 partial blocks
     assert tt.tt_fc_workspace_bytes(lay, 16, 2, "bf16", tt.TT_OP_DGRAD, "CC", "RR", "RR", "rr", "CC") > 0
+
+
+# ---- counted cross-shard elements (what an execution moves) against explicit index sets
+
+def _sets(rows, cols, t, s):
+    rs, cs = tl.shard_slices(rows, cols, t, s)
+    return {(i, j) for i in range(rs.start, rs.stop) for j in range(cs.start, cs.stop)}
+
+
+def _moved_conversion(rows, cols, frm, to):
+    k = len(frm)
+    return sum(len(_sets(rows, cols, to, s) - _sets(rows, cols, frm, s)) for s in range(1 << k))
+
+
+def _moved_reduction(rows, cols, form_seq, to):
+    """every device fetches, for every element it is to store, the partial sums that other devices computed (two
+    devices never hold the same value of an output element: an R or C cut puts them on different blocks, a form-3 cut
+    gives them different partial sums)"""
+    k = len(form_seq)
+    grid = ex.output_grid_tiling(form_seq)           # where each device's partial sums lie
+    made = [_sets(rows, cols, grid, q) for q in range(1 << k)]
+    moved = 0
+    for s in range(1 << k):
+        for e in _sets(rows, cols, to, s):
+            moved += sum(1 for q in range(1 << k) if q != s and e in made[q])
+    return moved
+
+
+def test_counted_conversion_elements_are_ghost_minus_held():
+    rng = np.random.default_rng(21)
+    for k in (1, 2, 3):
+        ts = tl.all_tilings(k)
+        for _ in range(40):
+            a, b = ts[rng.integers(len(ts))], ts[rng.integers(len(ts))]
+            rows, cols = 8 * int(rng.integers(1, 3)), 8 * int(rng.integers(1, 4))
+            assert tt.tt_conversion_cross_elems(rows, cols, a, b) == _moved_conversion(rows, cols, a, b), (a, b)
+    assert tt.tt_conversion_cross_elems(8, 8, "", "", 0) == 0
+    with pytest.raises(tt.TilingError) as e:
+        tt.tt_conversion_cross_elems(6, 8, "RR", "CC")
+    assert e.value.status == 2
+
+
+def test_counted_product_elements_against_index_sets_and_the_one_cut_cost():
+    rng = np.random.default_rng(22)
+    M, K, N = 8, 16, 8
+    # one cut: the count is Eq. 2's term, for every stored tiling and every form
+    for tx, ty, tz in itertools.product("RCr", repeat=3):
+        for f in "123":
+            got = sum(tt.tt_product_cross_elems(M, K, N, tx, ty, tz, f))
+            assert got == oc.eq2_term(int(f) - 1, tx, ty, tz, M * K, K * N, M * N)
+    # several cuts: explicit sets
+    for k in (2, 3):
+        ts = tl.all_tilings(k)
+        for _ in range(25):
+            tx, ty, tz = (ts[rng.integers(len(ts))] for _ in range(3))
+            f = "".join(rng.choice(list("123")) for _ in range(k))
+            if not ex.forms_feasible(f, M, K, N):
+                continue
+            aX, aY = ex.aligned_tilings(f)
+            want_out = _moved_reduction(M, N, f, tz) if "3" in f else _moved_conversion(M, N, ex.output_grid_tiling(f), tz)
+            got = tt.tt_product_cross_elems(M, K, N, tx, ty, tz, f)
+            assert got == [_moved_conversion(M, K, tx, aX), _moved_conversion(K, N, ty, aY), want_out], (tx, ty, tz, f)
+    assert tt.tt_product_cross_elems(8, 8, 8, "R", "r", "R", "1", mult=(3, 5, 7)) == [0, 0, 0]
+    assert tt.tt_product_cross_elems(8, 8, 8, "C", "C", "r", "1", mult=(3, 5, 7)) == [3 * 32, 5 * 64, 7 * 64]
+
+
+def test_counted_elements_of_a_whole_step_equal_the_plan_cost_at_one_cut():
+    batch, widths = 16, [24, 16, 8]
+    layers = fc_layers(widths)
+    p = tt.tt_plan_chain(layers, batch, 1)
+    forms = [[p.forms(l, op) for op in range(3)] for l in range(1, 3)]
+    assert tt.fc_step_cross_elems(widths, batch, 1, p.x(), p.g(), p.w(), forms) == p.cost
+    # data parallelism at one cut: both weight gradients are all-reduced, nothing else moves
+    x = g = ["R"] * 3
+    w = ["r"] * 2
+    cost, _, f = tt.tt_plan_eval(layers, batch, 1, x, g, w)
+    assert tt.fc_step_cross_elems(widths, batch, 1, x, g, w, f) == cost == 2 * (24 * 16 + 16 * 8)
+    # more cuts: the recursive model and the flat count part ways (two row cuts of a large batch, weights replicated:
+    # the model charges 2|W| (2^k - 1), every one of the four devices really fetches three foreign partial sums of |W|)
+    k, big = 2, 256
+    x = g = ["RR"] * 3
+    w = ["rr"] * 2
+    cost, _, f = tt.tt_plan_eval(layers, big, k, x, g, w)
+    counted = tt.fc_step_cross_elems(widths, big, k, x, g, w, f)
+    assert cost == 2 * (24 * 16 + 16 * 8) * 3 and counted == 4 * 3 * (24 * 16 + 16 * 8)
