@@ -244,7 +244,7 @@ def counted_cross_shard_elems(tt, cfg, chain, is_conv):
     if is_conv or any(f is None for layer_forms in chain.forms for f in layer_forms):
         return None
     try:
-        return tt.fc_step_cross_elems(list(cfg.widths), cfg.batch, cfg.k, chain.tx, chain.tg, chain.tw, chain.forms)
+        return tt.tt_fc_chain_cross_elems(chain.layers, cfg.batch, cfg.k, chain.tx, chain.tg, chain.tw, chain.forms)
     except Exception:  # a report line must not take the measurement down
         return None
 

@@ -168,6 +168,11 @@ tt_status tt_conversion_cross_elems(int64_t rows, int64_t cols, tt_tiling from, 
 tt_status tt_product_cross_elems(int64_t M, int64_t K, int64_t N, tt_tiling tX, tt_tiling tY, tt_tiling tZ,
                                  const uint8_t *forms, int k, uint64_t mult_x, uint64_t mult_y, uint64_t mult_z,
                                  uint64_t *elems /* [3] */);
+/* one forward + backward pass over a chain of fully-connected layers (TT_EUNSUPPORTED for other kinds): the sum over its
+ * 3 L products.  Tilings as tt_plan_eval takes them (x, g: L + 1; w: L); forms: 3 * L * k entries laid out as
+ * tt_plan_eval's forms_out (layer, then forward / data gradient / weight gradient, then cut). */
+tt_status tt_fc_chain_cross_elems(const tt_layer *layers, int n_layers, int64_t batch, int k, const tt_tiling *x,
+                                  const tt_tiling *g, const tt_tiling *w, const uint8_t *forms, uint64_t *elems);
 
 /* ------------------------------------------------- planner, general graphs
  * The tiling search on any dataflow graph (Sec. 4.2.2: operators organised into breadth-first levels, Eqs. 4-5 over

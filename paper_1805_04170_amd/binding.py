@@ -29,7 +29,7 @@ EXPORTS = [
     "tt_conv_forward", "tt_conv_backward", "tt_profile_begin", "tt_profile_end", "tt_profile_get",
     "tt_plan_graph", "tt_graph_eval", "tt_graph_plan_cost", "tt_graph_plan_delta", "tt_graph_plan_levels",
     "tt_graph_plan_level_of", "tt_graph_plan_tiling", "tt_graph_plan_forms", "tt_graph_plan_free",
-    "tt_conversion_cross_elems", "tt_product_cross_elems",
+    "tt_conversion_cross_elems", "tt_product_cross_elems", "tt_fc_chain_cross_elems",
 ]
 TT_LETTER_REP, TT_LETTER_FREE = 255, 253
 TT_GOP_CONTRACT, TT_GOP_ELEMENTWISE, TT_GOP_BATCH, TT_GOP_SAMPLE_CHANNEL = 0, 1, 2, 3
@@ -102,6 +102,7 @@ def lib():
         L.tt_conversion_cross_elems.argtypes = [ctypes.c_int64, ctypes.c_int64, tt_tiling, tt_tiling, ctypes.c_int, _u64p]
         L.tt_product_cross_elems.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, tt_tiling, tt_tiling, tt_tiling,
                                              _u8p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, _u64p]
+        L.tt_fc_chain_cross_elems.argtypes = [lp, ctypes.c_int, ctypes.c_int64, ctypes.c_int, tp, tp, tp, _u8p, _u64p]
         gtp, gop = ctypes.POINTER(tt_graph_tensor), ctypes.POINTER(tt_graph_op)
         L.tt_plan_graph.argtypes = [gtp, ctypes.c_int, gop, ctypes.c_int, ctypes.c_int, ctypes.c_uint32, _u8p,
                                     ctypes.POINTER(ctypes.c_void_p)]
@@ -311,23 +312,18 @@ def tt_product_cross_elems(M, K, N, tX, tY, tZ, form_seq, mult=(1, 1, 1), k=None
     return [out[0], out[1], out[2]]
 
 
-def swap_rc(t):
-    """tiling of the transposed matrix"""
-    return t.translate(str.maketrans("RC", "CR"))
-
-
-def fc_step_cross_elems(widths, batch, k, x, g, w, layer_forms):
-    """Counted cross-shard elements of one forward + backward pass over a fully-connected chain: tilings as the
-    planner returns them (x[0..L], g[0..L], w[0..L-1]), layer_forms[l][op] the form strings ('123') of the forward,
-    data-gradient and weight-gradient products.  Orientation of the three products as in the planner (Sec. 4.2.2)."""
-    total = 0
-    for l in range(1, len(widths)):
-        ni, no = widths[l - 1], widths[l]
-        f = layer_forms[l - 1]
-        total += sum(tt_product_cross_elems(batch, ni, no, x[l - 1], w[l - 1], x[l], f[0]))
-        total += sum(tt_product_cross_elems(batch, no, ni, g[l], swap_rc(w[l - 1]), g[l - 1], f[1]))
-        total += sum(tt_product_cross_elems(ni, batch, no, swap_rc(x[l - 1]), g[l], w[l - 1], f[2]))
-    return total
+def tt_fc_chain_cross_elems(layers, batch, k, x, g, w, layer_forms):
+    """layer_forms[l][op]: form strings ('123') of the forward, data-gradient and weight-gradient product of layer l."""
+    L = len(layers)
+    xa = (tt_tiling * (L + 1))(*[tiling(t) for t in x])
+    ga = (tt_tiling * (L + 1))(*[tiling(t) for t in g])
+    wa = (tt_tiling * L)(*[tiling(t) for t in w])
+    flat = [int(ch) - 1 for lf in layer_forms for f in lf for ch in f]
+    fo = (ctypes.c_uint8 * max(len(flat), 1))(*flat)
+    out = ctypes.c_uint64()
+    _check(lib().tt_fc_chain_cross_elems(_layers(layers), L, batch, k, xa, ga, wa, fo, ctypes.byref(out)),
+           "tt_fc_chain_cross_elems")
+    return out.value
 
 
 # ----------------------------------------------------- planner, general graphs

@@ -77,3 +77,31 @@ extern "C" tt_status tt_product_cross_elems(int64_t M, int64_t K, int64_t N, tt_
     if (st != TT_OK) return st;
     return tt::cross_elems(M, N, aZ, tZ.cut, k, mult_z, &elems[2]);
 }
+
+extern "C" tt_status tt_fc_chain_cross_elems(const tt_layer *layers, int n_layers, int64_t batch, int k, const tt_tiling *x,
+                                             const tt_tiling *g, const tt_tiling *w, const uint8_t *forms, uint64_t *elems)
+{
+    if (!layers || !x || !g || !w || !forms || !elems || n_layers < 1 || n_layers > TT_MAX_LAYERS || batch <= 0) return TT_EINVAL;
+    if (!tt::valid_k(k)) return TT_EINVAL;
+    uint64_t total = 0;
+    for (int l = 1; l <= n_layers; ++l) {
+        const tt_layer &y = layers[l - 1];
+        if (y.kind != TT_FC) return TT_EUNSUPPORTED;
+        if (y.n_in <= 0 || y.n_out <= 0 || (l > 1 && y.n_in != layers[l - 2].n_out)) return TT_EINVAL;
+        const uint8_t *f = forms + (size_t)(l - 1) * 3 * k;
+        uint64_t e[3];
+        // the three products in the planner's orientation (Sec. 4.2.2): x_l = x_{l-1} W_l; g_{l-1} = g_l W_l^T;
+        // dW_l = x_{l-1}^T g_l, stored like W_l
+        tt_status st = tt_product_cross_elems(batch, y.n_in, y.n_out, x[l - 1], w[l - 1], x[l], f, k, 1, 1, 1, e);
+        if (st != TT_OK) return st;
+        total += e[0] + e[1] + e[2];
+        st = tt_product_cross_elems(batch, y.n_out, y.n_in, g[l], tt::transpose_tiling(w[l - 1], k), g[l - 1], f + k, k, 1, 1, 1, e);
+        if (st != TT_OK) return st;
+        total += e[0] + e[1] + e[2];
+        st = tt_product_cross_elems(y.n_in, batch, y.n_out, tt::transpose_tiling(x[l - 1], k), g[l], w[l - 1], f + 2 * k, k, 1, 1, 1, e);
+        if (st != TT_OK) return st;
+        total += e[0] + e[1] + e[2];
+    }
+    *elems = total;
+    return TT_OK;
+}

@@ -347,17 +347,17 @@ def test_counted_elements_of_a_whole_step_equal_the_plan_cost_at_one_cut():
     layers = fc_layers(widths)
     p = tt.tt_plan_chain(layers, batch, 1)
     forms = [[p.forms(l, op) for op in range(3)] for l in range(1, 3)]
-    assert tt.fc_step_cross_elems(widths, batch, 1, p.x(), p.g(), p.w(), forms) == p.cost
+    assert tt.tt_fc_chain_cross_elems(layers, batch, 1, p.x(), p.g(), p.w(), forms) == p.cost
     # data parallelism at one cut: both weight gradients are all-reduced, nothing else moves
     x = g = ["R"] * 3
     w = ["r"] * 2
     cost, _, f = tt.tt_plan_eval(layers, batch, 1, x, g, w)
-    assert tt.fc_step_cross_elems(widths, batch, 1, x, g, w, f) == cost == 2 * (24 * 16 + 16 * 8)
+    assert tt.tt_fc_chain_cross_elems(layers, batch, 1, x, g, w, f) == cost == 2 * (24 * 16 + 16 * 8)
     # more cuts: the recursive model and the flat count part ways (two row cuts of a large batch, weights replicated:
     # the model charges 2|W| (2^k - 1), every one of the four devices really fetches three foreign partial sums of |W|)
     k, big = 2, 256
     x = g = ["RR"] * 3
     w = ["rr"] * 2
     cost, _, f = tt.tt_plan_eval(layers, big, k, x, g, w)
-    counted = tt.fc_step_cross_elems(widths, big, k, x, g, w, f)
+    counted = tt.tt_fc_chain_cross_elems(layers, big, k, x, g, w, f)
     assert cost == 2 * (24 * 16 + 16 * 8) * 3 and counted == 4 * 3 * (24 * 16 + 16 * 8)
