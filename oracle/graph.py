@@ -32,6 +32,11 @@ both: same letter 0; between two different cuts A/2; cut -> replicated A; replic
 cut A, -> replicated 2A.  Cut j prices the tiles left by cuts 0..j-1 and carries weight 2^j.  Only even cuts: a
 letter i needs an even extent, a form needs an even extent of the dimension it halves.  An operator's cost under
 k-cut tilings is the minimum over feasible form sequences of sum_j 2^j (cost of form f_j at cut j).
+
+Parity pins (tests/test_oracle_graph.py): one-cut costs of the element-wise, batch-only and per-sample-and-channel
+operators by explicit index-set counts; chains and convolutions written as graphs against the chain oracle (cost.c,
+other code) on random tilings of one to three cuts and on optima; closed forms.  The paper prints no cost of a general
+graph and no k-cut value: beyond those pins the k-cut figures are "parity unpinned by the paper".
 """
 import itertools
 
