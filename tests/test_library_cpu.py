@@ -361,3 +361,23 @@ def test_counted_elements_of_a_whole_step_equal_the_plan_cost_at_one_cut():
     cost, _, f = tt.tt_plan_eval(layers, big, k, x, g, w)
     counted = tt.tt_fc_chain_cross_elems(layers, big, k, x, g, w, f)
     assert cost == 2 * (24 * 16 + 16 * 8) * 3 and counted == 4 * 3 * (24 * 16 + 16 * 8)
+
+
+@pytest.mark.parametrize("net", [alexnet_layers, vgg16_layers])
+def test_whole_network_strategies_rank_as_in_the_paper(net):
+    # Sec. 2.2 / Sec. 6: data parallelism, model parallelism, the hand-made hybrid (convolutions data parallel,
+    # fully-connected layers model parallel) and the searched tiling, priced by the same cost model at three cuts
+    layers, k = net(), 3
+    L = len(layers)
+    fc = [l.kind == tt.TT_FC for l in layers]
+    first_fc = fc.index(True)
+    for b in (32, 256, 2048):
+        dp = tt.tt_plan_eval(layers, b, k, ["R" * k] * (L + 1), ["R" * k] * (L + 1), ["r" * k] * L)[0]
+        mp = tt.tt_plan_eval(layers, b, k, ["r" * k] * (L + 1), ["r" * k] * (L + 1), ["C" * k] * L)[0]
+        act = ["R" * k if l <= first_fc else "r" * k for l in range(L + 1)]
+        hybrid = tt.tt_plan_eval(layers, b, k, act, act, ["C" * k if fc[l] else "r" * k for l in range(L)])[0]
+        best = tt.tt_plan_chain(layers, b, k).cost
+        assert best < hybrid < min(dp, mp)
+        # model parallelism moves activations: it grows with the batch, data parallelism hardly does
+        if b > 32:
+            assert mp > dp
