@@ -381,3 +381,22 @@ def test_whole_network_strategies_rank_as_in_the_paper(net):
         # model parallelism moves activations: it grows with the batch, data parallelism hardly does
         if b > 32:
             assert mp > dp
+
+
+def test_counted_traffic_argument_errors():
+    def status(fn):
+        with pytest.raises(tt.TilingError) as e:
+            fn()
+        return e.value.status
+
+    assert status(lambda: tt.tt_conversion_cross_elems(0, 8, "R", "C")) == 1
+    assert status(lambda: tt.tt_conversion_cross_elems(8, 8, "RRRRRRR", "CCCCCCC")) == 1           # more than six cuts
+    assert status(lambda: tt.tt_product_cross_elems(8, 8, 8, "R", "r", "R", "4")) == 1              # no such form
+    assert status(lambda: tt.tt_product_cross_elems(6, 8, 8, "RR", "rr", "RR", "11")) == 2          # M = 6 cannot be halved twice
+    assert status(lambda: tt.tt_product_cross_elems(8, 8, 8, "R", "r", "R", "1", k=7)) == 1
+    conv = [conv_layer(4, 8, 8, 3, 1)]
+    assert status(lambda: tt.tt_fc_chain_cross_elems(conv, 8, 1, ["R"] * 2, ["R"] * 2, ["r"], [["1", "1", "3"]])) == 3
+    two = fc_layers([8, 6, 4])
+    bad = [tt.layer("fc", "none", 8, 6), tt.layer("fc", "none", 5, 4)]                                # widths do not chain
+    assert status(lambda: tt.tt_fc_chain_cross_elems(bad, 8, 1, ["R"] * 3, ["R"] * 3, ["r"] * 2, [["1", "1", "3"]] * 2)) == 1
+    assert tt.tt_fc_chain_cross_elems(two, 8, 0, [""] * 3, [""] * 3, [""] * 2, [["", "", ""]] * 2) == 0   # one device: nothing moves
