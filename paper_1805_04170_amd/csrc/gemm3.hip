@@ -6,6 +6,7 @@
 #include <cstdlib>
 #include "gemm_core3.h"
 #include "gemm_core4.h"
+#include "gemm3_params.h"
 #include "tt_internal.h"
 
 namespace tt {
@@ -112,29 +113,10 @@ tt_status launch_gemm_v4(int count, const void *const *A, const void *const *B, 
                          int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool a_kc, bool b_kc, int out_dtype, int relu,
                          bool vec, int ksplit, int64_t kchunk, void *stream)
 {
-    // what the kernel assumes
-    if (K <= 0 || K % core4::BK4 || (ksplit > 1 && kchunk % core4::BK4) || M < 8 || N < 8) return TT_EUNSUPPORTED;
-    if (count * ksplit > 64 || count < 1) return TT_EUNSUPPORTED;
-    if ((!a_kc && M % 8) || (!b_kc && N % 8)) return TT_EUNSUPPORTED;
-    if (M * K >= (int64_t(1) << 31) || K * N >= (int64_t(1) << 31)) return TT_EUNSUPPORTED; // 32-bit byte offsets
     core3::Params3 p;
-    for (int i = 0; i < 64; ++i) {
-        p.A[i] = i < count ? A[i] : nullptr;
-        p.B[i] = i < count ? B[i] : nullptr;
-        p.C[i] = i < count * ksplit ? C[i] : nullptr;
-    }
-    p.M = (int32_t)M; p.N = (int32_t)N; p.K = (int32_t)K;
-    p.lda = (int32_t)lda; p.ldb = (int32_t)ldb; p.ldc = (int32_t)ldc;
-    p.tiles_m = (int32_t)((M + core4::BM4 - 1) / core4::BM4);
-    p.tiles_n = (int32_t)((N + core4::BN4 - 1) / core4::BN4);
-    const int64_t total = (int64_t)p.tiles_m * p.tiles_n * count * ksplit;
-    if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
-    p.total = (int32_t)total;
-    p.per_xcd = (int32_t)((total + core::kXcds - 1) / core::kXcds);
-    p.wg_per_xcd = p.per_xcd;
-    p.relu = relu;
-    p.ksplit = ksplit;
-    p.kchunk = (int32_t)(ksplit > 1 ? kchunk : K);
+    const tt_status st = fill_params3(&p, core4::BM4, core4::BN4, core4::BK4, 0, count, A, B, C, M, N, K, lda, ldb, ldc, a_kc,
+                                      b_kc, relu, ksplit, kchunk);
+    if (st != TT_OK) return st;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     if (a_kc && b_kc) return launch_layout4<true, true>(p, out_dtype, vec, s);
     if (a_kc && !b_kc) return launch_layout4<true, false>(p, out_dtype, vec, s);
@@ -146,30 +128,10 @@ tt_status launch_gemm_v3(int count, const void *const *A, const void *const *B, 
                          int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool a_kc, bool b_kc, int out_dtype, int relu,
                          bool vec, int ksplit, int64_t kchunk, void *stream)
 {
-    // what the kernel assumes
-    if (K <= 0 || K % 64 || (ksplit > 1 && kchunk % 64) || M < 8 || N < 8) return TT_EUNSUPPORTED;
-    if (count * ksplit > 64 || count < 1) return TT_EUNSUPPORTED;
-    if ((!a_kc && M % 8) || (!b_kc && N % 8)) return TT_EUNSUPPORTED;
-    if (M * K >= (int64_t(1) << 31) || K * N >= (int64_t(1) << 31)) return TT_EUNSUPPORTED; // 32-bit byte offsets
     core3::Params3 p;
-    for (int i = 0; i < 64; ++i) {
-        p.A[i] = i < count ? A[i] : nullptr;
-        p.B[i] = i < count ? B[i] : nullptr;
-        p.C[i] = i < count * ksplit ? C[i] : nullptr;
-    }
-    p.M = (int32_t)M; p.N = (int32_t)N; p.K = (int32_t)K;
-    p.lda = (int32_t)lda; p.ldb = (int32_t)ldb; p.ldc = (int32_t)ldc;
-    p.tiles_m = (int32_t)((M + core3::BM3 - 1) / core3::BM3);
-    p.tiles_n = (int32_t)((N + core3::BN3 - 1) / core3::BN3);
-    const int64_t total = (int64_t)p.tiles_m * p.tiles_n * count * ksplit;
-    if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
-    p.total = (int32_t)total;
-    p.per_xcd = (int32_t)((total + core::kXcds - 1) / core::kXcds);
-    const int per_xcd_cus = cu_count() / core::kXcds > 0 ? cu_count() / core::kXcds : 1;
-    p.wg_per_xcd = p.per_xcd < per_xcd_cus ? p.per_xcd : per_xcd_cus;
-    p.relu = relu;
-    p.ksplit = ksplit;
-    p.kchunk = (int32_t)(ksplit > 1 ? kchunk : K);
+    const tt_status st = fill_params3(&p, core3::BM3, core3::BN3, 64, cu_count(), count, A, B, C, M, N, K, lda, ldb, ldc, a_kc,
+                                      b_kc, relu, ksplit, kchunk);
+    if (st != TT_OK) return st;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     if (a_kc && b_kc) return launch_layout<true, true>(p, out_dtype, vec, s);
     if (a_kc && !b_kc) return launch_layout<true, false>(p, out_dtype, vec, s);

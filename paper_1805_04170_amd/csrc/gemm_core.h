@@ -9,8 +9,8 @@
 // convolution.  The accumulators leave through a wave-private LDS staging area so that global stores are 16-byte
 // vectors along C's rows.
 #pragma once
-#include <hip/hip_runtime.h>
 #include <cstdint>
+#include "tt_device.h"
 
 namespace tt {
 namespace core {

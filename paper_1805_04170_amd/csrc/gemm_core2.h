@@ -11,8 +11,8 @@
 //                         row (k0 + j / 4, rows 4 (j % 4) ..) from lane j hands lane i the values (k0 + e, row i).
 // Out-of-range chunks (K tails, image padding) are fetched from a 16-byte block of zeros instead of being masked.
 #pragma once
-#include <hip/hip_runtime.h>
 #include <cstdint>
+#include "tt_device.h"
 #include "gemm_core.h"
 
 namespace tt {
@@ -29,8 +29,7 @@ constexpr int BM2 = 256, BN2 = 256;
 constexpr int kStageBytes = (BM2 + BN2) * BK * 2; // 64 KB
 constexpr size_t kSmemBytes = 2 * (size_t)kStageBytes;
 
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) void *lds_ptr;
+using dev::s16x4;
 
 __device__ __attribute__((aligned(16))) const uint32_t g_zero_chunk[4] = {0, 0, 0, 0};
 
@@ -62,14 +61,8 @@ struct DenseRC2 {
 
 __device__ __forceinline__ void load_chunk_to_lds(const void *g, char *lds_wave_base)
 {
-    // Every lane supplies its own global address; the 64 chunks land at lds_wave_base + lane * 16 (M0 holds the
-    // wave-uniform LDS base).  Written as inline assembly on purpose: for the builtin form the compiler's wait-count
-    // pass assumes that any later LDS read may alias the incoming data and puts s_waitcnt vmcnt(0) in front of the next
-    // fragment read, which turns the prefetch of tile kt+1 into a blocking load.  Here the waits are the explicit
-    // s_waitcnt vmcnt(..) + barrier pairs of the main loop.  (s_nop: one wait state between the write of M0 and its use.)
-    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
-        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_wave_base);
-    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "{m0}"(lds_addr), "v"(g) : "memory");
+    // every lane supplies its own global address; the 64 chunks land at lds_wave_base + lane * 16 (see tt_device.h)
+    dev::lds_dma16(g, __builtin_amdgcn_readfirstlane(dev::lds_addr(lds_wave_base)));
 }
 
 // issue the loads of one operand tile (ROWS x 64) into lds
@@ -107,7 +100,7 @@ template <int ROWS, bool KC> __device__ __forceinline__ bf16x8 read_frag(const c
         for (int h = 0; h < 2; ++h) {
             const int k = ks * 16 + (g16 >> 1) * 8 + h * 4 + (j >> 2);
             const char *a = lds + k * (ROWS * 2) + ((c ^ ((k & 3) << 1)) << 4) + byte;
-            u.h[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a);
+            u.h[h] = dev::lds_read_tr16_b64(a);
         }
         return u.v;
     }

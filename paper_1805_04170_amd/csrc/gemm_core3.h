@@ -21,8 +21,8 @@
 //     bytes of one C row.  bf16 results go through a small wave-private LDS area that lies outside the ring, 16 rows at
 //     a time, so the epilogue needs no workgroup barrier and never touches a stage that a prefetch may be filling.
 #pragma once
-#include <hip/hip_runtime.h>
 #include <cstdint>
+#include "tt_device.h"
 #include "gemm_core.h"
 #include "gemm_core2.h"
 
@@ -152,7 +152,7 @@ template <int BK, bool KC, bool IS_A> struct Feeder {
         const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b64 >> 32));
         const uint64_t sbase = ((uint64_t)b_hi << 32) | (uint64_t)b_lo;
         const uint32_t dst = lds + (wave * 64u + (uint32_t)i * kThreads3) * 16u;
-        asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff[i]), "s"(sbase), "{m0}"(dst) : "memory");
+        dev::lds_dma16(voff[i], sbase, dst);
     }
 
     // Move on to the next K tile.  Past the end of the list the last K tile stays current and is fetched again (into a
@@ -208,7 +208,7 @@ __device__ __forceinline__ void run_tiles(const Params3 &p, char *smem)
     static_assert(W <= 63, "vmcnt range");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm0 = (wave / WN) * (TM * 32), wn0 = (wave % WN) * (TN * 32);
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    const uint32_t lds0 = dev::lds_addr(smem);
 
     Feeder<BK, A_KC, true> fa;
     Feeder<BK, B_KC, false> fb;

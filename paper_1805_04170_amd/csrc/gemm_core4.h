@@ -17,8 +17,8 @@
 //   - epilogue: bf16 results with 16-byte rows are turned around in a wave-private strip of the (drained) ring, 16 rows
 //     at a time; everything else is stored element-wise from the accumulators.
 #pragma once
-#include <hip/hip_runtime.h>
 #include <cstdint>
+#include "tt_device.h"
 #include "gemm_core.h"
 #include "gemm_core2.h"
 #include "gemm_core3.h"
@@ -77,7 +77,7 @@ template <int NL> __device__ __forceinline__ void issue_chunks(const char *base,
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
         const uint32_t dst = lds + (wave * 64u + (uint32_t)i * kThreads4) * 16u;
-        asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff[i]), "s"(sbase), "{m0}"(dst) : "memory");
+        dev::lds_dma16(voff[i], sbase, dst);
     }
 }
 
@@ -103,7 +103,7 @@ __device__ __forceinline__ void tile_product4(const char *abase, int lda, const 
     constexpr int W = (D - 1) * (kLoadsA + kLoadsB); // loads that may still be in flight at the top of an item
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm0 = (wave / WN) * (TM * 32), wn0 = (wave % WN) * (TN * 32);
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    const uint32_t lds0 = dev::lds_addr(smem);
 
     uint32_t voa[kLoadsA], vob[kLoadsB];
     chunk_offsets<BM4, A_KC>(m0, M, lda, voa);

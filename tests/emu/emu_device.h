@@ -1,0 +1,88 @@
+// Host stand-ins for what the tile engines take from the device tool chain (see csrc/tt_device.h).  One thread of one
+// workgroup runs at a time; barriers, wait counts and scheduling hints do nothing (no thread's addresses depend on
+// another thread's data); MFMAs return their accumulator; every global and LDS access is a real host access into
+// buffers of exactly the size the launch was given, checked here and by the address sanitizer.
+#pragma once
+#include <cmath>
+#include <cstdint>
+#include <cstddef>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#define __device__
+#define __host__
+#define __global__
+#define __forceinline__ inline __attribute__((always_inline))
+#define __launch_bounds__(...)
+
+struct EmuDim3 { unsigned x, y, z; };
+extern EmuDim3 threadIdx, blockIdx;
+
+inline void __syncthreads() {}
+inline uint32_t __float_as_uint(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
+
+#define __builtin_amdgcn_readfirstlane(x) (x)
+#define __builtin_amdgcn_s_waitcnt(x) ((void)0)
+#define __builtin_amdgcn_sched_barrier(x) ((void)0)
+#define __builtin_amdgcn_iglp_opt(x) ((void)0)
+#define __builtin_amdgcn_wave_barrier() ((void)0)
+#define __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, x, y, z) (c)
+
+namespace tt {
+namespace dev {
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+struct Region { const char *lo, *hi; };
+extern char *g_lds;              // the workgroup's LDS
+extern size_t g_lds_bytes;
+extern Region g_readable[192];   // operand buffers of the launch
+extern int g_n_readable;
+extern unsigned long long g_dma_bytes;
+
+[[noreturn]] inline void fail(const char *what, const void *addr, size_t n)
+{
+    std::fprintf(stderr, "EMU FAULT: %s at %p (+%zu) block %u thread %u\n", what, addr, n, blockIdx.x, threadIdx.x);
+    std::abort();
+}
+
+inline uint32_t lds_addr(char *p)
+{
+    if (p < g_lds || p > g_lds + g_lds_bytes) fail("pointer outside LDS", p, 0);
+    return (uint32_t)(p - g_lds);
+}
+
+inline void check_read(const char *g, size_t n)
+{
+    for (int i = 0; i < g_n_readable; ++i)
+        if (g >= g_readable[i].lo && g + n <= g_readable[i].hi) return;
+    fail("global read outside every operand", g, n);
+}
+
+inline void land16(const char *g, uint32_t lds_wave_addr)
+{
+    const uint32_t dst = lds_wave_addr + (threadIdx.x & 63u) * 16u;
+    if ((size_t)dst + 16 > g_lds_bytes) fail("load lands outside LDS", g_lds + dst, 16);
+    if ((uintptr_t)g % 16) fail("misaligned 16-byte global -> LDS load", g, 16);
+    check_read(g, 16);
+    std::memcpy(g_lds + dst, g, 16);
+    g_dma_bytes += 16;
+}
+
+inline void lds_dma16(const void *g, uint32_t lds_wave_addr) { land16(static_cast<const char *>(g), lds_wave_addr); }
+inline void lds_dma16(uint32_t lane_offset, uint64_t uniform_base, uint32_t lds_wave_addr)
+{
+    land16(reinterpret_cast<const char *>(uniform_base) + lane_offset, lds_wave_addr);
+}
+
+inline s16x4 lds_read_tr16_b64(const char *a)
+{
+    if (a < g_lds || a + 8 > g_lds + g_lds_bytes) fail("LDS transpose read outside LDS", a, 8);
+    s16x4 v;
+    std::memcpy(&v, a, 8);
+    return v;
+}
+
+} // namespace dev
+} // namespace tt
