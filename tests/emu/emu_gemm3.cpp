@@ -1,11 +1,12 @@
-// Host build of the persistent tile engine (csrc/gemm_core3.h) and of the 256 x 128 engine (csrc/gemm_core4.h) for
-// checking their memory accesses without a GPU: for a list of products the launch parameters are derived exactly as the
+// Host build of the direct-to-LDS tile engine (csrc/gemm_core2.h), the persistent one (csrc/gemm_core3.h) and the
+// 256 x 128 one (csrc/gemm_core4.h) for checking their memory accesses without a GPU: for a list of products the launch parameters are derived exactly as the
 // launchers derive them (csrc/gemm3_params.h), every workgroup and every thread of the grid is run in turn, and every
 // access they make has to stay inside the operands, the outputs and the LDS of the launch; afterwards every element of
 // every output must have been written.  Build: see tests/test_kernel_emulation.py (host clang, address sanitizer).
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <type_traits>
 #include <vector>
 
 #define TT_HOST_EMULATION 1
@@ -67,9 +68,45 @@ template <bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED> void run4(const core
         }
 }
 
+template <bool A_KC, bool B_KC, bool OUT_BF16, bool VEC> void run2(const core3::Params3 &p, unsigned grid)
+{
+    std::vector<char> lds(core2::kSmemBytes);
+    dev::g_lds = lds.data();
+    dev::g_lds_bytes = core2::kSmemBytes;
+    for (unsigned b = 0; b < grid; ++b)
+        for (unsigned t = 0; t < (unsigned)core2::kThreads2; ++t) {
+            blockIdx = {b, 0, 0};
+            threadIdx = {t, 0, 0};
+            // the body of gemm_bf16_v2_kernel (csrc/gemm.hip)
+            const int logical = core::logical_block(p.per_xcd, p.total);
+            if (logical < 0) continue;
+            const int tiles = p.tiles_m * p.tiles_n;
+            const int vshard = logical / tiles;
+            const int tt_ = logical - vshard * tiles;
+            int tm, tn;
+            core::grouped_tile(tt_, p.tiles_m, p.tiles_n, &tm, &tn);
+            const int shard = vshard / p.ksplit;
+            const int kbeg = (vshard - shard * p.ksplit) * p.kchunk;
+            const int klen = p.K - kbeg < p.kchunk ? p.K - kbeg : p.kchunk;
+            using LA = std::conditional_t<A_KC, core2::DenseKC2, core2::DenseRC2>;
+            using LB = std::conditional_t<B_KC, core2::DenseKC2, core2::DenseRC2>;
+            LA la;
+            la.base = reinterpret_cast<const char *>(p.A[shard]) + (size_t)kbeg * (A_KC ? 2 : 2 * (size_t)p.lda);
+            la.ld = p.lda; la.rows = p.M; la.K = klen;
+            LB lb;
+            lb.base = reinterpret_cast<const char *>(p.B[shard]) + (size_t)kbeg * (B_KC ? 2 : 2 * (size_t)p.ldb);
+            lb.ld = p.ldb; lb.rows = p.N; lb.K = klen;
+            core2::tile_product2<OUT_BF16, VEC>(la, lb, p.C[vshard], p.ldc, p.M, p.N, klen, tm * 256, tn * 256, p.relu != 0, lds.data());
+        }
+}
+
 template <bool A_KC, bool B_KC> void dispatch(const Case &c, const core3::Params3 &p, bool vec)
 {
-    if (c.engine == 3) {
+    if (c.engine == 2) {
+        const unsigned grid = (unsigned)p.per_xcd * core::kXcds;
+        if (c.out_bf16) { if (vec) run2<A_KC, B_KC, true, true>(p, grid); else run2<A_KC, B_KC, true, false>(p, grid); }
+        else { if (vec) run2<A_KC, B_KC, false, true>(p, grid); else run2<A_KC, B_KC, false, false>(p, grid); }
+    } else if (c.engine == 3) {
         const unsigned grid = (unsigned)p.wg_per_xcd * core::kXcds;
         // the choice of launch_layout (csrc/gemm3.hip)
         if (c.out_bf16 && vec) { run3<A_KC, B_KC, true, true, true>(p, grid); return; }
@@ -110,7 +147,14 @@ int run_case(const Case &c)
     const long kchunk = c.ksplit == 1 ? c.K : ((c.K + c.ksplit - 1) / c.ksplit + 63) / 64 * 64; // as tt_shard_gemm splits K
     core3::Params3 p;
     const long lda = c.a_kc ? c.K : c.M, ldb = c.b_kc ? c.K : c.N;
-    const tt_status st = c.engine == 3
+    // (the second engine takes any K: its loaders read a zero chunk past the end; same tile grid as the third's, one
+    // workgroup per tile)
+    dev::g_readable[dev::g_n_readable++] = {reinterpret_cast<const char *>(core2::g_zero_chunk),
+                                            reinterpret_cast<const char *>(core2::g_zero_chunk) + 16};
+    const tt_status st = c.engine == 2
+        ? fill_params3(&p, 256, 256, 1, 0, c.count, Ap.data(), Bp.data(), Cp.data(), c.M, c.N, c.K, lda, ldb, c.N, c.a_kc, c.b_kc,
+                       c.relu, c.ksplit, kchunk)
+        : c.engine == 3
         ? fill_params3(&p, core3::BM3, core3::BN3, 64, 256, c.count, Ap.data(), Bp.data(), Cp.data(), c.M, c.N, c.K, lda, ldb, c.N,
                        c.a_kc, c.b_kc, c.relu, c.ksplit, kchunk)
         : fill_params3(&p, core4::BM4, core4::BN4, core4::BK4, 0, c.count, Ap.data(), Bp.data(), Cp.data(), c.M, c.N, c.K, lda, ldb,

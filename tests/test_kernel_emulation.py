@@ -41,6 +41,10 @@ CASES = [
     (3, 2, 520, 776, 64, 0, 0, 1, 0, 1),
     (3, 1, 264, 1000, 192, 1, 0, 1, 0, 1),      # 1000 columns: ragged last tile, 16-byte rows
     (3, 1, 264, 1004, 128, 1, 1, 0, 0, 1),      # fp32 rows of 1004
+    (2, 8, 256, 3136, 4096, 1, 1, 0, 0, 2),     # direct-to-LDS engine: data gradient of the VGG-16 first classifier layer
+    (2, 8, 1000, 1016, 200, 0, 0, 1, 1, 1),     # ragged M, N and K (K tail read as zero chunks)
+    (2, 8, 1024, 1024, 192, 0, 1, 0, 0, 1),
+    (2, 1, 520, 264, 72, 1, 1, 1, 0, 1),
     (4, 2, 520, 520, 96, 1, 1, 1, 1, 1),        # the 256 x 128 engine: shapes of its GPU tests and of the hidden layers
     (4, 8, 256, 1024, 512, 0, 0, 0, 0, 1),
     (4, 1, 136, 264, 32, 1, 0, 1, 0, 1),
