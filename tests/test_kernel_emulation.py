@@ -72,3 +72,27 @@ def test_products_the_engines_do_not_take_are_refused_by_the_launch_code(emu):
     assert run(emu, (3, 1, 264, 264, 96, 1, 1, 1, 0, 1)).returncode == 2      # K not a multiple of 64
     assert run(emu, (4, 1, 264, 260, 64, 1, 0, 1, 0, 1)).returncode == 2      # row-contiguous B with N not a multiple of 8
     assert run(emu, (3, 1, 4, 264, 64, 1, 1, 1, 0, 1)).returncode == 2        # fewer than eight rows
+
+
+# the register-staged engine: one kernel configuration per build
+# (BM, BN, WM, WN, DEPTH, KMASK, A_KC, B_KC, BF16, VEC), (count, M, N, K, relu, ksplit)
+CASES1 = [
+    ((128, 128, 2, 2, 1, 1, 1, 1, 0, 1), (8, 256, 512, 1000, 0, 1)),     # data gradient of the last VGG-16 classifier layer
+    ((128, 128, 2, 2, 1, 1, 0, 0, 1, 1), (1, 520, 72, 40, 0, 1)),        # three row tiles, one short K tile, both operands transposed in registers
+    ((128, 128, 2, 2, 1, 0, 1, 1, 1, 0), (2, 128, 132, 64, 1, 1)),       # element-wise stores (rows of 132 bf16; both operands K-contiguous, as the launcher demands of a product whose N is no multiple of 8)
+    ((256, 128, 2, 2, 2, 0, 1, 0, 1, 1), (1, 264, 264, 1024, 0, 1)),     # deep-prefetch variant
+    ((256, 256, 2, 4, 1, 1, 1, 0, 1, 1), (8, 1000, 1016, 200, 1, 1)),    # eight waves, ragged everything
+    ((128, 128, 2, 2, 0, 0, 0, 1, 0, 1), (2, 136, 264, 256, 0, 2)),      # single LDS buffer, in-shard K split
+]
+
+
+@pytest.mark.parametrize("cfg,case", CASES1, ids=lambda v: "x".join(str(i) for i in v))
+def test_register_staged_engine_stays_inside_its_buffers(tmp_path, cfg, case):
+    names = ["E1_BM", "E1_BN", "E1_WM", "E1_WN", "E1_DEPTH", "E1_KMASK", "E1_AKC", "E1_BKC", "E1_BF16", "E1_VEC"]
+    exe = str(tmp_path / "emu_gemm1")
+    cmd = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address"] + ["-D%s=%d" % (n, v) for n, v in zip(names, cfg)] + [
+        "-I" + os.path.join(ROOT, "tests", "emu"), "-I" + os.path.join(ROOT, "paper_1805_04170_amd", "csrc"),
+        "-I" + os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "emu", "emu_gemm1.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    r = run(exe, case)
+    assert r.returncode == 0, r.stdout[-400:] + r.stderr[-1200:]
