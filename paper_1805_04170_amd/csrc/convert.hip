@@ -7,9 +7,9 @@
 // workgroup's piece coordinates are wave-uniform (scalar) and each lane only moves 16-byte vectors.
 //
 // These kernels are HBM-bound: coalesced 128-bit accesses, several loads in flight per lane, no LDS.
-#include <hip/hip_runtime.h>
 #include <cstdint>
 #include <cstdlib>
+#include "tt_device.h"
 #include "tt_internal.h"
 
 namespace tt {

@@ -21,6 +21,8 @@ extern EmuDim3 threadIdx, blockIdx;
 
 inline void __syncthreads() {}
 inline uint32_t __float_as_uint(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
+inline float __uint_as_float(uint32_t u) { float f; std::memcpy(&f, &u, 4); return f; }
+inline int __popc(uint32_t v) { return __builtin_popcount(v); }
 
 #define __builtin_amdgcn_readfirstlane(x) (x)
 #define __builtin_amdgcn_s_waitcnt(x) ((void)0)
@@ -28,6 +30,28 @@ inline uint32_t __float_as_uint(float f) { uint32_t u; std::memcpy(&u, &f, 4); r
 #define __builtin_amdgcn_iglp_opt(x) ((void)0)
 #define __builtin_amdgcn_wave_barrier() ((void)0)
 #define __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, x, y, z) (c)
+
+// ---- the little of the HIP host API that the launch code of a .hip file uses: a launch runs the kernel for every thread
+// of every workgroup in turn (no thread of the emulated kernels reads what another thread wrote)
+struct dim3 {
+    unsigned x, y, z;
+    dim3(unsigned x_ = 1, unsigned y_ = 1, unsigned z_ = 1) : x(x_), y(y_), z(z_) {}
+};
+typedef void *hipStream_t;
+enum hipError_t { hipSuccess = 0 };
+inline hipError_t hipGetLastError() { return hipSuccess; }
+extern unsigned long long g_emu_threads_run;
+template <class F> inline void emu_launch(F &&body, dim3 grid, dim3 block)
+{
+    for (unsigned b = 0; b < grid.x; ++b)
+        for (unsigned t = 0; t < block.x; ++t) {
+            blockIdx = {b, 0, 0};
+            threadIdx = {t, 0, 0};
+            body();
+            ++g_emu_threads_run;
+        }
+}
+#define hipLaunchKernelGGL(kern, grid, block, smem, stream, ...) emu_launch([&]() { kern(__VA_ARGS__); }, grid, block)
 
 namespace tt {
 namespace dev {

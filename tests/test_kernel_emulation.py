@@ -96,3 +96,104 @@ def test_register_staged_engine_stays_inside_its_buffers(tmp_path, cfg, case):
     subprocess.run(cmd, check=True, capture_output=True, text=True)
     r = run(exe, case)
     assert r.returncode == 0, r.stdout[-400:] + r.stderr[-1200:]
+
+
+# ---- the conversion kernels with their launch code: tt_retile / tt_retile_gate / tt_reduce run on host buffers and are
+# compared bit for bit with what the oracle expects (same cases as the GPU tests, plus sizes that take the launches with
+# two and four vectors per lane)
+
+import itertools
+
+import numpy as np
+
+from oracle import execute as ex
+from oracle import tiling as tl
+from synthetic import bf16_bits_to_f32, to_bf16_bits
+
+
+@pytest.fixture(scope="module")
+def emu_convert(tmp_path_factory):
+    exe = str(tmp_path_factory.mktemp("emu") / "emu_convert")
+    cmd = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address", "-x", "c++", "-I" + os.path.join(ROOT, "tests", "emu"),
+           "-I" + os.path.join(ROOT, "paper_1805_04170_amd", "csrc"), "-I" + os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "emu", "emu_convert.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    return exe
+
+
+def _dump(d, stem, shards):
+    for i, sh in enumerate(shards):
+        np.ascontiguousarray(sh).tofile(os.path.join(d, "%s%d.bin" % (stem, i)))
+
+
+def _call(exe, d, *args):
+    r = subprocess.run([exe, str(d)] + [str(a) if a != "" else "-" for a in args], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout[-300:] + r.stderr[-1500:]
+    return r.stdout
+
+
+def test_retile_on_the_host_is_bit_exact(emu_convert, tmp_path):
+    rng = np.random.default_rng(5)
+    NP = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}
+    cases = []
+    for e in (1, 2, 4, 8):                                   # every pair of two-cut tilings, every element size
+        T = rng.integers(0, 256, size=(24, 40 * e), dtype=np.uint8).view(NP[e]).reshape(24, 40)
+        for A, B in itertools.product(tl.all_tilings(2), repeat=2):
+            cases.append((T, A, B, e))
+    T3 = rng.integers(0, 1 << 16, size=(200, 1000), dtype=np.uint16)   # 125-wide shards: 8-, 4- and 2-byte vectors
+    ts = tl.all_tilings(3)
+    for ia, ib in rng.choice(len(ts), size=(25, 2)):
+        cases.append((T3, ts[ia], ts[ib], 2))
+    big = rng.integers(0, 1 << 16, size=(512, 4096), dtype=np.uint16)   # 256 K vectors: two per lane
+    cases += [(big, "RC", "CR", 2), (big, "RRC", "Crr", 2)]
+    bigger = rng.integers(0, 1 << 16, size=(1024, 4104), dtype=np.uint16)  # four per lane, ragged tail of workgroups
+    cases += [(bigger, "RC", "CR", 2)]
+    cases += [(T3[:64, :96], "", "", 2), (T3[:64, :96].copy(), "RCRC", "CRrR", 2), (T3[:64, :64].copy(), "RCRCRC", "CRCRCR", 2)]
+    for n, (T, A, B, e) in enumerate(cases):
+        d = tmp_path / ("r%d" % n)
+        d.mkdir()
+        _dump(d, "src", tl.tile(T, A))
+        _dump(d, "exp", tl.tile(T, B))
+        _call(emu_convert, d, "retile", len(A), T.shape[0], T.shape[1], e, A, B)
+
+
+def test_gated_retile_and_reduce_on_the_host(emu_convert, tmp_path):
+    rng = np.random.default_rng(6)
+    n = 0
+    for rows, cols in ((48, 80), (512, 1032)):
+        v = rng.standard_normal((rows, cols)).astype(np.float32)
+        m = rng.standard_normal((rows, cols)).astype(np.float32)
+        m[rng.random((rows, cols)) < 0.3] = 0.0
+        for bf in (True, False):
+            V = to_bf16_bits(v) if bf else v
+            Mk = to_bf16_bits(m) if bf else m
+            mf = bf16_bits_to_f32(Mk) if bf else Mk
+            want = np.where(mf > 0, V, np.zeros_like(V))
+            for A, Am, B in [("RR", "CC", "Rr"), ("Cr", "rR", "CC"), ("rr", "RC", "RC")]:
+                d = tmp_path / ("g%d" % n)
+                n += 1
+                d.mkdir()
+                _dump(d, "src", tl.tile(V, A))
+                _dump(d, "msk", tl.tile(Mk, Am))
+                _dump(d, "exp", tl.tile(want, B))
+                _call(emu_convert, d, "gate", 2, rows, cols, 1 if bf else 0, A, Am, B)
+    # partial-sum reduction: fp32 sums in the kernel's fixed order (increasing partial number), then ReLU, then the cast
+    for forms, B, out_bf16, relu, rows, cols in [("31", "RC", True, True, 32, 48), ("33", "rR", False, False, 32, 48),
+                                                 ("313", "CRr", True, False, 64, 64), ("12", "CR", True, True, 32, 48),
+                                                 ("3", "R", False, True, 512, 4096), ("33", "RC", True, False, 1024, 4096)]:
+        k = len(forms)
+        grid = ex.output_grid_tiling(forms)
+        parts = [rng.standard_normal(tl.shard_shape(rows, cols, grid)).astype(np.float32) for _ in range(1 << k)]
+        Z = np.zeros((rows, cols), dtype=np.float32)
+        for s, p in enumerate(parts):                      # shard s adds into its block; ids in increasing order
+            sl = tl.shard_slices(rows, cols, grid, s)
+            Z[sl] = Z[sl] + p
+        if relu:
+            Z = np.maximum(Z, np.float32(0))
+        want = to_bf16_bits(Z) if out_bf16 else Z
+        d = tmp_path / ("s%d" % n)
+        n += 1
+        d.mkdir()
+        _dump(d, "src", parts)
+        _dump(d, "exp", tl.tile(want, B))
+        _call(emu_convert, d, "reduce", k, rows, cols, 1 if out_bf16 else 0, 1 if relu else 0, forms, B)
