@@ -11,9 +11,9 @@
 //   wgrad     dW[ko][(r,s,c)]  = sum_{(n,p,q)}  dY[(n,p,q)][ko] * X[n, p+r-pad, q+s-pad, c]
 //             GEMM M = Ks, N = R*S*Cs, K = Ns*P*Q;  A = dY transposed (dense), B gathered from X (c contiguous)
 // No im2col buffer is ever materialised: the gather happens while operand tiles are staged into LDS.
-#include <hip/hip_runtime.h>
 #include <cstdint>
 #include <cstdlib>
+#include "tt_device.h"
 #include "gemm_core.h"
 #include "tt_internal.h"
 

@@ -39,19 +39,34 @@ struct dim3 {
 };
 typedef void *hipStream_t;
 enum hipError_t { hipSuccess = 0 };
+enum hipFuncAttribute { hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
 inline hipError_t hipGetLastError() { return hipSuccess; }
+inline hipError_t hipFuncSetAttribute(const void *, hipFuncAttribute, int) { return hipSuccess; }
+#define __shared__
 extern unsigned long long g_emu_threads_run;
-template <class F> inline void emu_launch(F &&body, dim3 grid, dim3 block)
+// kernels that declare `extern __shared__ T name[]`: the driver defines the array with g_emu_dyn_cap bytes and registers
+// it here; a launch then makes everything past the launch's dynamic size inaccessible to the address sanitizer
+extern char *g_emu_dyn_lds;
+extern size_t g_emu_dyn_cap;
+extern "C" void __asan_poison_memory_region(void const volatile *addr, size_t size);
+extern "C" void __asan_unpoison_memory_region(void const volatile *addr, size_t size);
+template <class F> inline void emu_launch(F &&body, dim3 grid, dim3 block, size_t dyn_bytes)
 {
-    for (unsigned b = 0; b < grid.x; ++b)
-        for (unsigned t = 0; t < block.x; ++t) {
-            blockIdx = {b, 0, 0};
-            threadIdx = {t, 0, 0};
-            body();
-            ++g_emu_threads_run;
-        }
+    if (g_emu_dyn_lds) {
+        if (dyn_bytes > g_emu_dyn_cap) { std::fprintf(stderr, "EMU FAULT: launch asks for %zu bytes of LDS\n", dyn_bytes); std::abort(); }
+        __asan_unpoison_memory_region(g_emu_dyn_lds, g_emu_dyn_cap);
+        __asan_poison_memory_region(g_emu_dyn_lds + dyn_bytes, g_emu_dyn_cap - dyn_bytes);
+    }
+    for (unsigned by = 0; by < grid.y; ++by)
+        for (unsigned b = 0; b < grid.x; ++b)
+            for (unsigned t = 0; t < block.x; ++t) {
+                blockIdx = {b, by, 0};
+                threadIdx = {t, 0, 0};
+                body();
+                ++g_emu_threads_run;
+            }
 }
-#define hipLaunchKernelGGL(kern, grid, block, smem, stream, ...) emu_launch([&]() { kern(__VA_ARGS__); }, grid, block)
+#define hipLaunchKernelGGL(kern, grid, block, smem, stream, ...) emu_launch([&]() { kern(__VA_ARGS__); }, grid, block, smem)
 
 namespace tt {
 namespace dev {

@@ -197,3 +197,40 @@ def test_gated_retile_and_reduce_on_the_host(emu_convert, tmp_path):
         _dump(d, "src", parts)
         _dump(d, "exp", tl.tile(want, B))
         _call(emu_convert, d, "reduce", k, rows, cols, 1 if out_bf16 else 0, 1 if relu else 0, forms, B)
+
+
+# ---- the convolution kernels with their launch code (tile choice, grids, the filter flip in front of the data gradient)
+
+@pytest.fixture(scope="module")
+def emu_conv(tmp_path_factory):
+    exe = str(tmp_path_factory.mktemp("emu") / "emu_conv")
+    cmd = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address", "-x", "c++", "-I" + os.path.join(ROOT, "tests", "emu"),
+           "-I" + os.path.join(ROOT, "paper_1805_04170_amd", "csrc"), "-I" + os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "emu", "emu_conv.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    return exe
+
+
+# op (0 forward, 1 data gradient, 2 filter gradient), shards, images, in-channels, out-channels per shard, H, W, R, S, pad,
+# bf16 output, relu, filters flipped first
+CONV_CASES = [
+    (0, 8, 8, 512, 512, 28, 28, 3, 3, 1, 1, 0, 0),     # VGG-16 conv4 cut along the batch: the three benchmark launches
+    (1, 8, 8, 512, 512, 28, 28, 3, 3, 1, 1, 0, 1),
+    (2, 8, 8, 512, 512, 28, 28, 3, 3, 1, 0, 0, 0),
+    (0, 8, 64, 512, 64, 28, 28, 3, 3, 1, 1, 1, 0),     # ... cut along the output channels
+    (1, 8, 64, 512, 64, 28, 28, 3, 3, 1, 0, 0, 1),     # (its data gradient splits the reduction: fp32 partial sums)
+    (2, 8, 64, 512, 64, 28, 28, 3, 3, 1, 1, 0, 0),
+    (1, 2, 2, 16, 24, 9, 9, 3, 3, 1, 1, 0, 0),         # data gradient on its own kernel (filters transposed in registers)
+    (1, 2, 2, 16, 24, 9, 9, 3, 3, 1, 1, 0, 1),         # ... and through the element-wise flip (channel counts not multiples of 64)
+    (0, 2, 3, 8, 16, 7, 5, 5, 1, 2, 0, 0, 0),          # 5 x 1 filter, padding 2, odd image
+    (2, 2, 3, 8, 16, 7, 5, 1, 5, 2, 0, 0, 0),
+    (0, 1, 1, 8, 8, 6, 6, 5, 5, 0, 1, 1, 0),           # 25 taps, no padding
+    (0, 4, 2, 64, 64, 12, 12, 1, 1, 0, 1, 0, 0),       # 1 x 1 filter: the one-tap loader
+    (1, 4, 2, 64, 64, 12, 12, 1, 1, 0, 1, 0, 1),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "op%d_%dx%dx%dx%d_%dx%d_%dx%d" % (c[0], c[1], c[2], c[3], c[4], c[5], c[6], c[7], c[8]))
+def test_convolution_launches_stay_inside_their_buffers(emu_conv, case):
+    r = run(emu_conv, case)
+    assert r.returncode == 0, r.stdout[-400:] + r.stderr[-1500:]
