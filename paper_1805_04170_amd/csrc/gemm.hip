@@ -3,7 +3,7 @@
 //
 // bf16 path: the MFMA tile engine of gemm_core.h with dense-matrix loaders (NN, NT, TN, TT all share one main loop).
 // fp32 path / shapes without 16-byte rows: a plain LDS-tiled FMA kernel with arbitrary strides.
-#include <hip/hip_runtime.h>
+#include "tt_device.h"
 #include <cstdint>
 #include <cstdlib>
 #include <type_traits>

@@ -1,7 +1,7 @@
 // Shard products on the persistent, software-pipelined MFMA engine (gemm_core3.h): kernels and launcher.
 // One launch covers all shards (Sec. 5.2 step 2 of arXiv 1805.04170: every device runs the same sub-operator on its
 // own tiles); the grid is one workgroup per CU and each workgroup walks its share of the 256 x 256 output tiles.
-#include <hip/hip_runtime.h>
+#include "tt_device.h"
 #include <cstdint>
 #include <cstdlib>
 #include "gemm_core3.h"

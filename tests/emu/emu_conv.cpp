@@ -17,8 +17,6 @@ alignas(16) uint16_t smem[96 * 1024]; // what the kernels' `extern __shared__ ui
 
 EmuDim3 threadIdx, blockIdx;
 unsigned long long g_emu_threads_run = 0;
-char *g_emu_dyn_lds = reinterpret_cast<char *>(tt::smem);
-size_t g_emu_dyn_cap = sizeof(tt::smem);
 namespace tt {
 namespace dev {
 char *g_lds = nullptr;
@@ -33,6 +31,8 @@ ProfileScope::~ProfileScope() {}
 
 int main(int argc, char **argv)
 {
+    g_emu_dyn_lds = reinterpret_cast<char *>(tt::smem);
+    g_emu_dyn_cap = sizeof(tt::smem);
     // emu_conv op count Ns Cs Ks H W R S pad out_bf16 relu flip
     if (argc != 14) { std::fprintf(stderr, "usage: emu_conv op count Ns Cs Ks H W R S pad out_bf16 relu flip\n"); return 64; }
     const int op = std::atoi(argv[1]), count = std::atoi(argv[2]);

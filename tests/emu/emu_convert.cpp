@@ -15,8 +15,6 @@
 
 EmuDim3 threadIdx, blockIdx;
 unsigned long long g_emu_threads_run = 0;
-char *g_emu_dyn_lds = nullptr;
-size_t g_emu_dyn_cap = 0;
 namespace tt {
 namespace dev {
 char *g_lds = nullptr;

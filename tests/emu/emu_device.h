@@ -42,14 +42,21 @@ enum hipError_t { hipSuccess = 0 };
 enum hipFuncAttribute { hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
 inline hipError_t hipGetLastError() { return hipSuccess; }
 inline hipError_t hipFuncSetAttribute(const void *, hipFuncAttribute, int) { return hipSuccess; }
+enum hipDeviceAttribute_t { hipDeviceAttributeMultiprocessorCount = 63 };
+inline hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
+inline hipError_t hipDeviceGetAttribute(int *value, hipDeviceAttribute_t, int) { *value = 256; return hipSuccess; } // MI355X: 256 CUs
 #define __shared__
 extern unsigned long long g_emu_threads_run;
 // kernels that declare `extern __shared__ T name[]`: the driver defines the array with g_emu_dyn_cap bytes and registers
 // it here; a launch then makes everything past the launch's dynamic size inaccessible to the address sanitizer
-extern char *g_emu_dyn_lds;
-extern size_t g_emu_dyn_cap;
+inline char *g_emu_dyn_lds = nullptr;
+inline size_t g_emu_dyn_cap = 0;
+// ... several such arrays in one build (one name per kernel family): all of them, each of g_emu_dyn_cap bytes
+inline char *g_emu_dyn_all[4] = {nullptr, nullptr, nullptr, nullptr};
+inline int g_emu_dyn_n = 0;
 extern "C" void __asan_poison_memory_region(void const volatile *addr, size_t size);
 extern "C" void __asan_unpoison_memory_region(void const volatile *addr, size_t size);
+void emu_set_lds_limit(size_t dyn_bytes); // defined below, after tt::dev
 template <class F> inline void emu_launch(F &&body, dim3 grid, dim3 block, size_t dyn_bytes)
 {
     if (g_emu_dyn_lds) {
@@ -57,6 +64,12 @@ template <class F> inline void emu_launch(F &&body, dim3 grid, dim3 block, size_
         __asan_unpoison_memory_region(g_emu_dyn_lds, g_emu_dyn_cap);
         __asan_poison_memory_region(g_emu_dyn_lds + dyn_bytes, g_emu_dyn_cap - dyn_bytes);
     }
+    for (int i = 0; i < g_emu_dyn_n; ++i) {
+        if (dyn_bytes > g_emu_dyn_cap) { std::fprintf(stderr, "EMU FAULT: launch asks for %zu bytes of LDS\n", dyn_bytes); std::abort(); }
+        __asan_unpoison_memory_region(g_emu_dyn_all[i], g_emu_dyn_cap);
+        __asan_poison_memory_region(g_emu_dyn_all[i] + dyn_bytes, g_emu_dyn_cap - dyn_bytes);
+    }
+    emu_set_lds_limit(dyn_bytes);
     for (unsigned by = 0; by < grid.y; ++by)
         for (unsigned b = 0; b < grid.x; ++b)
             for (unsigned t = 0; t < block.x; ++t) {
@@ -88,6 +101,9 @@ extern unsigned long long g_dma_bytes;
 
 inline uint32_t lds_addr(char *p)
 {
+    // with several named LDS arrays in the build: the one the pointer lies in is this kernel's LDS
+    for (int i = 0; i < g_emu_dyn_n; ++i)
+        if (p >= g_emu_dyn_all[i] && p <= g_emu_dyn_all[i] + g_emu_dyn_cap) g_lds = g_emu_dyn_all[i];
     if (p < g_lds || p > g_lds + g_lds_bytes) fail("pointer outside LDS", p, 0);
     return (uint32_t)(p - g_lds);
 }
@@ -125,3 +141,9 @@ inline s16x4 lds_read_tr16_b64(const char *a)
 
 } // namespace dev
 } // namespace tt
+
+inline void emu_set_lds_limit(size_t dyn_bytes)
+{
+    if (g_emu_dyn_n > 0) tt::dev::g_lds_bytes = dyn_bytes;
+}
+

@@ -234,3 +234,49 @@ CONV_CASES = [
 def test_convolution_launches_stay_inside_their_buffers(emu_conv, case):
     r = run(emu_conv, case)
     assert r.returncode == 0, r.stdout[-400:] + r.stderr[-1500:]
+
+
+# ---- the shard-product entry point with its launch code: which engine and tile a shape gets is decided by the same
+# ---- code as in the library, on a device with 256 compute units
+
+@pytest.fixture(scope="module")
+def emu_shard_gemm(tmp_path_factory):
+    exe = str(tmp_path_factory.mktemp("emu") / "emu_shard_gemm")
+    # unoptimised: the optimiser needs minutes for the four engines' instantiations under the sanitizer
+    cmd = [CLANG, "-std=c++17", "-O0", "-fsanitize=address", "-x", "c++", "-I" + os.path.join(ROOT, "tests", "emu"),
+           "-I" + os.path.join(ROOT, "paper_1805_04170_amd", "csrc"), "-I" + os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "emu", "emu_shard_gemm.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    return exe
+
+
+# shards, M, N, K, A transposed, B transposed, bf16 operands, bf16 result, relu, K split inside the launch;
+# then the number of threads the launch must have run (which names the engine: workgroups x their size)
+SHARD_CASES = [
+    ((8, 256, 512, 4096, 0, 0, 1, 1, 1, 1), 32 * 256),      # hidden layer forward at batch 256: 256 x 128 tiles, two workgroups per CU
+    ((8, 3136, 4096, 256, 1, 0, 1, 1, 0, 1), 256 * 512),    # VGG-16 first weight gradient: the persistent engine, one workgroup per CU
+    ((16, 256, 4096, 512, 0, 1, 1, 0, 0, 1), 256 * 512),    # skinny data gradient: 256 x 256 tiles loaded straight into LDS
+    ((16, 256, 2048, 512, 0, 0, 1, 0, 0, 1), 128 * 512),    # skinny NN product: the persistent engine, 128 tiles
+    ((4, 256, 128, 1024, 0, 0, 1, 1, 0, 1), 8 * 256),       # one narrow column of tiles: register-staged 256 x 128
+    ((3, 64, 64, 72, 0, 0, 1, 0, 1, 1), 8 * 256),           # small product, K not a multiple of the tile depth: 128 x 128 with K mask
+    ((3, 50, 70, 33, 0, 1, 0, 0, 0, 1), 6 * 256),           # fp32 operands: the scalar kernel, 64 x 64 tiles
+    ((2, 296, 264, 200, 1, 0, 1, 1, 0, 1), None),           # ragged tiles on every side
+    ((8, 256, 512, 72, 0, 0, 1, 1, 0, 1), None),            # K the 256 x 128 engine refuses: falls through to the register-staged one
+    ((4, 256, 512, 3136, 0, 0, 1, 0, 0, 4), 64 * 256),      # reduction split four ways inside one launch, sixteen partial products
+    ((2, 40, 24, 300, 1, 1, 1, 1, 0, 3), None),             # the same on the smallest tile
+]
+
+
+@pytest.mark.parametrize("case,threads", SHARD_CASES, ids=lambda c: "x".join(map(str, c)) if isinstance(c, tuple) else None)
+def test_shard_product_entry_point_stays_inside_its_buffers(emu_shard_gemm, case, threads):
+    r = run(emu_shard_gemm, case)
+    assert r.returncode == 0, r.stdout[-400:] + r.stderr[-1500:]
+    assert r.stdout.startswith("ok shard_gemm")
+    if threads is not None:
+        assert int(r.stdout.split()[2]) == threads, r.stdout
+
+
+def test_shard_product_entry_point_rejects_what_the_library_rejects(emu_shard_gemm):
+    # a K split that would leave the last chunk empty (chunks are rounded up to the tile depth: two of 64 cover K = 128)
+    r = run(emu_shard_gemm, (2, 64, 64, 128, 0, 0, 1, 0, 0, 3))
+    assert r.returncode == 2 and "status" in r.stdout
