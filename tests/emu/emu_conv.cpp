@@ -10,7 +10,7 @@
 #include <cstdint>
 namespace tt {
 namespace {
-alignas(16) uint16_t smem[96 * 1024]; // what the kernels' `extern __shared__ uint16_t smem[]` refers to here
+alignas(16) thread_local uint16_t smem[96 * 1024]; // what the kernels' `extern __shared__ uint16_t smem[]` refers to here
 }
 } // namespace tt
 #include "conv.hip"

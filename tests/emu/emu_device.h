@@ -19,17 +19,21 @@
 struct EmuDim3 { unsigned x, y, z; };
 extern EmuDim3 threadIdx, blockIdx;
 
-inline void __syncthreads() {}
 inline uint32_t __float_as_uint(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
 inline float __uint_as_float(uint32_t u) { float f; std::memcpy(&f, &u, 4); return f; }
 inline int __popc(uint32_t v) { return __builtin_popcount(v); }
 
 #define __builtin_amdgcn_readfirstlane(x) (x)
-#define __builtin_amdgcn_s_waitcnt(x) ((void)0)
 #define __builtin_amdgcn_sched_barrier(x) ((void)0)
 #define __builtin_amdgcn_iglp_opt(x) ((void)0)
+#ifdef TT_EMU_LOCKSTEP
+#include "emu_lockstep.h"
+#else
+inline void __syncthreads() {}
+#define __builtin_amdgcn_s_waitcnt(x) ((void)0)
 #define __builtin_amdgcn_wave_barrier() ((void)0)
 #define __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, x, y, z) (c)
+#endif
 
 // ---- the little of the HIP host API that the launch code of a .hip file uses: a launch runs the kernel for every thread
 // of every workgroup in turn (no thread of the emulated kernels reads what another thread wrote)
@@ -44,8 +48,16 @@ inline hipError_t hipGetLastError() { return hipSuccess; }
 inline hipError_t hipFuncSetAttribute(const void *, hipFuncAttribute, int) { return hipSuccess; }
 enum hipDeviceAttribute_t { hipDeviceAttributeMultiprocessorCount = 63 };
 inline hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
-inline hipError_t hipDeviceGetAttribute(int *value, hipDeviceAttribute_t, int) { *value = 256; return hipSuccess; } // MI355X: 256 CUs
-#define __shared__
+inline hipError_t hipDeviceGetAttribute(int *value, hipDeviceAttribute_t, int)
+{
+    // MI355X: 256 CUs (EMU_CUS: a smaller device, so that small products give a persistent workgroup several tiles)
+    const char *e = std::getenv("EMU_CUS");
+    *value = e ? std::atoi(e) : 256;
+    return hipSuccess;
+}
+// LDS arrays: one copy for the whole process (one workgroup runs at a time), whether a kernel declares them inside its
+// body or as `extern __shared__ T name[]`, which the driver then defines with the same storage class
+#define __shared__ thread_local
 extern unsigned long long g_emu_threads_run;
 // kernels that declare `extern __shared__ T name[]`: the driver defines the array with g_emu_dyn_cap bytes and registers
 // it here; a launch then makes everything past the launch's dynamic size inaccessible to the address sanitizer
@@ -54,8 +66,13 @@ inline size_t g_emu_dyn_cap = 0;
 // ... several such arrays in one build (one name per kernel family): all of them, each of g_emu_dyn_cap bytes
 inline char *g_emu_dyn_all[4] = {nullptr, nullptr, nullptr, nullptr};
 inline int g_emu_dyn_n = 0;
+#ifdef TT_EMU_LOCKSTEP // built without the address sanitizer (it does not follow fibers): the explicit range checks remain
+inline void __asan_poison_memory_region(void const volatile *, size_t) {}
+inline void __asan_unpoison_memory_region(void const volatile *, size_t) {}
+#else
 extern "C" void __asan_poison_memory_region(void const volatile *addr, size_t size);
 extern "C" void __asan_unpoison_memory_region(void const volatile *addr, size_t size);
+#endif
 void emu_set_lds_limit(size_t dyn_bytes); // defined below, after tt::dev
 template <class F> inline void emu_launch(F &&body, dim3 grid, dim3 block, size_t dyn_bytes)
 {
@@ -71,13 +88,19 @@ template <class F> inline void emu_launch(F &&body, dim3 grid, dim3 block, size_
     }
     emu_set_lds_limit(dyn_bytes);
     for (unsigned by = 0; by < grid.y; ++by)
-        for (unsigned b = 0; b < grid.x; ++b)
+        for (unsigned b = 0; b < grid.x; ++b) {
+            blockIdx = {b, by, 0};
+#ifdef TT_EMU_LOCKSTEP
+            emu::run_block(body, block.x);
+            g_emu_threads_run += block.x;
+#else
             for (unsigned t = 0; t < block.x; ++t) {
-                blockIdx = {b, by, 0};
                 threadIdx = {t, 0, 0};
                 body();
                 ++g_emu_threads_run;
             }
+#endif
+        }
 }
 #define hipLaunchKernelGGL(kern, grid, block, smem, stream, ...) emu_launch([&]() { kern(__VA_ARGS__); }, grid, block, smem)
 
@@ -135,7 +158,13 @@ inline s16x4 lds_read_tr16_b64(const char *a)
 {
     if (a < g_lds || a + 8 > g_lds + g_lds_bytes) fail("LDS transpose read outside LDS", a, 8);
     s16x4 v;
+#ifdef TT_EMU_LOCKSTEP
+    std::memcpy(emu::my_wave().tr[emu::lane()], a, 8);
+    emu::transpose_groups_of_16();
+    std::memcpy(&v, emu::my_wave().tr[emu::lane()], 8);
+#else
     std::memcpy(&v, a, 8);
+#endif
     return v;
 }
 

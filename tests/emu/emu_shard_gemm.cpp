@@ -12,8 +12,8 @@
 namespace tt {
 namespace {
 // what the kernels' `extern __shared__` arrays refer to here (one name per kernel family)
-alignas(16) uint16_t smem[80 * 1024];
-alignas(16) char smem2[160 * 1024], smem3[160 * 1024], smem4[160 * 1024];
+alignas(16) thread_local uint16_t smem[80 * 1024];
+alignas(16) thread_local char smem2[160 * 1024], smem3[160 * 1024], smem4[160 * 1024];
 }
 } // namespace tt
 #include "gemm.hip"
@@ -33,12 +33,27 @@ ProfileScope::ProfileScope(void *, int, int, int64_t, int64_t, int64_t, uint64_t
 ProfileScope::~ProfileScope() {}
 } // namespace tt
 
+static bool read_file(const char *dir, const char *name, int s, std::vector<char> &into)
+{
+    char path[512];
+    std::snprintf(path, sizeof(path), "%s/%s%d.bin", dir, name, s);
+    FILE *f = std::fopen(path, "rb");
+    if (!f) return false;
+    const size_t got = std::fread(into.data(), 1, into.size(), f);
+    const bool at_end = std::fgetc(f) == EOF;
+    std::fclose(f);
+    return got == into.size() && at_end;
+}
+
 int main(int argc, char **argv)
 {
     // emu_shard_gemm count M N K trans_a trans_b in_bf16 out_bf16 relu ksplit
     // (ksplit 1: the exported entry point; above 1: the in-launch K split the layer-chain code asks launch_gemm for,
     // which writes count * ksplit partial products)
-    if (argc != 11) { std::fprintf(stderr, "usage: emu_shard_gemm count M N K trans_a trans_b in_bf16 out_bf16 relu ksplit\n"); return 64; }
+    // With a directory as one more argument (lock-step build): operands are read from a<s>.bin / b<s>.bin there and the
+    // results written to c<s>.bin, for the caller to compare with the oracle's.
+    if (argc != 11 && argc != 12) { std::fprintf(stderr, "usage: emu_shard_gemm count M N K trans_a trans_b in_bf16 out_bf16 relu ksplit [dir]\n"); return 64; }
+    const char *dir = argc == 12 ? argv[11] : nullptr;
     g_emu_dyn_all[0] = reinterpret_cast<char *>(tt::smem); g_emu_dyn_all[1] = tt::smem2; g_emu_dyn_all[2] = tt::smem3; g_emu_dyn_all[3] = tt::smem4;
     g_emu_dyn_n = 4;
     g_emu_dyn_cap = 160 * 1024;
@@ -56,6 +71,7 @@ int main(int argc, char **argv)
     for (int s = 0; s < count; ++s) {
         A[s].assign((size_t)M * K * ib, 0);
         B[s].assign((size_t)K * N * ib, 0);
+        if (dir && (!read_file(dir, "a", s, A[s]) || !read_file(dir, "b", s, B[s]))) { std::fprintf(stderr, "cannot read operand %d\n", s); return 65; }
         Ap.push_back(A[s].data()); Bp.push_back(B[s].data());
         tt::dev::g_readable[tt::dev::g_n_readable++] = {A[s].data(), A[s].data() + A[s].size()};
         tt::dev::g_readable[tt::dev::g_n_readable++] = {B[s].data(), B[s].data() + B[s].size()};
@@ -65,6 +81,17 @@ int main(int argc, char **argv)
     const tt_status st = ksplit == 1 ? tt_shard_gemm(count, Ap.data(), Bp.data(), Cp.data(), M, N, K, ta, tb, in_dt, out_dt, act, nullptr)
                                      : tt::launch_gemm(count, Ap.data(), Bp.data(), Cp.data(), M, N, K, ta, tb, in_dt, out_dt, act, ksplit, nullptr);
     if (st != TT_OK) { std::printf("status %d\n", (int)st); return 2; }
+    if (dir) {
+        for (size_t s = 0; s < C.size(); ++s) {
+            char path[512];
+            std::snprintf(path, sizeof(path), "%s/c%zu.bin", dir, s);
+            FILE *f = std::fopen(path, "wb");
+            if (!f || std::fwrite(C[s].data(), 1, C[s].size(), f) != C[s].size()) { std::fprintf(stderr, "cannot write %s\n", path); return 66; }
+            std::fclose(f);
+        }
+        std::printf("ok shard_gemm values: %llu threads run\n", g_emu_threads_run);
+        return 0;
+    }
     for (size_t s = 0; s < C.size(); ++s)
         for (size_t i = 0; i < C[s].size(); ++i)
             if (C[s][i] != 0) { std::printf("output %zu byte %zu never written\n", s, i); return 1; }

@@ -1,0 +1,135 @@
+"""The shard-product kernels run on the host in lock step (tests/emu/emu_lockstep.h: the threads of a workgroup as
+cooperative fibers, barriers that hold, MFMA and the LDS transpose read computing what the instructions compute) and
+their results compared with the oracle's, to the bar of the GPU tests.  The entry point is the library's own
+(csrc/gemm.hip and csrc/gemm3.hip compiled for the host as they are), so every engine is reached the way the library
+reaches it.  What this cannot show is what only the hardware decides (timing, instruction alignment rules); what it does
+show without a GPU: tile and fragment indexing, LDS layouts, K tails, write-out, the K split inside a launch.
+"""
+import os
+import shutil
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import layers as ly
+from synthetic import bf16_bits_to_f64, normal_f32, to_bf16_bits
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CLANG = shutil.which("clang++", path="/opt/rocm/llvm/bin") or shutil.which("clang++")
+pytestmark = pytest.mark.skipif(CLANG is None, reason="no host clang++ for the emulation build")
+
+
+@pytest.fixture(scope="module")
+def lockstep_gemm(tmp_path_factory):
+    exe = str(tmp_path_factory.mktemp("emu") / "emu_shard_gemm_lockstep")
+    cmd = [CLANG, "-std=c++17", "-O0", "-DTT_EMU_LOCKSTEP", "-x", "c++", "-I" + os.path.join(ROOT, "tests", "emu"),
+           "-I" + os.path.join(ROOT, "paper_1805_04170_amd", "csrc"), "-I" + os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "emu", "emu_shard_gemm.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    return exe
+
+
+def check(exe, tmp, count, M, N, K, ta, tb, in_dt, out_dt, relu, seed, ksplit=1, env=None):
+    bf = in_dt == "bf16"
+    want, mags = [], []
+    for s in range(count):
+        a = normal_f32(seed, 2 * s, (M, K), 1.0)
+        b = normal_f32(seed, 2 * s + 1, (K, N), 0.05)
+        if bf:
+            a, b = to_bf16_bits(a), to_bf16_bits(b)
+        af = bf16_bits_to_f64(a) if bf else a.astype(np.float64)
+        bfl = bf16_bits_to_f64(b) if bf else b.astype(np.float64)
+        z = af @ bfl
+        want.append(np.maximum(z, 0) if relu else z)
+        mags.append(ly.abs_product(af, bfl))
+        np.ascontiguousarray(a.T if ta else a).tofile(os.path.join(tmp, "a%d.bin" % s))
+        np.ascontiguousarray(b.T if tb else b).tofile(os.path.join(tmp, "b%d.bin" % s))
+    e = dict(os.environ)
+    e.update(env or {})
+    r = subprocess.run([exe] + [str(v) for v in (count, M, N, K, ta, tb, int(bf), int(out_dt == "bf16"), int(relu), ksplit, tmp)],
+                       capture_output=True, text=True, env=e)
+    assert r.returncode == 0, r.stdout[-400:] + r.stderr[-1500:]
+    for s in range(count):
+        # with a K split the launch leaves ksplit partial products per shard, to be summed
+        gf = np.zeros((M, N))
+        for q in range(ksplit):
+            raw = np.fromfile(os.path.join(tmp, "c%d.bin" % (s * ksplit + q)), dtype=np.uint16 if out_dt == "bf16" else np.float32)
+            gf += (bf16_bits_to_f64(raw) if out_dt == "bf16" else raw.astype(np.float64)).reshape(M, N)
+        tol = (1e-2 if bf else 1e-5) * mags[s]
+        if out_dt == "bf16":
+            tol = tol + ksplit * 2.0 ** -8 * np.abs(want[s])
+        err = np.abs(gf - want[s])
+        assert np.all(np.isfinite(gf)), (s, "non-finite output")
+        assert np.all(err <= tol + 1e-30), (s, float(err.max()), float((err / (tol + 1e-30)).max()), np.argwhere(err > tol + 1e-30)[:5])
+        if bf and out_dt == "f32" and not relu:
+            assert float(np.max(err / (mags[s] + 1e-30))) < 1e-4
+    return r.stdout
+
+
+LAYOUTS = [(0, 0), (0, 1), (1, 0), (1, 1)]
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_register_staged_engine_values(lockstep_gemm, tmp_path, ta, tb):
+    check(lockstep_gemm, str(tmp_path), 2, 264, 200, 104, ta, tb, "bf16", "bf16", False, 31)   # ragged on every side, K mask
+    check(lockstep_gemm, str(tmp_path), 1, 136, 72, 64, ta, tb, "bf16", "f32", True, 32)
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+@pytest.mark.parametrize("out_dt", ["bf16", "f32"])
+def test_two_workgroups_per_cu_engine_values(lockstep_gemm, tmp_path, ta, tb, out_dt):
+    # few 256 x 256 tiles: the 256 x 128 engine; ragged M and N, a K loop shorter than its ring and a longer one
+    out = check(lockstep_gemm, str(tmp_path), 1, 264, 392, 96, ta, tb, "bf16", out_dt, True, 45)
+    assert int(out.split()[3]) == 8 * 256      # 2 x 4 tiles of 256 x 128, 256 threads each
+    check(lockstep_gemm, str(tmp_path), 2, 136, 264, 32, ta, tb, "bf16", out_dt, False, 47)
+    check(lockstep_gemm, str(tmp_path), 1, 256, 256, 256, ta, tb, "bf16", out_dt, False, 46)
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+@pytest.mark.parametrize("out_dt", ["bf16", "f32"])
+def test_persistent_engine_values(lockstep_gemm, tmp_path, ta, tb, out_dt):
+    # on a stand-in device of 16 CUs, with the engine and tile forced the way the tuning switches allow: 24 ragged
+    # tiles, one or two per workgroup (the operand ring runs across tile boundaries), K loops of one and three tiles
+    env = {"EMU_CUS": "16", "TT_GEMM_ENGINE": "3", "TT_GEMM_TILE": "5"}
+    out = check(lockstep_gemm, str(tmp_path), 2, 520, 776, 64, ta, tb, "bf16", out_dt, True, 42, env=env)
+    assert int(out.split()[3]) == 16 * 512
+    check(lockstep_gemm, str(tmp_path), 1, 264, 520, 192, ta, tb, "bf16", out_dt, False, 44, env=env)
+
+
+def test_persistent_engine_values_as_the_library_chooses_it(lockstep_gemm, tmp_path):
+    # 240 tiles on 256 CUs: the weight-gradient layout, bf16 results (loads interleaved with the K steps)
+    out = check(lockstep_gemm, str(tmp_path), 8, 1288, 1272, 64, 1, 0, "bf16", "bf16", False, 43)
+    assert int(out.split()[3]) == 240 * 512
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_direct_to_lds_engine_values(lockstep_gemm, tmp_path, ta, tb):
+    # the eight-wave 256 x 256 engine that loads tiles straight into LDS, forced by the tuning switches on small
+    # products: ragged M and N, a K tail that is no multiple of the tile depth
+    env = {"TT_GEMM_ENGINE": "1", "TT_GEMM_TILE": "8"}
+    out = check(lockstep_gemm, str(tmp_path), 2, 264, 520, 72, ta, tb, "bf16", "bf16", True, 39, env=env)
+    assert int(out.split()[3]) == 16 * 512     # 12 tiles, rounded up to a multiple of the 8 XCDs
+    check(lockstep_gemm, str(tmp_path), 1, 256, 264, 128, ta, tb, "bf16", "f32", False, 40, env=env)
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5])
+def test_register_staged_engine_every_tile_values(lockstep_gemm, tmp_path, tile):
+    env = {"TT_GEMM_ENGINE": "1", "TT_GEMM_TILE": str(tile)}
+    check(lockstep_gemm, str(tmp_path), 1, 264, 392, 104, 0, 0, "bf16", "bf16", False, 50 + tile, env=env)
+    check(lockstep_gemm, str(tmp_path), 1, 264, 392, 96, 1, 1, "bf16", "f32", True, 60 + tile, env=env)
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_k_split_inside_a_launch_values(lockstep_gemm, tmp_path, ta, tb):
+    # the partial products of the chunks add up to the product (chunks of 128, 128 and 64 of K = 320; on the smallest tile
+    # chunks of 64, 64 and 22 of K = 150 would leave ... K must keep 16-byte rows: 152)
+    check(lockstep_gemm, str(tmp_path), 2, 264, 264, 320, ta, tb, "bf16", "f32", False, 70, ksplit=3)
+    check(lockstep_gemm, str(tmp_path), 1, 40, 72, 152, ta, tb, "bf16", "f32", False, 71, ksplit=3)
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_generic_kernel_values(lockstep_gemm, tmp_path, ta, tb):
+    check(lockstep_gemm, str(tmp_path), 2, 70, 130, 65, ta, tb, "f32", "f32", True, 38)
+    check(lockstep_gemm, str(tmp_path), 2, 37, 125, 50, ta, tb, "bf16", "bf16", True, 35)       # rows without 16-byte vectors
+    check(lockstep_gemm, str(tmp_path), 1, 33, 10, 17, ta, tb, "bf16", "f32", False, 36, ksplit=1)
