@@ -28,3 +28,12 @@ def golden(name):
 @pytest.fixture(scope="session")
 def golden_loader():
     return golden
+
+
+@pytest.fixture(scope="session")
+def emulators(tmp_path_factory):
+    """the host emulation programs of tests/emu, built together on first use (tests/emu_build.py)"""
+    import emu_build
+    if emu_build.CLANG is None:
+        pytest.skip("no host clang++ for the emulation build")
+    return emu_build.Emulators(tmp_path_factory.mktemp("emu"))

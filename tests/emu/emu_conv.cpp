@@ -15,24 +15,14 @@ alignas(16) thread_local uint16_t smem[96 * 1024]; // what the kernels' `extern 
 } // namespace tt
 #include "conv.hip"
 
-EmuDim3 threadIdx, blockIdx;
-unsigned long long g_emu_threads_run = 0;
 namespace tt {
-namespace dev {
-char *g_lds = nullptr;
-size_t g_lds_bytes = 0;
-Region g_readable[192];
-int g_n_readable = 0;
-unsigned long long g_dma_bytes = 0;
-} // namespace dev
 ProfileScope::ProfileScope(void *, int, int, int64_t, int64_t, int64_t, uint64_t, uint64_t) : slot(-1), stream(nullptr) {}
 ProfileScope::~ProfileScope() {}
 } // namespace tt
 
 int main(int argc, char **argv)
 {
-    g_emu_dyn_lds = reinterpret_cast<char *>(tt::smem);
-    g_emu_dyn_cap = sizeof(tt::smem);
+    emu_register_lds(tt::smem, sizeof(tt::smem));
     // emu_conv op count Ns Cs Ks H W R S pad out_bf16 relu flip
     if (argc != 14) { std::fprintf(stderr, "usage: emu_conv op count Ns Cs Ks H W R S pad out_bf16 relu flip\n"); return 64; }
     const int op = std::atoi(argv[1]), count = std::atoi(argv[2]);

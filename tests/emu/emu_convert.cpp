@@ -13,16 +13,7 @@
 #define TT_HOST_EMULATION 1
 #include "convert.hip"
 
-EmuDim3 threadIdx, blockIdx;
-unsigned long long g_emu_threads_run = 0;
 namespace tt {
-namespace dev {
-char *g_lds = nullptr;
-size_t g_lds_bytes = 0;
-Region g_readable[192];
-int g_n_readable = 0;
-unsigned long long g_dma_bytes = 0;
-} // namespace dev
 // measurement hooks: nothing to record here
 ProfileScope::ProfileScope(void *, int, int, int64_t, int64_t, int64_t, uint64_t, uint64_t) : slot(-1), stream(nullptr) {}
 ProfileScope::~ProfileScope() {}

@@ -17,7 +17,7 @@
 #define __launch_bounds__(...)
 
 struct EmuDim3 { unsigned x, y, z; };
-extern EmuDim3 threadIdx, blockIdx;
+inline EmuDim3 threadIdx, blockIdx;
 
 inline uint32_t __float_as_uint(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
 inline float __uint_as_float(uint32_t u) { float f; std::memcpy(&f, &u, 4); return f; }
@@ -46,6 +46,16 @@ enum hipError_t { hipSuccess = 0 };
 enum hipFuncAttribute { hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
 inline hipError_t hipGetLastError() { return hipSuccess; }
 inline hipError_t hipFuncSetAttribute(const void *, hipFuncAttribute, int) { return hipSuccess; }
+// streams and events: everything here runs at once and in order
+typedef void *hipEvent_t;
+enum { hipEventDisableTiming = 2 };
+inline hipError_t hipEventCreate(hipEvent_t *e) { *e = reinterpret_cast<hipEvent_t>(1); return hipSuccess; }
+inline hipError_t hipEventCreateWithFlags(hipEvent_t *e, unsigned) { *e = reinterpret_cast<hipEvent_t>(1); return hipSuccess; }
+inline hipError_t hipEventDestroy(hipEvent_t) { return hipSuccess; }
+inline hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }
+inline hipError_t hipEventSynchronize(hipEvent_t) { return hipSuccess; }
+inline hipError_t hipEventElapsedTime(float *ms, hipEvent_t, hipEvent_t) { *ms = 0.0f; return hipSuccess; }
+inline hipError_t hipStreamWaitEvent(hipStream_t, hipEvent_t, unsigned) { return hipSuccess; }
 enum hipDeviceAttribute_t { hipDeviceAttributeMultiprocessorCount = 63 };
 inline hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
 inline hipError_t hipDeviceGetAttribute(int *value, hipDeviceAttribute_t, int)
@@ -58,14 +68,18 @@ inline hipError_t hipDeviceGetAttribute(int *value, hipDeviceAttribute_t, int)
 // LDS arrays: one copy for the whole process (one workgroup runs at a time), whether a kernel declares them inside its
 // body or as `extern __shared__ T name[]`, which the driver then defines with the same storage class
 #define __shared__ thread_local
-extern unsigned long long g_emu_threads_run;
-// kernels that declare `extern __shared__ T name[]`: the driver defines the array with g_emu_dyn_cap bytes and registers
-// it here; a launch then makes everything past the launch's dynamic size inaccessible to the address sanitizer
-inline char *g_emu_dyn_lds = nullptr;
-inline size_t g_emu_dyn_cap = 0;
-// ... several such arrays in one build (one name per kernel family): all of them, each of g_emu_dyn_cap bytes
-inline char *g_emu_dyn_all[4] = {nullptr, nullptr, nullptr, nullptr};
-inline int g_emu_dyn_n = 0;
+inline unsigned long long g_emu_threads_run = 0;
+// kernels that declare `extern __shared__ T name[]`: whoever defines the array registers it here; a launch then makes
+// everything past its dynamic size inaccessible to the address sanitizer (several arrays: one name per kernel family)
+struct EmuLds { char *base; size_t cap; };
+inline EmuLds g_emu_lds[8];
+inline int g_emu_lds_n = 0;
+inline int emu_register_lds(void *base, size_t cap)
+{
+    if (g_emu_lds_n == 8) { std::fprintf(stderr, "EMU: too many LDS arrays\n"); std::abort(); }
+    g_emu_lds[g_emu_lds_n++] = {static_cast<char *>(base), cap};
+    return g_emu_lds_n;
+}
 #ifdef TT_EMU_LOCKSTEP // built without the address sanitizer (it does not follow fibers): the explicit range checks remain
 inline void __asan_poison_memory_region(void const volatile *, size_t) {}
 inline void __asan_unpoison_memory_region(void const volatile *, size_t) {}
@@ -76,15 +90,10 @@ extern "C" void __asan_unpoison_memory_region(void const volatile *addr, size_t 
 void emu_set_lds_limit(size_t dyn_bytes); // defined below, after tt::dev
 template <class F> inline void emu_launch(F &&body, dim3 grid, dim3 block, size_t dyn_bytes)
 {
-    if (g_emu_dyn_lds) {
-        if (dyn_bytes > g_emu_dyn_cap) { std::fprintf(stderr, "EMU FAULT: launch asks for %zu bytes of LDS\n", dyn_bytes); std::abort(); }
-        __asan_unpoison_memory_region(g_emu_dyn_lds, g_emu_dyn_cap);
-        __asan_poison_memory_region(g_emu_dyn_lds + dyn_bytes, g_emu_dyn_cap - dyn_bytes);
-    }
-    for (int i = 0; i < g_emu_dyn_n; ++i) {
-        if (dyn_bytes > g_emu_dyn_cap) { std::fprintf(stderr, "EMU FAULT: launch asks for %zu bytes of LDS\n", dyn_bytes); std::abort(); }
-        __asan_unpoison_memory_region(g_emu_dyn_all[i], g_emu_dyn_cap);
-        __asan_poison_memory_region(g_emu_dyn_all[i] + dyn_bytes, g_emu_dyn_cap - dyn_bytes);
+    for (int i = 0; i < g_emu_lds_n; ++i) {
+        if (dyn_bytes > g_emu_lds[i].cap) { std::fprintf(stderr, "EMU FAULT: launch asks for %zu bytes of LDS\n", dyn_bytes); std::abort(); }
+        __asan_unpoison_memory_region(g_emu_lds[i].base, g_emu_lds[i].cap);
+        __asan_poison_memory_region(g_emu_lds[i].base + dyn_bytes, g_emu_lds[i].cap - dyn_bytes);
     }
     emu_set_lds_limit(dyn_bytes);
     for (unsigned by = 0; by < grid.y; ++by)
@@ -110,11 +119,11 @@ namespace dev {
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 struct Region { const char *lo, *hi; };
-extern char *g_lds;              // the workgroup's LDS
-extern size_t g_lds_bytes;
-extern Region g_readable[192];   // operand buffers of the launch
-extern int g_n_readable;
-extern unsigned long long g_dma_bytes;
+inline char *g_lds = nullptr;    // the workgroup's LDS
+inline size_t g_lds_bytes = 0;
+inline Region g_readable[192];   // operand buffers of the launch (none registered: reads are not range-checked here)
+inline int g_n_readable = 0;
+inline unsigned long long g_dma_bytes = 0;
 
 [[noreturn]] inline void fail(const char *what, const void *addr, size_t n)
 {
@@ -125,14 +134,15 @@ extern unsigned long long g_dma_bytes;
 inline uint32_t lds_addr(char *p)
 {
     // with several named LDS arrays in the build: the one the pointer lies in is this kernel's LDS
-    for (int i = 0; i < g_emu_dyn_n; ++i)
-        if (p >= g_emu_dyn_all[i] && p <= g_emu_dyn_all[i] + g_emu_dyn_cap) g_lds = g_emu_dyn_all[i];
+    for (int i = 0; i < g_emu_lds_n; ++i)
+        if (p >= g_emu_lds[i].base && p <= g_emu_lds[i].base + g_emu_lds[i].cap) g_lds = g_emu_lds[i].base;
     if (p < g_lds || p > g_lds + g_lds_bytes) fail("pointer outside LDS", p, 0);
     return (uint32_t)(p - g_lds);
 }
 
 inline void check_read(const char *g, size_t n)
 {
+    if (g_n_readable == 0) return;
     for (int i = 0; i < g_n_readable; ++i)
         if (g >= g_readable[i].lo && g + n <= g_readable[i].hi) return;
     fail("global read outside every operand", g, n);
@@ -173,6 +183,6 @@ inline s16x4 lds_read_tr16_b64(const char *a)
 
 inline void emu_set_lds_limit(size_t dyn_bytes)
 {
-    if (g_emu_dyn_n > 0) tt::dev::g_lds_bytes = dyn_bytes;
+    if (g_emu_lds_n > 0) tt::dev::g_lds_bytes = dyn_bytes;
 }
 

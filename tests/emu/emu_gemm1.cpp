@@ -11,15 +11,7 @@
 #include "gemm_core.h"
 #include "tt_internal.h"
 
-EmuDim3 threadIdx, blockIdx;
 namespace tt {
-namespace dev {
-char *g_lds = nullptr;
-size_t g_lds_bytes = 0;
-Region g_readable[192];
-int g_n_readable = 0;
-unsigned long long g_dma_bytes = 0;
-} // namespace dev
 } // namespace tt
 
 using namespace tt;

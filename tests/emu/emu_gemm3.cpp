@@ -12,15 +12,7 @@
 #define TT_HOST_EMULATION 1
 #include "gemm3_params.h"
 
-EmuDim3 threadIdx, blockIdx;
 namespace tt {
-namespace dev {
-char *g_lds = nullptr;
-size_t g_lds_bytes = 0;
-Region g_readable[192];
-int g_n_readable = 0;
-unsigned long long g_dma_bytes = 0;
-} // namespace dev
 } // namespace tt
 
 using namespace tt;

@@ -19,16 +19,7 @@ alignas(16) thread_local char smem2[160 * 1024], smem3[160 * 1024], smem4[160 * 
 #include "gemm.hip"
 #include "gemm3.hip"
 
-EmuDim3 threadIdx, blockIdx;
-unsigned long long g_emu_threads_run = 0;
 namespace tt {
-namespace dev {
-char *g_lds = reinterpret_cast<char *>(tt::smem);
-size_t g_lds_bytes = 0;
-Region g_readable[192];
-int g_n_readable = 0;
-unsigned long long g_dma_bytes = 0;
-} // namespace dev
 ProfileScope::ProfileScope(void *, int, int, int64_t, int64_t, int64_t, uint64_t, uint64_t) : slot(-1), stream(nullptr) {}
 ProfileScope::~ProfileScope() {}
 } // namespace tt
@@ -54,9 +45,10 @@ int main(int argc, char **argv)
     // results written to c<s>.bin, for the caller to compare with the oracle's.
     if (argc != 11 && argc != 12) { std::fprintf(stderr, "usage: emu_shard_gemm count M N K trans_a trans_b in_bf16 out_bf16 relu ksplit [dir]\n"); return 64; }
     const char *dir = argc == 12 ? argv[11] : nullptr;
-    g_emu_dyn_all[0] = reinterpret_cast<char *>(tt::smem); g_emu_dyn_all[1] = tt::smem2; g_emu_dyn_all[2] = tt::smem3; g_emu_dyn_all[3] = tt::smem4;
-    g_emu_dyn_n = 4;
-    g_emu_dyn_cap = 160 * 1024;
+    emu_register_lds(tt::smem, sizeof(tt::smem));
+    emu_register_lds(tt::smem2, sizeof(tt::smem2));
+    emu_register_lds(tt::smem3, sizeof(tt::smem3));
+    emu_register_lds(tt::smem4, sizeof(tt::smem4));
     const int count = std::atoi(argv[1]);
     const long M = std::atol(argv[2]), N = std::atol(argv[3]), K = std::atol(argv[4]);
     const int ta = std::atoi(argv[5]), tb = std::atoi(argv[6]), in_bf = std::atoi(argv[7]), out_bf = std::atoi(argv[8]), relu = std::atoi(argv[9]);

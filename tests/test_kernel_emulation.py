@@ -14,13 +14,8 @@ pytestmark = pytest.mark.skipif(CLANG is None, reason="no host clang++ for the e
 
 
 @pytest.fixture(scope="module")
-def emu(tmp_path_factory):
-    exe = str(tmp_path_factory.mktemp("emu") / "emu_gemm3")
-    cmd = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address", "-I" + os.path.join(ROOT, "tests", "emu"),
-           "-I" + os.path.join(ROOT, "paper_1805_04170_amd", "csrc"), "-I" + os.path.join(ROOT, "include"),
-           os.path.join(ROOT, "tests", "emu", "emu_gemm3.cpp"), "-o", exe]
-    subprocess.run(cmd, check=True, capture_output=True, text=True)
-    return exe
+def emu(emulators):
+    return emulators.get("gemm3")
 
 
 def run(exe, case, env=None):
@@ -35,7 +30,7 @@ CASES = [
     (3, 8, 1032, 1544, 64, 1, 1, 0, 0, 1),
     (3, 3, 2056, 1800, 320, 0, 1, 1, 0, 1),
     (3, 8, 2056, 2312, 256, 0, 0, 1, 1, 1),
-    (3, 8, 3136, 4096, 256, 0, 0, 1, 0, 1),     # the weight gradient of the VGG-16 first classifier layer (benchmark shape)
+    # (the weight gradient of the VGG-16 first classifier layer, 8 x 3136 x 4096 x 256, runs below through tt_shard_gemm)
     (3, 8, 256, 4096, 3136, 1, 0, 0, 0, 2),     # its forward product with the in-shard K split, fp32 partial sums
     (3, 16, 512, 2048, 2048, 1, 1, 1, 0, 1),    # wide MLP shard product
     (3, 2, 520, 776, 64, 0, 0, 1, 0, 1),
@@ -87,13 +82,9 @@ CASES1 = [
 
 
 @pytest.mark.parametrize("cfg,case", CASES1, ids=lambda v: "x".join(str(i) for i in v))
-def test_register_staged_engine_stays_inside_its_buffers(tmp_path, cfg, case):
-    names = ["E1_BM", "E1_BN", "E1_WM", "E1_WN", "E1_DEPTH", "E1_KMASK", "E1_AKC", "E1_BKC", "E1_BF16", "E1_VEC"]
-    exe = str(tmp_path / "emu_gemm1")
-    cmd = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address"] + ["-D%s=%d" % (n, v) for n, v in zip(names, cfg)] + [
-        "-I" + os.path.join(ROOT, "tests", "emu"), "-I" + os.path.join(ROOT, "paper_1805_04170_amd", "csrc"),
-        "-I" + os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "emu", "emu_gemm1.cpp"), "-o", exe]
-    subprocess.run(cmd, check=True, capture_output=True, text=True)
+def test_register_staged_engine_stays_inside_its_buffers(emulators, cfg, case):
+    emulators.prefetch([("gemm1", c) for c, _ in CASES1])
+    exe = emulators.get(("gemm1", cfg))
     r = run(exe, case)
     assert r.returncode == 0, r.stdout[-400:] + r.stderr[-1200:]
 
@@ -112,13 +103,8 @@ from synthetic import bf16_bits_to_f32, to_bf16_bits
 
 
 @pytest.fixture(scope="module")
-def emu_convert(tmp_path_factory):
-    exe = str(tmp_path_factory.mktemp("emu") / "emu_convert")
-    cmd = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address", "-x", "c++", "-I" + os.path.join(ROOT, "tests", "emu"),
-           "-I" + os.path.join(ROOT, "paper_1805_04170_amd", "csrc"), "-I" + os.path.join(ROOT, "include"),
-           os.path.join(ROOT, "tests", "emu", "emu_convert.cpp"), "-o", exe]
-    subprocess.run(cmd, check=True, capture_output=True, text=True)
-    return exe
+def emu_convert(emulators):
+    return emulators.get("convert")
 
 
 def _dump(d, stem, shards):
@@ -202,13 +188,8 @@ def test_gated_retile_and_reduce_on_the_host(emu_convert, tmp_path):
 # ---- the convolution kernels with their launch code (tile choice, grids, the filter flip in front of the data gradient)
 
 @pytest.fixture(scope="module")
-def emu_conv(tmp_path_factory):
-    exe = str(tmp_path_factory.mktemp("emu") / "emu_conv")
-    cmd = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address", "-x", "c++", "-I" + os.path.join(ROOT, "tests", "emu"),
-           "-I" + os.path.join(ROOT, "paper_1805_04170_amd", "csrc"), "-I" + os.path.join(ROOT, "include"),
-           os.path.join(ROOT, "tests", "emu", "emu_conv.cpp"), "-o", exe]
-    subprocess.run(cmd, check=True, capture_output=True, text=True)
-    return exe
+def emu_conv(emulators):
+    return emulators.get("conv")
 
 
 # op (0 forward, 1 data gradient, 2 filter gradient), shards, images, in-channels, out-channels per shard, H, W, R, S, pad,
@@ -240,14 +221,8 @@ def test_convolution_launches_stay_inside_their_buffers(emu_conv, case):
 # ---- code as in the library, on a device with 256 compute units
 
 @pytest.fixture(scope="module")
-def emu_shard_gemm(tmp_path_factory):
-    exe = str(tmp_path_factory.mktemp("emu") / "emu_shard_gemm")
-    # unoptimised: the optimiser needs minutes for the four engines' instantiations under the sanitizer
-    cmd = [CLANG, "-std=c++17", "-O0", "-fsanitize=address", "-x", "c++", "-I" + os.path.join(ROOT, "tests", "emu"),
-           "-I" + os.path.join(ROOT, "paper_1805_04170_amd", "csrc"), "-I" + os.path.join(ROOT, "include"),
-           os.path.join(ROOT, "tests", "emu", "emu_shard_gemm.cpp"), "-o", exe]
-    subprocess.run(cmd, check=True, capture_output=True, text=True)
-    return exe
+def emu_shard_gemm(emulators):
+    return emulators.get("shard_gemm")
 
 
 # shards, M, N, K, A transposed, B transposed, bf16 operands, bf16 result, relu, K split inside the launch;

@@ -21,13 +21,8 @@ pytestmark = pytest.mark.skipif(CLANG is None, reason="no host clang++ for the e
 
 
 @pytest.fixture(scope="module")
-def lockstep_gemm(tmp_path_factory):
-    exe = str(tmp_path_factory.mktemp("emu") / "emu_shard_gemm_lockstep")
-    cmd = [CLANG, "-std=c++17", "-O0", "-DTT_EMU_LOCKSTEP", "-x", "c++", "-I" + os.path.join(ROOT, "tests", "emu"),
-           "-I" + os.path.join(ROOT, "paper_1805_04170_amd", "csrc"), "-I" + os.path.join(ROOT, "include"),
-           os.path.join(ROOT, "tests", "emu", "emu_shard_gemm.cpp"), "-o", exe]
-    subprocess.run(cmd, check=True, capture_output=True, text=True)
-    return exe
+def lockstep_gemm(emulators):
+    return emulators.get("shard_gemm_lockstep")
 
 
 def check(exe, tmp, count, M, N, K, ta, tb, in_dt, out_dt, relu, seed, ksplit=1, env=None):

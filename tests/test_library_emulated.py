@@ -1,0 +1,140 @@
+"""The whole library built for the host and run in lock step (tests/emu): every source file of the library as it is,
+kernels included (tests/emu/emu_lockstep.h says how threads, barriers and the wave-wide instructions are stood in for),
+loaded in place of the HIP build for the duration of a test.  The checks are the GPU parity tests' own functions, called
+on host tensors at sizes the emulation finishes in seconds: the execute calls (planning of conversions, workspace
+layout, launches, reductions) and the kernels produce, on the host, what the oracle says.  This is a test of the
+product's sources; the product itself never loads this build.
+"""
+import ctypes
+import os
+import shutil
+import subprocess
+
+import numpy as np
+import pytest
+import torch
+
+import paper_1805_04170_amd.binding as binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CLANG = shutil.which("clang++", path="/opt/rocm/llvm/bin") or shutil.which("clang++")
+pytestmark = pytest.mark.skipif(CLANG is None, reason="no host clang++ for the emulation build")
+
+
+@pytest.fixture(scope="module")
+def emulated_library(emulators):
+    return emulators.get("library")
+
+
+@pytest.fixture
+def on_host(emulated_library, monkeypatch):
+    """the binding and the GPU tests' helpers pointed at the emulated library and at host tensors"""
+    import gpu_util
+    import test_gpu_conv
+    import test_gpu_convert
+    import test_gpu_fc
+    import test_gpu_gemm
+    monkeypatch.setattr(binding, "LIB_PATH", emulated_library)
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_stream", lambda stream: ctypes.c_void_p(0))
+    monkeypatch.setattr(torch.cuda, "synchronize", lambda *a, **k: None)
+    for m in (gpu_util, test_gpu_fc, test_gpu_conv, test_gpu_convert, test_gpu_gemm):
+        if hasattr(m, "DEV"):
+            monkeypatch.setattr(m, "DEV", "cpu")
+
+    def aligned_workspace(nbytes):      # device allocations are 256-byte aligned, which the library asks of a workspace
+        n = max(int(nbytes), 256)
+        raw = torch.empty(n + 256, dtype=torch.uint8)
+        return raw[(-raw.data_ptr()) % 256:][:n]
+
+    monkeypatch.setattr(test_gpu_fc, "workspace", aligned_workspace)
+    monkeypatch.setattr(test_gpu_conv, "ws", aligned_workspace)
+    return dict(fc=test_gpu_fc, conv=test_gpu_conv, convert=test_gpu_convert, gemm=test_gpu_gemm)
+
+
+def test_every_declared_symbol_is_exported_by_the_host_build(emulated_library):
+    L = ctypes.CDLL(emulated_library)
+    for name in binding.EXPORTS:
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_fc_layer_named_tilings(on_host, golden_loader, dt):
+    g = golden_loader("paper_tilings.txt")
+    for name in ["T_data", "T_model", "T_hybrid"]:
+        tW, tA, tG = g[name]
+        k = len(tW)
+        on_host["fc"].run_layer(32, 64, 48, k, dt, True, tA, tW, tA, tG, tG, None, None, None, 50 + k)
+
+
+# ---- the GPU parity tests themselves, run on the host where their sizes allow
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_fc_every_form_sequence_two_cuts(on_host, relu):
+    on_host["fc"].test_every_form_sequence_two_cuts(relu)
+
+
+def test_fc_random_stored_tilings(on_host):
+    on_host["fc"].test_random_stored_tilings_default_forms()
+
+
+def test_fc_three_cuts_ragged_width_and_skip_dx(on_host):
+    on_host["fc"].test_three_cuts_ragged_width_and_skip_dx()
+
+
+def test_fc_refusals(on_host):
+    on_host["fc"].test_uneven_and_bad_workspace_are_refused()
+
+
+def test_fc_tiny_mlp_planned_and_recursive(on_host):
+    on_host["fc"].test_config_tiny_mlp_fp32_planned_and_recursive()
+
+
+def test_conv_single_shard_and_one_cut(on_host):
+    on_host["conv"].test_single_shard_and_one_cut()
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_conv_every_form_sequence_two_cuts(on_host, relu):
+    on_host["conv"].test_every_form_sequence_two_cuts(relu)
+
+
+def test_conv_random_stored_tilings(on_host):
+    on_host["conv"].test_random_stored_tilings_default_forms()
+
+
+def test_conv_other_filter_shapes(on_host):
+    on_host["conv"].test_other_filter_shapes()
+
+
+def test_conv_refusals(on_host):
+    on_host["conv"].test_refusals()
+
+
+@pytest.mark.parametrize("e", [1, 2, 4, 8])
+def test_retile_all_pairs_two_cuts(on_host, e):
+    on_host["convert"].test_retile_all_pairs_two_cuts(e)
+
+
+def test_retile_ragged_deep_and_gated(on_host):
+    c = on_host["convert"]
+    c.test_retile_three_cuts_ragged_shapes()
+    c.test_retile_k0_k4_and_roundtrip()
+    c.test_retile_six_cuts()
+    c.test_gated_retile("bf16")
+    c.test_gated_retile("f32")
+
+
+def test_reduce(on_host):
+    c = on_host["convert"]
+    c.test_reduce_ragged_columns_scalar_path()
+    for forms, B, out, relu in [("3", "r", "f32", False), ("33", "RR", "bf16", True), ("13", "CR", "f32", True), ("32", "rC", "bf16", False),
+                                ("333", "RRR", "bf16", False), ("231", "rCr", "f32", False), ("3333", "RRCC", "f32", False)]:
+        c.test_reduce_against_oracle(forms, B, out, relu)
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_shard_products_small(on_host, ta, tb):
+    g = on_host["gemm"]
+    g.test_bf16_unaligned_falls_back(ta, tb)
+    g.test_fp32(ta, tb)
