@@ -26,6 +26,8 @@ GEMM1_NAMES = ["E1_BM", "E1_BN", "E1_WM", "E1_WN", "E1_DEPTH", "E1_KMASK", "E1_A
 LIBRARY_UNITS = [os.path.join(EMU, f) for f in ("emu_lib_gemm.cpp", "emu_lib_conv.cpp", "emu_lib_convert.cpp")] + \
                 [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".cpp")]
 LIBRARY_FLAGS = ["-O0", "-fPIC", "-DTT_EMU_LOCKSTEP", "-DTT_HOST_EMULATION"]
+# the same units in address mode under the sanitizer, linked with the driver of a whole training step
+STEP_FLAGS = {"emu_lib_conv.cpp": ["-O1"], "emu_lib_convert.cpp": ["-O1"]}      # the rest -O0
 
 
 def _run(cmd):
@@ -42,6 +44,7 @@ class Emulators:
         for name in PROGRAMS:
             self._submit(name)
         self._submit("library")
+        self._submit("step")
 
     def _submit(self, name):
         if name in self.jobs:
@@ -58,6 +61,20 @@ class Emulators:
                 _run([CLANG, "-shared", "-o", so] + objs)
                 return so
             self.jobs[name] = link            # linked by whoever asks first (a pool worker waiting on the pool could starve it)
+            return
+        if name == "step":
+            units = LIBRARY_UNITS + [os.path.join(EMU, "emu_step.cpp")]
+            objs = [os.path.join(self.out, "step_" + os.path.basename(u) + ".o") for u in units]
+            parts = [self.pool.submit(_run, [CLANG] + BASE + STEP_FLAGS.get(os.path.basename(u), ["-O0"]) + ASAN +
+                                      ["-DTT_HOST_EMULATION"] + INCLUDES + ["-c", u, "-o", o]) for u, o in zip(units, objs)]
+            exe = os.path.join(self.out, "emu_step")
+
+            def link_step():
+                for p in parts:
+                    p.result()
+                _run([CLANG] + ASAN + ["-o", exe] + objs)
+                return exe
+            self.jobs[name] = link_step
             return
         if isinstance(name, tuple):           # ("gemm1", configuration): the register-staged engine, one instantiation
             src, flags = "emu_gemm1.cpp", ["-O1"] + ASAN + ["-D%s=%d" % (n, v) for n, v in zip(GEMM1_NAMES, name[1])]

@@ -255,3 +255,94 @@ def test_shard_product_entry_point_rejects_what_the_library_rejects(emu_shard_ge
     # a K split that would leave the last chunk empty (chunks are rounded up to the tile depth: two of 64 cover K = 128)
     r = run(emu_shard_gemm, (2, 64, 64, 128, 0, 0, 1, 0, 0, 3))
     assert r.returncode == 2 and "status" in r.stdout
+
+
+# ---- a whole training step through the execute calls (planning of conversions, workspace layout, every launch of the
+# ---- forward and backward pass), with shards and workspace of exactly the sizes the library asks for
+
+import paper_1805_04170_amd as tt
+from synthetic import CONFIGS
+
+
+@pytest.fixture(scope="module")
+def emu_step(emulators):
+    return emulators.get("step")
+
+
+def _t(s):
+    return s if s else "-"
+
+
+def fc_step_args(batch, k, dtype, widths, relus, tx, tg, tw, forms):
+    L = len(widths) - 1
+    return (["fc", batch, k, dtype, L] + list(widths) + [int(r) for r in relus] + [_t(t) for t in tx] + [_t(t) for t in tg] +
+            [_t(t) for t in tw] + [_t(f) if f else "-" for lf in forms for f in lf])
+
+
+def planned_fc_step(cfg, mode=tt.TT_PLAN_EXACT):
+    L = cfg.n_layers
+    plan = tt.tt_plan_chain([tt.layer("fc", "none", cfg.widths[l], cfg.widths[l + 1]) for l in range(L)], cfg.batch, cfg.k, mode)
+    forms = [[plan.forms(l, op) for op in range(3)] for l in range(1, L + 1)]
+    return fc_step_args(cfg.batch, cfg.k, cfg.dtype, cfg.widths, [cfg.act(l) for l in range(1, L + 1)], plan.x(), plan.g(), plan.w(), forms)
+
+
+@pytest.mark.parametrize("name", ["tiny_mlp", "vgg16_fc"])
+def test_benchmark_step_stays_inside_its_buffers(emu_step, name):
+    # the step bench.py times, at its full size: planner tilings and forms, overlapped backward
+    r = run(emu_step, planned_fc_step(CONFIGS[name]))
+    assert r.returncode == 0 and r.stdout.startswith("ok fc step"), r.stdout[-400:] + r.stderr[-1500:]
+
+
+def test_the_step_checker_sees_a_workspace_that_is_too_short(emu_step):
+    # a step that needs its workspace (a reduction-split product), told the truth and then given 256 bytes less
+    args = fc_step_args(64, 2, "bf16", (72, 136, 40), (True, False), ["CC", "CC", "CC"], ["rr", "CC", "CC"], ["RR", "RR"], [[None] * 3] * 2)
+    assert run(emu_step, args).returncode == 0
+    r = run(emu_step, args, env={"EMU_WS_LIE": "256"})
+    assert r.returncode != 0 and "AddressSanitizer" in r.stderr
+
+
+def test_steps_under_random_tilings_stay_inside_their_buffers(emu_step):
+    # conversions in front of and behind every product, reductions of every depth: random stored tilings, default forms
+    rng = np.random.default_rng(11)
+    for k in (1, 2, 3):
+        ts = tl.all_tilings(k)
+        for _ in range(6):
+            tx = [ts[i] for i in rng.integers(0, len(ts), 3)]
+            tg = [ts[i] for i in rng.integers(0, len(ts), 3)]
+            tw = [ts[i] for i in rng.integers(0, len(ts), 2)]
+            dt = "bf16" if rng.integers(0, 2) else "f32"
+            args = fc_step_args(64, k, dt, (96, 1000, 40) if k == 3 else (72, 136, 40), (True, False), tx, tg, tw, [[None] * 3] * 2)
+            r = run(emu_step, args)
+            assert r.returncode == 0 and r.stdout.startswith("ok fc step"), (args, r.stdout[-400:] + r.stderr[-1500:])
+
+
+def conv_step_args(N, k, C, K, H, W, R, S, pad, relu, t, f):
+    return ["conv", N, k, C, K, H, W, R, S, pad, int(relu)] + [_t(t[n]) for n in ("X", "W", "Y", "dY", "dX")] + [x if x else "-" for x in f]
+
+
+@pytest.mark.parametrize("split", ["planner", "batch", "out_channel"])
+def test_convolution_step_stays_inside_its_buffers(emu_step, split):
+    # the three splits bench.py offers for a convolution layer, on a layer small enough for every split to run in seconds
+    N, k, C, K, H, W = 16, 3, 64, 128, 12, 12
+    lay = tt.layer("conv", "none", C, K, H=H, W=W, R=3, S=3, pad=1)
+    if split == "planner":
+        p = tt.tt_plan_chain([lay], N, k)
+        t = dict(X=p.x()[0], Y=p.x()[1], W=p.w()[0], dY=p.g()[1], dX=p.g()[0])
+        f = [p.forms(1, o) for o in range(3)]
+    elif split == "batch":
+        t = dict(X="R" * k, Y="R" * k, W="r" * k, dY="R" * k, dX="R" * k)
+        f = ["1" * k, "1" * k, "3" * k]
+    else:
+        t = dict(X="r" * k, Y="C" * k, W="C" * k, dY="C" * k, dX="r" * k)
+        f = ["2" * k, "3" * k, "2" * k]
+    r = run(emu_step, conv_step_args(N, k, C, K, H, W, 3, 3, 1, True, t, f))
+    assert r.returncode == 0 and r.stdout.startswith("ok conv step"), r.stdout[-400:] + r.stderr[-1500:]
+
+
+def test_convolution_steps_under_random_tilings_stay_inside_their_buffers(emu_step):
+    rng = np.random.default_rng(12)
+    ts = tl.all_tilings(2)
+    for i in range(8):
+        t = {n: ts[j] for n, j in zip(("X", "W", "Y", "dY", "dX"), rng.integers(0, len(ts), 5))}
+        r = run(emu_step, conv_step_args(4, 2, 32, 64, 9, 9, 3, 3, 1, bool(i % 2), t, [None] * 3))
+        assert r.returncode == 0 and r.stdout.startswith("ok conv step"), (t, r.stdout[-400:] + r.stderr[-1500:])
