@@ -129,18 +129,28 @@ inline tt_status plan_output(const uint8_t *forms, const tt_tiling &tZ, void *co
 // Extra split of the reduction dimension inside every shard product.  Skinny products (few output tiles, long K: the
 // batch-256 layers) leave most CUs idle and too few bytes in flight to stream the weights; cutting K puts more
 // workgroups on the machine at the price of fp32 partial sums that the reduction kernel adds up.
+// The launch cuts K into chunks of ceil(K / s) rounded up to the tile depth of 64; a split is usable only if that
+// leaves the last chunk non-empty (K = 1664 cut eight ways would give chunks of 256, of which six and a half exist).
+inline bool ksplit_fits(int64_t K, int s)
+{
+    const int64_t chunk = ((K + s - 1) / s + 63) / 64 * 64;
+    return s == 1 || chunk * (s - 1) < K;
+}
+
 inline int pick_ksplit(int64_t M, int64_t N, int64_t K, int count, int dtype, bool a_contig8, bool b_contig8)
 {
     if (dtype != TT_BF16 || !a_contig8 || !b_contig8) return 1;
     if (const char *e = std::getenv("TT_KSPLIT")) { // tuning aid
         const int f = std::atoi(e);
-        if (f >= 1 && K / f >= 256 && count * f <= kMaxShards) return f;
+        if (f >= 1 && K / f >= 256 && count * f <= kMaxShards && ksplit_fits(K, f)) return f;
     }
     const int64_t blocks = ((M + 255) / 256) * ((N + 255) / 256) * count; // 256 x 256 tiles, one per CU
     // chunks stay at least 512 deep, except where the launch would otherwise occupy under a quarter of the CUs (the
     // 1000-wide last layer): there chunks down to 192 still pay for the extra partial sums
     int s = 1;
-    while (blocks * s < 200 && s < 8 && K / (2 * s) >= (blocks * s < 64 ? 192 : 512) && count * 2 * s <= kMaxShards) s *= 2;
+    while (blocks * s < 200 && s < 8 && K / (2 * s) >= (blocks * s < 64 ? 192 : 512) && count * 2 * s <= kMaxShards &&
+           ksplit_fits(K, 2 * s))
+        s *= 2;
     return s;
 }
 

@@ -138,3 +138,9 @@ def test_shard_products_small(on_host, ta, tb):
     g = on_host["gemm"]
     g.test_bf16_unaligned_falls_back(ta, tb)
     g.test_fp32(ta, tb)
+
+
+def test_fc_backward_with_a_k_split_that_does_not_divide_into_whole_chunks(on_host):
+    # the data gradient here is a skinny product over K = 1664 = 26 x 64 per shard; cut eight ways inside the launch the
+    # chunks (rounded up to the tile depth) would be 256 deep and the last one and a half empty: the split has to stop at four
+    on_host["fc"].run_layer(128, 96, 1664, 3, "bf16", False, "CRR", "rCr", "RRR", "rrr", "CCR", None, "212", "313", 1134)
