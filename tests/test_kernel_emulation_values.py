@@ -128,3 +128,32 @@ def test_generic_kernel_values(lockstep_gemm, tmp_path, ta, tb):
     check(lockstep_gemm, str(tmp_path), 2, 70, 130, 65, ta, tb, "f32", "f32", True, 38)
     check(lockstep_gemm, str(tmp_path), 2, 37, 125, 50, ta, tb, "bf16", "bf16", True, 35)       # rows without 16-byte vectors
     check(lockstep_gemm, str(tmp_path), 1, 33, 10, 17, ta, tb, "bf16", "f32", False, 36, ksplit=1)
+
+
+def test_random_products_values(lockstep_gemm, tmp_path):
+    # seeded random shapes, layouts, types and tuning switches (sizes mostly multiples of eight, some odd): whatever
+    # engine the launch code picks or falls back to has to give the product
+    rng = np.random.default_rng(2024)
+    switches = [{}, {}, {"TT_GEMM_ENGINE": "4"}, {"TT_GEMM_ENGINE": "3", "TT_GEMM_TILE": "5", "EMU_CUS": "8"},
+                {"TT_GEMM_ENGINE": "1", "TT_GEMM_TILE": "8"}] + [{"TT_GEMM_ENGINE": "1", "TT_GEMM_TILE": str(t)} for t in range(6)]
+
+    def dim(hi):
+        v = int(rng.integers(8, hi))
+        return v if rng.random() < 0.15 else max(8, v // 8 * 8)
+
+    for case in range(24):
+        M, N, K = dim(560), dim(560), dim(330)
+        ta, tb = (int(v) for v in rng.integers(0, 2, 2))
+        in_dt = "bf16" if rng.random() < 0.85 else "f32"
+        out_dt = "bf16" if rng.integers(0, 2) else "f32"
+        ksplit = int(rng.choice([1, 1, 1, 2]))
+        if ksplit > 1 and ((K + 1) // 2 + 63) // 64 * 64 >= K:
+            ksplit = 1                                       # the second chunk would be empty: the launch refuses that
+        relu = bool(rng.integers(0, 2)) and ksplit == 1
+        if ksplit > 1:
+            out_dt = "f32"                                   # partial products are kept in fp32, as the execute calls ask
+        env = switches[int(rng.integers(0, len(switches)))]
+        try:
+            check(lockstep_gemm, str(tmp_path), int(rng.integers(1, 3)), M, N, K, ta, tb, in_dt, out_dt, relu, 300 + case, ksplit=ksplit, env=env)
+        except AssertionError as e:
+            raise AssertionError((case, M, N, K, ta, tb, in_dt, out_dt, relu, ksplit, env, str(e)[:500]))

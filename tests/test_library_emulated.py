@@ -15,6 +15,7 @@ import pytest
 import torch
 
 import paper_1805_04170_amd.binding as binding
+from oracle import tiling as tl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CLANG = shutil.which("clang++", path="/opt/rocm/llvm/bin") or shutil.which("clang++")
@@ -138,9 +139,73 @@ def test_shard_products_small(on_host, ta, tb):
     g = on_host["gemm"]
     g.test_bf16_unaligned_falls_back(ta, tb)
     g.test_fp32(ta, tb)
+    g.test_k_zero_and_empty()
 
 
 def test_fc_backward_with_a_k_split_that_does_not_divide_into_whole_chunks(on_host):
     # the data gradient here is a skinny product over K = 1664 = 26 x 64 per shard; cut eight ways inside the launch the
     # chunks (rounded up to the tile depth) would be 256 deep and the last one and a half empty: the split has to stop at four
     on_host["fc"].run_layer(128, 96, 1664, 3, "bf16", False, "CRR", "rCr", "RRR", "rrr", "CCR", None, "212", "313", 1134)
+
+
+def test_random_fc_layers(on_host):
+    # seeded random sizes, stored tilings and form sequences, one to three cuts; requests the library declines as
+    # infeasible or unsupported are skipped, any other status or a wrong value fails
+    rng = np.random.default_rng(77)
+    ran = 0
+    for case in range(20):
+        k = int(rng.choice([1, 2, 3, 3]))
+        ts = tl.all_tilings(k)
+        t = [ts[int(i)] for i in rng.integers(0, len(ts), 5)]
+        f = [None if rng.random() < 0.5 else "".join(str(int(v)) for v in rng.integers(1, 4, k)) for _ in range(3)]
+        mult = 1 << k
+        b, ni, no = (mult * int(rng.integers(1, 12)) * int(rng.choice([1, 8])) for _ in range(3))
+        dt = "bf16" if rng.random() < 0.7 else "f32"
+        try:
+            on_host["fc"].run_layer(b, ni, no, k, dt, bool(rng.integers(0, 2)), *t, *f, 3000 + case, with_dx=rng.random() < 0.85)
+            ran += 1
+        except binding.TilingError as e:
+            assert e.status in (2, 3), (case, b, ni, no, k, dt, t, f, str(e))
+    assert ran >= 10
+
+
+def test_random_conv_layers(on_host):
+    rng = np.random.default_rng(78)
+    ran = 0
+    for case in range(7):
+        k = int(rng.choice([1, 2, 2, 3]))
+        ts = tl.all_tilings(k)
+        t = [ts[int(i)] for i in rng.integers(0, len(ts), 5)]
+        f = [None if rng.random() < 0.5 else "".join(str(int(v)) for v in rng.integers(1, 4, k)) for _ in range(3)]
+        mult = 1 << k
+        N, C, K = mult * int(rng.integers(1, 3)), 8 * mult * int(rng.integers(1, 4)), 8 * mult * int(rng.integers(1, 4))
+        H, W, pad = int(rng.integers(3, 8)), int(rng.integers(3, 8)), int(rng.integers(0, 3))
+        R, S = int(rng.choice([1, 3, 5])), int(rng.choice([1, 3, 5]))
+        if H + 2 * pad < R or W + 2 * pad < S:
+            continue
+        try:
+            on_host["conv"].run_conv(N, C, K, H, W, R, S, pad, k, bool(rng.integers(0, 2)), *t, *f, 4000 + case, with_dx=rng.random() < 0.85)
+            ran += 1
+        except binding.TilingError as e:
+            assert e.status in (2, 3), (case, N, C, K, H, W, R, S, pad, k, t, f, str(e))
+    assert ran >= 4
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_fc_backward_overlapped_equals_backward(on_host, monkeypatch, relu):
+    # the two-stream variant's own path (fork, weight gradient first, join) gives the very same bits
+    from synthetic import normal_f32
+    fc = on_host["fc"]
+    monkeypatch.setattr(binding, "_stream", lambda s: ctypes.c_void_p(s if isinstance(s, int) else 0))
+    b, ni, no, k, dt = 64, 512, 384, 3, "bf16"
+    t = dict(X="CCr", W="RRC", Y="CCC", dY="CrC", dX="CCr")
+    forms = ("233", "112")
+    lay = binding.layer("fc", "relu" if relu else "none", ni, no)
+    X, W, Y, dY = (fc.to_store(normal_f32(90, i, shape, s), dt) for i, shape, s in
+                   ((0, (b, ni), 1.0), (1, (ni, no), 0.05), (3, (b, no), 1.0), (2, (b, no), 1.0)))
+    Xs, Ws, Ys, dYs = (fc.shards_to_dev(a, tt_, True) for a, tt_ in ((X, t["X"]), (W, t["W"]), (Y, t["Y"]), (dY, t["dY"])))
+    ref_dX, ref_dW, _ = fc._backward_once(binding.tt_fc_backward, lay, b, k, dt, t, forms, Xs, Ws, Ys, dYs, ni, no)
+    got_dX, got_dW, _ = fc._backward_once(binding.tt_fc_backward_overlapped, lay, b, k, dt, t, forms, Xs, Ws, Ys, dYs, ni, no, aux_stream=16)
+    for g, r in zip(got_dX + got_dW, ref_dX + ref_dW):
+        assert torch.equal(g.view(torch.int16), r.view(torch.int16))
+        assert not torch.isnan(g.float()).any()
