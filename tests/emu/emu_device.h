@@ -154,7 +154,11 @@ inline void land16(const char *g, uint32_t lds_wave_addr)
     if ((size_t)dst + 16 > g_lds_bytes) fail("load lands outside LDS", g_lds + dst, 16);
     if ((uintptr_t)g % 16) fail("misaligned 16-byte global -> LDS load", g, 16);
     check_read(g, 16);
+#ifdef TT_EMU_LOCKSTEP
+    emu::issue_lds_load(g_lds + dst, g);
+#else
     std::memcpy(g_lds + dst, g, 16);
+#endif
     g_dma_bytes += 16;
 }
 

@@ -9,9 +9,15 @@
 //     8 (r / 4) + 4 (lane / 32) + r % 4 for register r), products and sums in double, rounded once to fp32;
 //   - ds_read_b64_tr_b16: in every group of 16 lanes, element e of lane i comes from lane 4 e + i / 4, element i % 4
 //     (the 4 x 16 block of 16-bit values the group addressed, transposed).
-// Global -> LDS loads land at once.  With this the kernels produce values, which the tests compare with the oracle's.
+// Global -> LDS loads land late: a lane's loads stay pending, in order, until a wait count of that lane lets them
+// through (s_waitcnt vmcnt(n) lands all but the newest n), which is the latest the hardware may deliver them; its
+// stores and register loads, which the hardware counts as well, are not seen here, so the model never lands more than
+// the hardware has.  A kernel that reads a stage before waiting for it therefore reads stale data here, and one that
+// ends with loads still in flight towards LDS is reported.  With this the kernels produce values, which the tests
+// compare with the oracle's.
 #pragma once
 #include <ucontext.h>
+#include <deque>
 #include <functional>
 #include <vector>
 
@@ -28,7 +34,10 @@ struct WaveState {
     uint16_t tr[kWave][4];
 };
 
+struct PendingLoad { char *dst; const char *src; };
+
 struct Block {
+    std::vector<std::deque<PendingLoad>> pending; // per thread: global -> LDS loads issued and not yet landed
     ucontext_t sched;
     std::vector<ucontext_t> ctx;
     std::vector<char> done;
@@ -68,6 +77,23 @@ template <class F> inline void wave_collective(int kind, F &&complete)
     ++g_block.progress;
 }
 inline void wave_sync() { wave_collective(1, [](WaveState &) {}); }
+
+inline void issue_lds_load(char *dst, const char *src) { g_block.pending[g_block.cur].push_back({dst, src}); }
+
+// s_waitcnt with the gfx9 encoding of its operand: vmcnt in bits 3:0 and 15:14
+inline void wait_counts(unsigned imm)
+{
+    // EMU_VMCNT_SLACK=n: every wait lets n more loads stay in flight than the kernel asked for (self-check of this model:
+    // the kernels' results must then be wrong)
+    static const unsigned slack = [] { const char *e = std::getenv("EMU_VMCNT_SLACK"); return e ? (unsigned)std::atoi(e) : 0u; }();
+    const unsigned vmcnt = ((imm & 15u) | (((imm >> 14) & 3u) << 4)) + slack;
+    std::deque<PendingLoad> &q = g_block.pending[g_block.cur];
+    while (q.size() > vmcnt) {
+        std::memcpy(q.front().dst, q.front().src, 16);
+        q.pop_front();
+    }
+    wave_sync();
+}
 
 inline void block_barrier()
 {
@@ -133,6 +159,7 @@ inline void trampoline()
     Block &b = g_block;
     b.body();
     const int t = b.cur;
+    if (!b.pending[t].empty()) die("the kernel ended with global -> LDS loads still in flight");
     b.done[t] = 1;
     --b.live;
     WaveState &w = b.waves[t / kWave];
@@ -156,6 +183,7 @@ template <class F> inline void run_block(F &&body, unsigned threads)
     b.bar_arrived = 0;
     b.ctx.resize(threads);
     b.done.assign(threads, 0);
+    b.pending.assign(threads, std::deque<PendingLoad>());
     b.waves.assign((threads + kWave - 1) / kWave, WaveState());
     while (b.stacks.size() < threads) b.stacks.push_back(static_cast<char *>(std::malloc(kStackBytes)));
     for (unsigned t = 0; t < threads; ++t) {
@@ -181,6 +209,6 @@ template <class F> inline void run_block(F &&body, unsigned threads)
 } // namespace emu
 
 inline void __syncthreads() { emu::block_barrier(); }
-#define __builtin_amdgcn_s_waitcnt(x) emu::wave_sync()
+#define __builtin_amdgcn_s_waitcnt(x) emu::wait_counts(x)
 #define __builtin_amdgcn_wave_barrier() emu::wave_sync()
 #define __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, x, y, z) emu::mfma_32x32x16_bf16(a, b, c)

@@ -157,3 +157,13 @@ def test_random_products_values(lockstep_gemm, tmp_path):
             check(lockstep_gemm, str(tmp_path), int(rng.integers(1, 3)), M, N, K, ta, tb, in_dt, out_dt, relu, 300 + case, ksplit=ksplit, env=env)
         except AssertionError as e:
             raise AssertionError((case, M, N, K, ta, tb, in_dt, out_dt, relu, ksplit, env, str(e)[:500]))
+
+
+@pytest.mark.parametrize("env", [{"EMU_CUS": "16", "TT_GEMM_ENGINE": "3", "TT_GEMM_TILE": "5"}, {"TT_GEMM_ENGINE": "1", "TT_GEMM_TILE": "8"}, {}])
+def test_the_model_of_late_loads_bites(lockstep_gemm, tmp_path, env):
+    # global -> LDS loads land only when a wait count lets them (see emu_lockstep.h); if every wait let two more loads
+    # stay in flight than the kernel asks for, the engines that load straight into LDS must not get away with it
+    shape = (2, 520, 776, 192, 0, 1, "bf16", "f32", False, 42) if env else (1, 264, 392, 96, 0, 1, "bf16", "f32", False, 45)
+    check(lockstep_gemm, str(tmp_path), *shape, env=env)
+    with pytest.raises(AssertionError):
+        check(lockstep_gemm, str(tmp_path), *shape, env=dict(env, EMU_VMCNT_SLACK="2"))
