@@ -194,14 +194,19 @@ template <class F> inline void run_block(F &&body, unsigned threads)
         makecontext(&b.ctx[t], trampoline, 0);
         ++b.waves[t / kWave].live;
     }
+    // EMU_ORDER=reverse: the last wave runs ahead of the first instead of behind it (results must not depend on which
+    // wave reaches a barrier first)
+    static const bool reversed = [] { const char *e = std::getenv("EMU_ORDER"); return e && std::strcmp(e, "reverse") == 0; }();
     while (b.live > 0) {
         const unsigned long long before = b.progress;
-        for (unsigned t = 0; t < threads; ++t)
+        for (unsigned i = 0; i < threads; ++i) {
+            const unsigned t = reversed ? threads - 1 - i : i;
             if (!b.done[t]) {
                 b.cur = (int)t;
                 threadIdx = {t, 0, 0};
                 swapcontext(&b.sched, &b.ctx[t]);
             }
+        }
         if (b.progress == before) die("deadlock: every thread waits (a barrier or wave-wide operation not reached by all)");
     }
 }

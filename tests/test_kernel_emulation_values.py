@@ -167,3 +167,12 @@ def test_the_model_of_late_loads_bites(lockstep_gemm, tmp_path, env):
     check(lockstep_gemm, str(tmp_path), *shape, env=env)
     with pytest.raises(AssertionError):
         check(lockstep_gemm, str(tmp_path), *shape, env=dict(env, EMU_VMCNT_SLACK="2"))
+
+
+@pytest.mark.parametrize("env", [{"EMU_CUS": "16", "TT_GEMM_ENGINE": "3", "TT_GEMM_TILE": "5"}, {"TT_GEMM_ENGINE": "1", "TT_GEMM_TILE": "8"}, {},
+                                 {"TT_GEMM_ENGINE": "1", "TT_GEMM_TILE": "5"}])
+def test_results_do_not_depend_on_which_wave_runs_ahead(lockstep_gemm, tmp_path, env):
+    # the emulation runs the threads of a workgroup in index order between synchronisation points; with the order
+    # reversed the last wave reaches every barrier first, issues its loads first and writes its results first
+    shape = (2, 520, 776, 192, 1, 0, "bf16", "bf16", True, 42) if env else (1, 264, 392, 96, 1, 0, "bf16", "bf16", True, 45)
+    check(lockstep_gemm, str(tmp_path), *shape, env=dict(env, EMU_ORDER="reverse"))
