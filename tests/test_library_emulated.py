@@ -209,3 +209,49 @@ def test_fc_backward_overlapped_equals_backward(on_host, monkeypatch, relu):
     for g, r in zip(got_dX + got_dW, ref_dX + ref_dW):
         assert torch.equal(g.view(torch.int16), r.view(torch.int16))
         assert not torch.isnan(g.float()).any()
+
+
+def test_random_reductions_and_gated_retiles(on_host):
+    # partial sums of random form sequences reduced into random stored tilings (fp32 and bf16 results, with and without
+    # relu), and dY gated by Y > 0 on its way between random tilings: against the oracle, sizes with ragged vector tails
+    import paper_1805_04170_amd as tt
+    from gpu_util import alloc_shards, dev_to_np, np_to_dev, shards_to_dev, shards_to_np
+    from oracle import execute as ex
+    from synthetic import bf16_bits_to_f32, to_bf16_bits
+    rng = np.random.default_rng(91)
+    for case in range(30):
+        k = int(rng.choice([1, 2, 3, 4]))
+        forms = "".join(str(int(v)) for v in rng.integers(1, 4, k))
+        B = "".join("RCr"[int(v)] for v in rng.integers(0, 3, k))
+        mult = 1 << k
+        rows, cols = mult * int(rng.integers(1, 9)), mult * int(rng.integers(1, 40))
+        out, relu = ("bf16" if rng.integers(0, 2) else "f32"), bool(rng.integers(0, 2))
+        k1, k2 = forms.count("1"), forms.count("2")
+        parts = [rng.standard_normal((rows >> k1, cols >> k2)).astype(np.float32) for _ in range(mult)]
+        want = ex.reduce_to([p.astype(np.float64) for p in parts], forms, B, rows, cols, relu)
+        dst = alloc_shards(rows, cols, B, torch.bfloat16 if out == "bf16" else torch.float32)
+        tt.tt_reduce(dst, B, out, [np_to_dev(p) for p in parts], forms, rows, cols, tt.TT_ACT_RELU if relu else tt.TT_ACT_NONE)
+        mag = ex.assemble([np.abs(p).astype(np.float64) for p in parts], forms, rows, cols)
+        for s, (d, w) in enumerate(zip(dst, want)):
+            g = dev_to_np(d)
+            gf = bf16_bits_to_f32(g).astype(np.float64) if out == "bf16" else g.astype(np.float64)
+            tol = 1e-5 * mag[tl.shard_slices(rows, cols, B, s)] + (2.0 ** -8 * np.abs(w) if out == "bf16" else 0.0)
+            assert np.all(np.abs(gf - w) <= tol + 1e-30), (case, forms, B, rows, cols, out, relu, s)
+    for case in range(20):
+        k = int(rng.choice([1, 2, 3]))
+        tA, tM, tB = ("".join("RCr"[int(v)] for v in rng.integers(0, 3, k)) for _ in range(3))
+        mult = 1 << k
+        rows, cols = mult * int(rng.integers(1, 9)), mult * int(rng.integers(1, 40))
+        bf = bool(rng.integers(0, 2))
+        v = rng.standard_normal((rows, cols)).astype(np.float32)
+        m = rng.standard_normal((rows, cols)).astype(np.float32)
+        m[rng.random((rows, cols)) < 0.3] = 0.0
+        if bf:
+            v, m = to_bf16_bits(v), to_bf16_bits(m)
+        mf = bf16_bits_to_f32(m) if bf else m
+        want_full = np.where(mf > 0, v, np.zeros_like(v))
+        dst = alloc_shards(rows, cols, tB, torch.bfloat16 if bf else torch.float32, fill=float("nan"))
+        tt.tt_retile_gate(dst, tB, shards_to_dev(v, tA, bf), tA, shards_to_dev(m, tM, bf), tM, rows, cols, "bf16" if bf else "f32")
+        got = tl.untile(shards_to_np(dst), tB, rows, cols)
+        u = np.uint16 if bf else np.uint32
+        assert np.array_equal(got.view(u), want_full.view(u)), (case, tA, tM, tB, rows, cols, bf)
