@@ -286,7 +286,7 @@ def planned_fc_step(cfg, mode=tt.TT_PLAN_EXACT):
     return fc_step_args(cfg.batch, cfg.k, cfg.dtype, cfg.widths, [cfg.act(l) for l in range(1, L + 1)], plan.x(), plan.g(), plan.w(), forms)
 
 
-@pytest.mark.parametrize("name", ["tiny_mlp", "vgg16_fc"])
+@pytest.mark.parametrize("name", ["tiny_mlp", "vgg16_fc", "alexnet_fc"])
 def test_benchmark_step_stays_inside_its_buffers(emu_step, name):
     # the step bench.py times, at its full size: planner tilings and forms, overlapped backward
     r = run(emu_step, planned_fc_step(CONFIGS[name]))
@@ -336,6 +336,16 @@ def test_convolution_step_stays_inside_its_buffers(emu_step, split):
         t = dict(X="r" * k, Y="C" * k, W="C" * k, dY="C" * k, dX="r" * k)
         f = ["2" * k, "3" * k, "2" * k]
     r = run(emu_step, conv_step_args(N, k, C, K, H, W, 3, 3, 1, True, t, f))
+    assert r.returncode == 0 and r.stdout.startswith("ok conv step"), r.stdout[-400:] + r.stderr[-1500:]
+
+
+def test_convolution_benchmark_step_stays_inside_its_buffers(emu_step):
+    # vgg16_conv4 at full size under the planner's tiling, as bench.py runs it
+    c = CONFIGS["vgg16_conv4"]
+    lay = tt.layer("conv", "none", c.C, c.K, H=c.H, W=c.W, R=c.R, S=c.S, pad=c.pad)
+    p = tt.tt_plan_chain([lay], c.N, c.k)
+    t = dict(X=p.x()[0], Y=p.x()[1], W=p.w()[0], dY=p.g()[1], dX=p.g()[0])
+    r = run(emu_step, conv_step_args(c.N, c.k, c.C, c.K, c.H, c.W, c.R, c.S, c.pad, False, t, [p.forms(1, o) for o in range(3)]))
     assert r.returncode == 0 and r.stdout.startswith("ok conv step"), r.stdout[-400:] + r.stderr[-1500:]
 
 
