@@ -30,13 +30,11 @@ CASES = [
     (3, 8, 1032, 1544, 64, 1, 1, 0, 0, 1),
     (3, 3, 2056, 1800, 320, 0, 1, 1, 0, 1),
     (3, 8, 2056, 2312, 256, 0, 0, 1, 1, 1),
-    # (the weight gradient of the VGG-16 first classifier layer, 8 x 3136 x 4096 x 256, runs below through tt_shard_gemm)
-    (3, 8, 256, 4096, 3136, 1, 0, 0, 0, 2),     # its forward product with the in-shard K split, fp32 partial sums
+    # (the three products of the VGG-16 first classifier layer run below, through tt_shard_gemm and in the benchmark step)
     (3, 16, 512, 2048, 2048, 1, 1, 1, 0, 1),    # wide MLP shard product
     (3, 2, 520, 776, 64, 0, 0, 1, 0, 1),
     (3, 1, 264, 1000, 192, 1, 0, 1, 0, 1),      # 1000 columns: ragged last tile, 16-byte rows
     (3, 1, 264, 1004, 128, 1, 1, 0, 0, 1),      # fp32 rows of 1004
-    (2, 8, 256, 3136, 4096, 1, 1, 0, 0, 2),     # direct-to-LDS engine: data gradient of the VGG-16 first classifier layer
     (2, 8, 1000, 1016, 200, 0, 0, 1, 1, 1),     # ragged M, N and K (K tail read as zero chunks)
     (2, 8, 1024, 1024, 192, 0, 1, 0, 0, 1),
     (2, 1, 520, 264, 72, 1, 1, 1, 0, 1),
