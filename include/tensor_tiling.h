@@ -252,6 +252,18 @@ tt_status tt_fc_forward(const tt_layer *layer, int64_t batch, int k, int dtype, 
                         tt_tiling tY, const uint8_t *forms, const void *const *X, const void *const *W,
                         void *const *Y, void *workspace, size_t ws_bytes, void *stream);
 
+/* tt_fc_forward for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments, results and errors as tt_fc_forward; the
+ * scratch comes from an array of TT_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU the
+ * library runs on holds its copy until the process ends).  The call allocates nothing and frees nothing.
+ * TT_EWORKSPACE if the layer needs more scratch than that (tt_fc_workspace_bytes tells how much).  All calls on one
+ * GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads) race; the array keeps
+ * the last call's contents and nothing in it needs clearing between calls. */
+enum { TT_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024 };
+tt_status tt_fc_forward_static(const tt_layer *layer, int64_t batch, int k, int dtype, tt_tiling tX, tt_tiling tW,
+                               tt_tiling tY, const uint8_t *forms, const void *const *X, const void *const *W,
+                               void *const *Y, void *stream);
+
 /* G = dY gated by [Y > 0] (act RELU) or dY;  dX = G W^T (under tdX);  dW = X^T G (under tW, dtype as W).
  * Y is the layer's stored output under tY (ignored when act is NONE; may then be NULL).
  * dX may be NULL to skip the activation gradient. */

@@ -12,6 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libtensor_tiling.so")
 
 TT_MAX_K = 6
 TT_MAX_LAYERS = 16
+TT_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 TT_R, TT_C, TT_REP = 0, 1, 2
 TT_F32, TT_BF16 = 0, 1
 TT_ACT_NONE, TT_ACT_RELU = 0, 1
@@ -25,7 +26,8 @@ STATUS_NAMES = {0: "TT_OK", 1: "TT_EINVAL", 2: "TT_EINFEASIBLE", 3: "TT_EUNSUPPO
 EXPORTS = [
     "tt_strerror", "tt_shard_shape", "tt_plan_chain", "tt_plan_eval", "tt_plan_k", "tt_plan_layers", "tt_plan_cost",
     "tt_plan_delta", "tt_plan_tiling", "tt_plan_forms", "tt_plan_free", "tt_retile", "tt_retile_gate", "tt_reduce",
-    "tt_shard_gemm", "tt_fc_workspace_bytes", "tt_fc_forward", "tt_fc_backward", "tt_fc_backward_overlapped", "tt_conv_workspace_bytes",
+    "tt_shard_gemm", "tt_fc_workspace_bytes", "tt_fc_forward", "tt_fc_forward_static", "tt_fc_backward", "tt_fc_backward_overlapped",
+    "tt_conv_workspace_bytes",
     "tt_conv_forward", "tt_conv_backward", "tt_profile_begin", "tt_profile_end", "tt_profile_get",
     "tt_plan_graph", "tt_graph_eval", "tt_graph_plan_cost", "tt_graph_plan_delta", "tt_graph_plan_levels",
     "tt_graph_plan_level_of", "tt_graph_plan_tiling", "tt_graph_plan_forms", "tt_graph_plan_free",
@@ -135,6 +137,7 @@ def lib():
         L.tt_conv_workspace_bytes.argtypes = ws_args
         L.tt_fc_forward.argtypes = fwd_args
         L.tt_conv_forward.argtypes = fwd_args
+        L.tt_fc_forward_static.argtypes = fwd_args[:11] + [ctypes.c_void_p]
         L.tt_fc_backward.argtypes = bwd_args
         L.tt_conv_backward.argtypes = bwd_args
         L.tt_fc_backward_overlapped.argtypes = bwd_args + [ctypes.c_void_p]
@@ -487,6 +490,11 @@ def _backward(fn, what, lay, batch, k, dtype, tX, tW, tY, tdY, tdX, forms_dgrad,
 
 def tt_fc_forward(lay, batch, k, dtype, tX, tW, tY, form_seq, X, W, Y, workspace=None, stream=None):
     _forward(lib().tt_fc_forward, "tt_fc_forward", lay, batch, k, dtype, tX, tW, tY, form_seq, X, W, Y, workspace, stream)
+
+
+def tt_fc_forward_static(lay, batch, k, dtype, tX, tW, tY, form_seq, X, W, Y, stream=None):
+    _check(lib().tt_fc_forward_static(ctypes.byref(lay), batch, k, _dtype(dtype), tiling(tX), tiling(tW), tiling(tY),
+                                      forms(form_seq), ptrs(X), ptrs(W), ptrs(Y), _stream(stream)), "tt_fc_forward_static")
 
 
 def tt_fc_backward(lay, batch, k, dtype, tX, tW, tY, tdY, tdX, forms_dgrad, forms_wgrad, X, W, Y, dY, dX, dW,

@@ -15,6 +15,7 @@
 #define __global__
 #define __forceinline__ inline __attribute__((always_inline))
 #define __launch_bounds__(...)
+#define __align__(n) __attribute__((aligned(n)))
 
 struct EmuDim3 { unsigned x, y, z; };
 inline EmuDim3 threadIdx, blockIdx;
@@ -56,6 +57,9 @@ inline hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }
 inline hipError_t hipEventSynchronize(hipEvent_t) { return hipSuccess; }
 inline hipError_t hipEventElapsedTime(float *ms, hipEvent_t, hipEvent_t) { *ms = 0.0f; return hipSuccess; }
 inline hipError_t hipStreamWaitEvent(hipStream_t, hipEvent_t, unsigned) { return hipSuccess; }
+// a `__device__` array is a plain host array here, and its "device address" is its own
+#define HIP_SYMBOL(x) (x)
+inline hipError_t hipGetSymbolAddress(void **p, const void *symbol) { *p = const_cast<void *>(symbol); return hipSuccess; }
 enum hipDeviceAttribute_t { hipDeviceAttributeMultiprocessorCount = 63 };
 inline hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
 inline hipError_t hipDeviceGetAttribute(int *value, hipDeviceAttribute_t, int)

@@ -211,6 +211,12 @@ def test_fc_backward_overlapped_equals_backward(on_host, monkeypatch, relu):
         assert not torch.isnan(g.float()).any()
 
 
+def test_forward_with_the_library_s_own_scratch(on_host):
+    import test_zz_no_alloc as na
+    na.test_static_scratch_forward_twice_second_smaller()
+    na.test_static_scratch_refuses_what_does_not_fit()
+
+
 def test_random_reductions_and_gated_retiles(on_host):
     # partial sums of random form sequences reduced into random stored tilings (fp32 and bf16 results, with and without
     # relu), and dY gated by Y > 0 on its way between random tilings: against the oracle, sizes with ragged vector tails
