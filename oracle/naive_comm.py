@@ -21,7 +21,15 @@ def model_parallel(batch, width, layers, n_dev, elem=4):
     return activation_bytes(batch, width, layers, elem) * n_dev * 2
 
 
+def hybrid_across(width, layers, groups, elem=4):
+    # data parallelism across the groups: every group's gradients gathered, the parameters sent back
+    return param_bytes(width, layers, elem) * groups * 2
+
+
+def hybrid_within(batch, width, layers, groups, per_group, elem=4):
+    # model parallelism inside one group, on that group's share of the batch
+    return activation_bytes(batch, width, layers, elem) // groups * per_group * 2
+
+
 def hybrid(batch, width, layers, groups, per_group, elem=4):
-    across = param_bytes(width, layers, elem) * groups * 2
-    within = activation_bytes(batch, width, layers, elem) // groups * per_group * 2
-    return across + groups * within
+    return hybrid_across(width, layers, groups, elem) + groups * hybrid_within(batch, width, layers, groups, per_group, elem)

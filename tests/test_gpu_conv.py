@@ -45,7 +45,7 @@ def ws(nbytes):
 
 
 def close(got, want, mag, what):
-    tol = 1e-2 * mag + 2.0 ** -8 * np.abs(want)
+    tol = 1e-2 * mag                                               # the stated bound, nothing added
     err = np.abs(got - want)
     assert np.all(np.isfinite(got)), what
     assert np.all(err <= tol + 1e-30), (what, float(err.max()), float((err / (tol + 1e-30)).max()))
@@ -131,8 +131,24 @@ def test_refusals():
     assert e.value.status == 2
 
 
+_CONV4_ORACLE = {}
+
+
+def conv4_oracle(cfg):
+    """the untiled fp64 results of the full-size layer and their magnitude products (the same for every split: no
+    activation, so the gated gradient is the incoming one); computed once per session, about half a minute of host time"""
+    if not _CONV4_ORACLE:
+        X, W, dY = bf16_bits_to_f64(cfg.x()), bf16_bits_to_f64(cfg.weight()), bf16_bits_to_f64(cfg.grad_out())
+        aX, aW, adY = np.abs(X), np.abs(W), np.abs(dY)
+        _CONV4_ORACLE.update(
+            Y=(ly.conv_forward(X, W, cfg.pad), ly.conv_forward(aX, aW, cfg.pad)),
+            dX=(ly.conv_dgrad(dY, W, cfg.pad, cfg.H, cfg.W), ly.conv_dgrad(adY, aW, cfg.pad, cfg.H, cfg.W)),
+            dW=(ly.conv_wgrad(X, dY, cfg.pad, cfg.R, cfg.S), ly.conv_wgrad(aX, adY, cfg.pad, cfg.R, cfg.S)))
+    return _CONV4_ORACLE
+
+
 @pytest.mark.parametrize("split", ["planner", "batch", "out_channel"])
-def test_config_vgg_conv4_full_size_sampled(split):
+def test_config_vgg_conv4_full_size_every_element(split):
     cfg = CONFIGS["vgg16_conv4"]
     N, C, K, H, Wd, R, S, pad, k = cfg.N, cfg.C, cfg.K, cfg.H, cfg.W, cfg.R, cfg.S, cfg.pad, cfg.k
     P, Q = cfg.P, cfg.Q
@@ -157,15 +173,10 @@ def test_config_vgg_conv4_full_size_sampled(split):
     tt.tt_conv_forward(lay, N, k, "bf16", tX, tW, tY, f[0], Xs, Ws_, Ys, w)
     tt.tt_conv_backward(lay, N, k, "bf16", tX, tW, tY, tdY, tdX, f[1], f[2], Xs, Ws_, Ys, dYs, dXs, dWs, w)
     torch.cuda.synchronize()
-    X, W, dY = bf16_bits_to_f64(Xb), bf16_bits_to_f64(Wb), bf16_bits_to_f64(dYb)
     Yg = act_from_matrix(bf16_bits_to_f64(tl.untile(shards_to_np(Ys), tY, N * P * Q, K)), N, K, P, Q)
     dXg = act_from_matrix(bf16_bits_to_f64(tl.untile(shards_to_np(dXs), tdX, N * H * Wd, C)), N, C, H, Wd)
     dWg = filt_from_matrix(bf16_bits_to_f64(tl.untile(shards_to_np(dWs), tWs, K * R * S, C)), K, C, R, S)
-    for n in (0, 37, 63):                                  # whole images, one per shard region
-        close(Yg[n:n + 1], ly.conv_forward(X[n:n + 1], W, pad), conv_mag_fwd(X[n:n + 1], W, pad), ("fwd", n))
-        close(dXg[n:n + 1], ly.conv_dgrad(dY[n:n + 1], W, pad, H, Wd),
-              ly.conv_dgrad(np.abs(dY[n:n + 1]), np.abs(W), pad, H, Wd), ("dgrad", n))
-    for k0, c0 in ((0, 0), (250, 500), (504, 8)):          # 8 x 8 blocks of filters, all taps, summed over the whole batch
-        want = ly.conv_wgrad(X[:, c0:c0 + 8], dY[:, k0:k0 + 8], pad, R, S)
-        mag = ly.conv_wgrad(np.abs(X[:, c0:c0 + 8]), np.abs(dY[:, k0:k0 + 8]), pad, R, S)
-        close(dWg[k0:k0 + 8, c0:c0 + 8], want, mag, ("wgrad", k0, c0))
+    o = conv4_oracle(cfg)                                  # all 64 images, all 512 x 512 x 3 x 3 filter gradients
+    close(Yg, o["Y"][0], o["Y"][1], ("fwd", split))
+    close(dXg, o["dX"][0], o["dX"][1], ("dgrad", split))
+    close(dWg, o["dW"][0], o["dW"][1], ("wgrad", split))

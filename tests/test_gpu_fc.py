@@ -36,9 +36,7 @@ def workspace(nbytes):
 def assert_close(got_shards, t, rows, cols, want, mag, dt, what):
     got = tl.untile(shards_to_np(got_shards), t, rows, cols)      # also checks replicas are identical
     gf = f64(got, dt)
-    tol = (1e-2 if dt == "bf16" else 1e-5) * mag
-    if dt == "bf16":
-        tol = tol + 2.0 ** -8 * np.abs(want)                       # the result is stored in bf16
+    tol = (1e-2 if dt == "bf16" else 1e-5) * mag                   # the stated bound, nothing added
     err = np.abs(gf - want)
     assert np.all(np.isfinite(gf)), what
     assert np.all(err <= tol + 1e-30), (what, float(err.max()), float((err / (tol + 1e-30)).max()))
@@ -215,9 +213,10 @@ def chain_tensors(cfg):
     return cfg.x0(), [cfg.weight(l) for l in range(1, cfg.n_layers + 1)], cfg.grad_out()
 
 
-def run_chain(cfg, plan, check_rows=None):
-    """Forward and backward of a whole chain under a plan; each op is compared with the oracle applied to the
-    operands the GPU actually stored.  check_rows: rows of the activations to check (None = all)."""
+def run_chain(cfg, plan):
+    """Forward and backward of a whole chain under a plan; every element of every activation, activation gradient and
+    weight gradient is compared with the oracle applied to the operands the GPU actually stored (per operation, so
+    tolerances do not compound along the chain).  Returns the largest error / bound ratio seen per kind of product."""
     dt, k, b, L = cfg.dtype, cfg.k, cfg.batch, cfg.n_layers
     bf = dt == "bf16"
     x0, Ws, gL = chain_tensors(cfg)
@@ -232,14 +231,21 @@ def run_chain(cfg, plan, check_rows=None):
         tt.tt_fc_forward(layers[l - 1], b, k, dt, tx[l - 1], tw[l - 1], tx[l], f, xs[l - 1], wsh[l - 1], ys, workspace(nb))
         xs.append(ys)
     torch.cuda.synchronize()
-    rows = slice(None) if check_rows is None else check_rows
+    tol_c = 1e-2 if bf else 1e-5                                   # the stated bounds, nothing added
+    worst = {"fwd": 0.0, "dgrad": 0.0, "wgrad": 0.0}
+
+    def compare(kind, l, got, want, mag):
+        err = np.abs(got - want)
+        assert np.all(np.isfinite(got)), (kind, l)
+        bound = tol_c * mag + 1e-30
+        assert np.all(err <= bound), (kind, l, float(err.max()), np.argwhere(err > bound)[:5])
+        worst[kind] = max(worst[kind], float((err / bound).max()))
+
     full_x = [f64(tl.untile(shards_to_np(xs[l]), tx[l], b, cfg.widths[l]), dt) for l in range(L + 1)]
     Wf = [f64(w, dt) for w in Ws]
     for l in range(1, L + 1):
-        want = ly.fc_forward(full_x[l - 1][rows], Wf[l - 1], bool(cfg.act(l)))
-        mag = ly.abs_product(full_x[l - 1][rows], Wf[l - 1])
-        tol = (1e-2 if bf else 1e-5) * mag + (2.0 ** -8 * np.abs(want) if bf else 0)
-        assert np.all(np.abs(full_x[l][rows] - want) <= tol + 1e-30), ("fwd", l)
+        compare("fwd", l, full_x[l], ly.fc_forward(full_x[l - 1], Wf[l - 1], bool(cfg.act(l))),
+                ly.abs_product(full_x[l - 1], Wf[l - 1]))
     gs = [None] * (L + 1)
     gs[L] = shards_to_dev(gL, tg[L], bf)
     dws = [None] * L
@@ -255,18 +261,14 @@ def run_chain(cfg, plan, check_rows=None):
     for l in range(L, 0, -1):
         relu = bool(cfg.act(l))
         G = full_g[l] * (full_x[l] > 0) if relu else full_g[l]
-        want_dx = G[rows] @ Wf[l - 1].T
-        mag = np.abs(G[rows]) @ np.abs(Wf[l - 1].T)
-        tol = (1e-2 if bf else 1e-5) * mag + (2.0 ** -8 * np.abs(want_dx) if bf else 0)
-        assert np.all(np.abs(full_g[l - 1][rows] - want_dx) <= tol + 1e-30), ("dgrad", l)
-        # weight gradient: sampled rows of dW (input neurons), all columns
+        want_dx, want_dw = ly.fc_backward(full_g[l], full_x[l - 1], Wf[l - 1], full_x[l], relu)
+        compare("dgrad", l, full_g[l - 1], want_dx, ly.abs_product(G, Wf[l - 1].T))
         ni = cfg.widths[l - 1]
-        pick = np.arange(ni) if check_rows is None else np.unique(np.linspace(0, ni - 1, 64).astype(int))
         dW = f64(tl.untile(shards_to_np(dws[l - 1]), tw[l - 1], ni, cfg.widths[l]), dt)
-        want_dw = full_x[l - 1][:, pick].T @ G
-        mag = np.abs(full_x[l - 1][:, pick].T) @ np.abs(G)
-        tol = (1e-2 if bf else 1e-5) * mag + (2.0 ** -8 * np.abs(want_dw) if bf else 0)
-        assert np.all(np.abs(dW[pick] - want_dw) <= tol + 1e-30), ("wgrad", l)
+        dws[l - 1] = None
+        compare("wgrad", l, dW, want_dw, ly.abs_product(full_x[l - 1].T, G))
+        del dW, want_dx, want_dw
+    return worst
 
 
 def plan_for(cfg, mode=tt.TT_PLAN_EXACT, **pins):
@@ -284,7 +286,7 @@ def test_config_tiny_mlp_fp32_planned_and_recursive():
 @pytest.mark.parametrize("name", ["alexnet_fc", "vgg16_fc"])
 def test_config_fc_stacks_full_size(name):
     cfg = CONFIGS[name]
-    run_chain(cfg, plan_for(cfg), check_rows=np.array([0, 1, 31, 32, 100, 255]))
+    run_chain(cfg, plan_for(cfg))
 
 
 class ForcedPlan:
@@ -312,7 +314,7 @@ def test_config_wide_mlp_full_size_forced_tiling():
     # first operand; the weight gradient lands directly in the stored grid.
     cfg = CONFIGS["wide_mlp"]
     plan = ForcedPlan(cfg.n_layers, "RRCC", "RRCC", "RRCC", ["3322", "2233", "1122"])
-    run_chain(cfg, plan, check_rows=np.array([0, 127, 128, 300, 511]))
+    run_chain(cfg, plan)
 
 
 def test_wide_mlp_shapes_sixteen_way_reduce():

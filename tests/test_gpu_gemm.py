@@ -35,15 +35,16 @@ def check(count, M, N, K, ta, tb, in_dt, out_dt, relu, seed):
     for s in range(count):
         got = dev_to_np(Cs[s])
         gf = bf16_bits_to_f64(got) if out_dt == "bf16" else got.astype(np.float64)
-        tol = (1e-2 if bf else 1e-5) * mags[s]
-        if out_dt == "bf16":
-            tol = tol + 2.0 ** -8 * np.abs(want[s])
+        tol = (1e-2 if bf else 1e-5) * mags[s]                      # the stated bound, nothing added
         err = np.abs(gf - want[s])
         assert np.all(np.isfinite(gf)), (s, "non-finite output")
         assert np.all(err <= tol + 1e-30), (s, float(err.max()), float((err / (tol + 1e-30)).max()))
-        # the bound is loose for fp32 accumulation; also require a tight typical error so a dropped k-tile cannot hide
-        if bf and out_dt == "f32":
-            assert float(np.max(err / (mags[s] + 1e-30))) < 1e-4
+        # the bound is loose for fp32 accumulation; also require a tight typical error so a dropped k-tile cannot hide:
+        # 1e-4 of the magnitude product, plus the rounding of the stored result where that is bf16 (8 significant bits,
+        # round to nearest: at most 2^-8 of the value)
+        if bf:
+            tight = 1e-4 * mags[s] + (2.0 ** -8 * np.abs(want[s]) if out_dt == "bf16" else 0.0)
+            assert np.all(err <= tight + 1e-30), (s, float((err / (tight + 1e-30)).max()))
 
 
 LAYOUTS = [(0, 0), (0, 1), (1, 0), (1, 1)]
@@ -113,9 +114,8 @@ def test_k_zero_and_empty():
     tt.tt_shard_gemm(A, A, C, 0, 8, 4, 0, 0, "bf16", "f32")          # nothing to do
 
 
-def test_vgg_shard_shape_sampled():
-    # the K-split shard product of the VGG-16 first classifier layer: 256 x 3136 x 4096, fp32 partial output;
-    # sampled rows checked against the oracle
+def test_vgg_shard_shape_every_element():
+    # the K-split shard product of the VGG-16 first classifier layer: 256 x 3136 x 4096, fp32 partial output
     M, K, N = 256, 3136, 4096
     a = to_bf16_bits(normal_f32(41, 0, (M, K), 1.0)); b = to_bf16_bits(normal_f32(41, 1, (K, N), 0.005))
     A = [np_to_dev(a, True)]; B = [np_to_dev(b, True)]
@@ -123,9 +123,8 @@ def test_vgg_shard_shape_sampled():
     tt.tt_shard_gemm(A, B, C, M, N, K, 0, 0, "bf16", "f32")
     torch.cuda.synchronize()
     got = dev_to_np(C[0]).astype(np.float64)
-    rows = [0, 1, 127, 128, 200, 255]
-    af, bfl = bf16_bits_to_f64(a[rows]), bf16_bits_to_f64(b)
+    af, bfl = bf16_bits_to_f64(a), bf16_bits_to_f64(b)
     want = af @ bfl
-    mag = np.abs(af) @ np.abs(bfl)
-    assert np.all(np.abs(got[rows] - want) <= 1e-2 * mag)
-    assert float(np.max(np.abs(got[rows] - want) / mag)) < 1e-4
+    mag = ly.abs_product(af, bfl)
+    assert np.all(np.abs(got - want) <= 1e-2 * mag)
+    assert float(np.max(np.abs(got - want) / mag)) < 1e-4

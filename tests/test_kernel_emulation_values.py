@@ -52,8 +52,6 @@ def check(exe, tmp, count, M, N, K, ta, tb, in_dt, out_dt, relu, seed, ksplit=1,
             raw = np.fromfile(os.path.join(tmp, "c%d.bin" % (s * ksplit + q)), dtype=np.uint16 if out_dt == "bf16" else np.float32)
             gf += (bf16_bits_to_f64(raw) if out_dt == "bf16" else raw.astype(np.float64)).reshape(M, N)
         tol = (1e-2 if bf else 1e-5) * mags[s]
-        if out_dt == "bf16":
-            tol = tol + ksplit * 2.0 ** -8 * np.abs(want[s])
         err = np.abs(gf - want[s])
         assert np.all(np.isfinite(gf)), (s, "non-finite output")
         assert np.all(err <= tol + 1e-30), (s, float(err.max()), float((err / (tol + 1e-30)).max()), np.argwhere(err > tol + 1e-30)[:5])

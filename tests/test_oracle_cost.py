@@ -221,6 +221,8 @@ def test_sec_2_2_numbers(golden_loader):
     assert nc.activation_bytes(400, 300, 5) / MB == g["activation_MB"]
     assert nc.data_parallel(300, 5, 16) / MB == g["data_parallel_MB"]
     assert nc.model_parallel(400, 300, 5, 16) / MB == g["model_parallel_MB"]
+    assert nc.hybrid_across(300, 5, 4) / MB == g["hybrid_across_MB"]
+    assert nc.hybrid_within(400, 300, 5, 4, 4) / MB == g["hybrid_within_MB"]
     hy = nc.hybrid(400, 300, 5, 4, 4)
     assert hy / MB == g["hybrid_MB"]
     assert round(100 * (1 - hy / nc.data_parallel(300, 5, 16)), 1) == g["saving_vs_data_percent"]

@@ -86,3 +86,46 @@ def test_conv_point_matches_full():
     for (n, k, y, x) in [(0, 0, 0, 0), (1, 4, 4, 3), (0, 2, 2, 1), (1, 1, 0, 3)]:
         v, mag = ly.conv_forward_point(X, W, 1, n, k, y, x)
         assert abs(v - Y[n, k, y, x]) < 1e-12 and mag >= abs(v)
+
+
+# ---- the same operators as plain nested loops (oracle/layers_plain.c): the definitions written out; the numpy forms
+# above must agree with them up to the order of the fp64 additions
+
+def test_plain_loops_hand_case_and_orientation():
+    from oracle import layers_plain as lp
+    X = np.array([[1.0, 2.0, 3.0], [-1.0, 0.5, 0.0]])
+    W = np.array([[1.0, -1.0], [0.0, 2.0], [2.0, 1.0]])
+    assert np.array_equal(lp.fc_forward(X, W, False), np.array([[7.0, 6.0], [-1.0, 2.0]]))     # by hand, as above
+    Y = lp.fc_forward(X, W, True)
+    assert np.array_equal(Y, np.array([[7.0, 6.0], [0.0, 2.0]]))
+    dX, dW = lp.fc_backward(np.array([[1.0, 1.0], [10.0, 100.0]]), X, W, Y, True)
+    assert np.array_equal(dX, np.array([[0.0, 2.0, 3.0], [-100.0, 200.0, 100.0]]))
+    assert np.array_equal(dW, np.array([[1.0, -99.0], [2.0, 52.0], [3.0, 3.0]]))
+    # a filter with a single 1 at tap (r, s) of channel pair (ko, c) shifts channel c of the image into channel ko
+    Xi = np.arange(2 * 2 * 3 * 4, dtype=np.float64).reshape(2, 2, 3, 4)
+    Wt = np.zeros((3, 2, 3, 3)); Wt[2, 1, 0, 2] = 1.0          # reads X[n, 1, y + 0 - 1, x + 2 - 1]
+    Yc = lp.conv_forward(Xi, Wt, 1)
+    want = np.zeros((2, 3, 3, 4)); want[:, 2, 1:, :3] = Xi[:, 1, :2, 1:]
+    assert np.array_equal(Yc, want)
+
+
+def test_numpy_forms_agree_with_the_plain_loops():
+    from oracle import layers_plain as lp
+    rng = np.random.default_rng(11)
+    for (b, ni, no, relu) in [(5, 7, 3, False), (9, 33, 17, True), (16, 64, 40, True)]:
+        X, W, dY = rng.standard_normal((b, ni)), rng.standard_normal((ni, no)), rng.standard_normal((b, no))
+        Y = ly.fc_forward(X, W, relu)
+        np.testing.assert_allclose(Y, lp.fc_forward(X, W, relu), rtol=0, atol=1e-12)
+        dX, dW = ly.fc_backward(dY, X, W, Y, relu)
+        pX, pW = lp.fc_backward(dY, X, W, Y, relu)
+        np.testing.assert_allclose(dX, pX, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(dW, pW, rtol=0, atol=1e-12)
+    for (N, C, K, H, Wd, R, S, pad) in [(2, 3, 4, 5, 6, 3, 3, 1), (3, 2, 5, 4, 4, 1, 1, 0), (2, 4, 3, 7, 5, 5, 3, 2),
+                                        (1, 2, 2, 6, 6, 3, 3, 0)]:
+        X, W = rng.standard_normal((N, C, H, Wd)), rng.standard_normal((K, C, R, S))
+        Y = ly.conv_forward(X, W, pad)
+        np.testing.assert_allclose(Y, lp.conv_forward(X, W, pad), rtol=0, atol=1e-12)
+        dY = rng.standard_normal(Y.shape)
+        if R == S:      # the numpy data gradient takes one padding for both image dimensions
+            np.testing.assert_allclose(ly.conv_dgrad(dY, W, pad, H, Wd), lp.conv_dgrad(dY, W, pad, H, Wd), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(ly.conv_wgrad(X, dY, pad, R, S), lp.conv_wgrad(X, dY, pad, R, S), rtol=0, atol=1e-12)
