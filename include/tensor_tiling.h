@@ -21,7 +21,9 @@
  *  - every call returns a tt_status; nothing throws across the ABI.  Argument and
  *    feasibility errors are detected on the host before anything is launched.
  *    Only even cuts exist (Sec. 4.1): an extent that does not divide gives TT_EINFEASIBLE.
- *  - calls are re-entrant; there is no global mutable state.
+ *  - calls are re-entrant.  The library keeps no mutable state between calls except guarded, once-only set-up
+ *    (which kernels have had their LDS limit raised; the address of tt_fc_forward_static's scratch array per device),
+ *    and it reads no environment variable: every launch decision is a function of the call's arguments.
  */
 #ifndef TENSOR_TILING_H
 #define TENSOR_TILING_H

@@ -16,6 +16,7 @@
 #include "tt_device.h"
 #include "gemm_core.h"
 #include "tt_internal.h"
+#include "launch_util.h"
 
 namespace tt {
 namespace {
@@ -273,8 +274,7 @@ __global__ __launch_bounds__(256) void filter_flip_tiled_kernel(const FlipParams
 
 template <typename Kern> tt_status launch(Kern kern, size_t smem, ConvParams &p, int BM, int BN, int threads, int count, hipStream_t s)
 {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-        return TT_EDEVICE;
+    if (ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem) != TT_OK) return TT_EDEVICE;
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     const int64_t total = (int64_t)p.tiles_m * p.tiles_n * count;
@@ -289,7 +289,7 @@ template <typename Kern> tt_status launch(Kern kern, size_t smem, ConvParams &p,
 // or 128 x 128 with four waves.  TT_CONV_TILE=0|1|2 overrides (tuning aid).
 int conv_tile(int64_t M, int64_t N, int count)
 {
-    static const int forced = [] { const char *e = std::getenv("TT_CONV_TILE"); return e ? std::atoi(e) : -1; }();
+    const int forced = tuning_int("TT_CONV_TILE", -1);
     if (forced >= 0 && forced <= 2) return forced;
     const int64_t big = ((M + 255) / 256) * ((N + 255) / 256) * count;
     if (M > 128 && N > 128 && big >= 128) return 2;
@@ -327,7 +327,7 @@ template <bool OUT_BF16> tt_status launch_wgrad(ConvParams &p, int count, hipStr
     const bool kmask = p.K % core::BK != 0;
     // the pixel-walking gather of the weight gradient measured slower with the eight-wave tile: keep four waves
     int tile = conv_tile(p.M, p.N, count);
-    if (tile == 2 && !std::getenv("TT_CONV_TILE")) tile = 0;
+    if (tile == 2 && tuning_int("TT_CONV_TILE", -1) < 0) tile = 0;
     if (tile == 2) {
         constexpr size_t sm = core::smem_bytes<256, 256>();
         return kmask ? launch(conv_wgrad_kernel<256, 256, 4, 1, true, OUT_BF16>, sm, p, 256, 256, 512, count, s)
@@ -399,7 +399,7 @@ tt_status launch_conv(int op, int count, const void *const *A, const void *const
     ProfileScope scope(stream, kclass, count, M, N, K, bytes * (uint64_t)count,
                        2ull * (uint64_t)M * (uint64_t)N * (uint64_t)K * (uint64_t)count);
     if (op == TT_OP_FWD) return obf ? launch_gather_a<0, true>(p, count, s) : launch_gather_a<0, false>(p, count, s);
-    if (op == TT_OP_DGRAD && flip_ws && R == S && pad <= R - 1 && !std::getenv("TT_CONV_DGRAD_DIRECT")) {
+    if (op == TT_OP_DGRAD && flip_ws && R == S && pad <= R - 1 && !tuning_int("TT_CONV_DGRAD_DIRECT", 0)) {
         // as a forward convolution of dY (P x Q images, Ks channels) with the flipped filters, padding R - 1 - pad;
         // M, N, K of the implicit GEMM are the same
         FlipParams f;

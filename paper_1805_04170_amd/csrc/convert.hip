@@ -10,6 +10,8 @@
 #include <cstdint>
 #include <cstdlib>
 #include "tt_device.h"
+#include "tt_bf16.h"
+#include "launch_util.h"
 #include "tt_internal.h"
 
 namespace tt {
@@ -176,21 +178,6 @@ struct ReduceParams {
     uint32_t relu;
     uint32_t piece_rows, piece_cv, pieces_c, pieces, tiles_per_piece, piece_vecs, step_rows, step_cv;
 };
-
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u; // NaN stays NaN
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                  // round to nearest even
-}
-
-// two floats -> packed bf16 pair (low half = a), round to nearest even (v_cvt_pk_bf16_f32)
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
-{
-    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-    bf16x2_t v = {(__bf16)a, (__bf16)b};
-    return *reinterpret_cast<uint32_t *>(&v);
-}
 
 template <int EV> struct FVec;
 template <> struct FVec<4> { using type = f32x4; };
@@ -384,10 +371,7 @@ tt_status launch_convert(void *const *dst, const uint8_t *Bl, const void *const 
     const int64_t piece_cv = piece_cols / vec_elems;
     const uint64_t unique_vecs = (uint64_t)rows * (uint64_t)(cols / vec_elems);
     p.unroll = (uint32_t)pick_unroll(unique_vecs);
-    if (const char *e = std::getenv("TT_CVT_U")) { // tuning aid: 1, 2, 4, 8, 16
-        const int u = std::atoi(e);
-        if (u == 1 || u == 2 || u == 4 || u == 8 || u == 16) p.unroll = (uint32_t)u;
-    }
+    if (const int u = tuning_int("TT_CVT_U", 0); u == 1 || u == 2 || u == 4 || u == 8 || u == 16) p.unroll = (uint32_t)u;
     p.piece_rows = (uint32_t)piece_rows;
     p.piece_cv = (uint32_t)piece_cv;
     p.pieces_c = (uint32_t)(B.scols / piece_cols);
@@ -434,7 +418,7 @@ template <int EV, bool OUT_BF16> static tt_status launch_reduce_e(const ReducePa
 tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, const float *const *partials,
                         const uint8_t *zl, int k, int64_t rows, int64_t cols, int act, int ksplit, void *stream)
 {
-    if (ksplit < 1 || (ksplit << k) > kMaxShards) return TT_EINVAL;
+    if (ksplit < 1 || (ksplit & (ksplit - 1)) != 0 || (ksplit << k) > kMaxShards) return TT_EINVAL; // the partial count must be a power of two
     if (!dst || !partials || !valid_k(k) || rows < 0 || cols < 0) return TT_EINVAL;
     if (rows == 0 || cols == 0) return TT_OK;
     if (out_dtype != TT_F32 && out_dtype != TT_BF16) return TT_EINVAL;
@@ -482,10 +466,7 @@ tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, cons
     int unroll = 1;
     if (unique_vecs >= (uint64_t)1 << 20) unroll = n_part >= 8 ? 1 : (n_part == 4 ? 4 : 2);
     else if (unique_vecs >= (uint64_t)1 << 17) unroll = 2;
-    if (const char *e = std::getenv("TT_RED_U")) { // tuning aid: 1, 2, 4
-        const int u = std::atoi(e);
-        if (u == 1 || u == 2 || u == 4) unroll = u;
-    }
+    if (const int u = tuning_int("TT_RED_U", 0); u == 1 || u == 2 || u == 4) unroll = u;
     p.piece_rows = (uint32_t)piece_rows;
     p.piece_cv = (uint32_t)piece_cv;
     p.pieces_c = (uint32_t)(B.scols / piece_cols);

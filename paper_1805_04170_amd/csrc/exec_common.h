@@ -140,10 +140,12 @@ inline bool ksplit_fits(int64_t K, int s)
 inline int pick_ksplit(int64_t M, int64_t N, int64_t K, int count, int dtype, bool a_contig8, bool b_contig8)
 {
     if (dtype != TT_BF16 || !a_contig8 || !b_contig8) return 1;
-    if (const char *e = std::getenv("TT_KSPLIT")) { // tuning aid
+#ifdef TT_TUNING
+    if (const char *e = std::getenv("TT_KSPLIT")) { // development builds only; powers of two, as the reduction assumes
         const int f = std::atoi(e);
-        if (f >= 1 && K / f >= 256 && count * f <= kMaxShards && ksplit_fits(K, f)) return f;
+        if (f >= 1 && (f & (f - 1)) == 0 && K / f >= 256 && count * f <= kMaxShards && ksplit_fits(K, f)) return f;
     }
+#endif
     const int64_t blocks = ((M + 255) / 256) * ((N + 255) / 256) * count; // 256 x 256 tiles, one per CU
     // chunks stay at least 512 deep, except where the launch would otherwise occupy under a quarter of the CUs (the
     // 1000-wide last layer): there chunks down to 192 still pay for the extra partial sums

@@ -10,6 +10,7 @@
 #include "gemm_core.h"
 #include "gemm_core2.h"
 #include "tt_internal.h"
+#include "launch_util.h"
 
 namespace tt {
 namespace {
@@ -88,12 +89,7 @@ __global__ __launch_bounds__(core2::kThreads2, 2) void gemm_bf16_v2_kernel(const
 template <bool A_KC, bool B_KC, bool OUT_BF16, bool VEC> tt_status launch_v2(GemmParams &p, int count, hipStream_t s)
 {
     auto kern = gemm_bf16_v2_kernel<A_KC, B_KC, OUT_BF16, VEC>;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)core2::kSmemBytes) != hipSuccess)
-            return TT_EDEVICE;
-        configured = true;
-    }
+    if (ensure_dynamic_lds(reinterpret_cast<const void *>(kern), core2::kSmemBytes) != TT_OK) return TT_EDEVICE;
     p.tiles_m = (p.M + 255) / 256;
     p.tiles_n = (p.N + 255) / 256;
     int64_t total = (int64_t)p.tiles_m * p.tiles_n * count * p.ksplit;
@@ -183,12 +179,7 @@ tt_status launch_mfma_cfg(GemmParams &p, int count, hipStream_t s)
 {
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, DEPTH, KMASK, A_KC, B_KC, OUT_BF16, VEC>;
     constexpr size_t smem = core::smem_bytes<BM, BN, DEPTH>();
-    static bool configured = false; // per instantiation; setting the attribute twice is harmless
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return TT_EDEVICE;
-        configured = true;
-    }
+    if (ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem) != TT_OK) return TT_EDEVICE;
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     int64_t total = (int64_t)p.tiles_m * p.tiles_n * count * p.ksplit;
@@ -209,7 +200,7 @@ tt_status launch_mfma_cfg(GemmParams &p, int count, hipStream_t s)
 //   8: 256 x 256, eight waves, second engine (gemm_core2.h): tiles loaded straight into LDS.
 int pick_tile(int64_t M, int64_t N, int64_t K, int count)
 {
-    static const int forced = [] { const char *e = std::getenv("TT_GEMM_TILE"); return e ? std::atoi(e) : -1; }();
+    const int forced = tuning_int("TT_GEMM_TILE", -1);
     if ((forced >= 0 && forced <= 5) || forced == 8) return forced;
     const int64_t big = ((M + 255) / 256) * ((N + 255) / 256) * count;
     if (M > 128 && N > 128 && big >= 128) return 5;
@@ -233,7 +224,7 @@ template <bool A_KC, bool B_KC, bool OUT_BF16, bool VEC> tt_status launch_mfma_k
     // every layout but NN (A K-contiguous, B row-contiguous), which stays on the register-staged engine.
     const int tile = pick_tile(p.M, p.N, p.ksplit > 1 ? p.kchunk : p.K, count * p.ksplit);
     const bool nn = A_KC && !B_KC;
-    if ((tile == 8 || (tile == 5 && !nn && !std::getenv("TT_GEMM_TILE"))) && p.M >= 8 && p.N >= 8)
+    if ((tile == 8 || (tile == 5 && !nn && tuning_int("TT_GEMM_TILE", -1) < 0)) && p.M >= 8 && p.N >= 8)
         return launch_v2<A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
     return p.K % core::BK ? launch_mfma_tile<true, A_KC, B_KC, OUT_BF16, VEC>(p, count, s)
                           : launch_mfma_tile<false, A_KC, B_KC, OUT_BF16, VEC>(p, count, s);
@@ -322,8 +313,16 @@ tt_status launch_gemm(int count, const void *const *A, const void *const *B, voi
         //  - large launches with more than one row of tiles: the persistent pipelined engine;
         //  - of the skinny batch-256 products of the wide layers (one row of tiles, bound by the weight stream) the NN
         //    layout measured 6 % faster on the persistent engine, the others equal or faster on the direct-to-LDS engine.
-        static const int engine = [] { const char *e = std::getenv("TT_GEMM_ENGINE"); return e ? std::atoi(e) : 0; }();
+        const int engine = tuning_int("TT_GEMM_ENGINE", 0);
         const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * count * ksplit;
+        //  - weight-gradient shaped products (both operands stored with K as the slow dimension, K = 128 or 256, a bf16
+        //    result large enough to give every resident workgroup several 256 x 64 units): the engine that keeps the left
+        //    operand's panel in registers and is bound by writing the result (gemm_core5.h)
+        if ((engine == 5 || engine == 0) && !a_kc && !b_kc && ksplit == 1 && out_dtype == TT_BF16 && vec && in_dtype == TT_BF16 &&
+            (engine == 5 || ((M + 255) / 256) * (N / 64) * count >= 4 * 512)) {
+            const tt_status st = launch_gemm_v5(count, A, B, C, M, N, K, a_contig, b_contig, N, act == TT_ACT_RELU, stream);
+            if (st != TT_EUNSUPPORTED) return st;
+        }
         if (engine == 4 || (engine == 0 && big_tiles < 200 && M > 128 && N >= 256)) {
             const tt_status st = launch_gemm_v4(count, A, B, C, M, N, K, a_contig, b_contig, N, a_kc, b_kc, out_dtype,
                                                 act == TT_ACT_RELU, vec, ksplit, kchunk, stream);

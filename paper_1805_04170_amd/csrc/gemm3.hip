@@ -6,8 +6,10 @@
 #include <cstdlib>
 #include "gemm_core3.h"
 #include "gemm_core4.h"
+#include "gemm_core5.h"
 #include "gemm3_params.h"
 #include "tt_internal.h"
+#include "launch_util.h"
 
 namespace tt {
 namespace {
@@ -43,12 +45,7 @@ __global__ __launch_bounds__(core4::kThreads4, 2) void gemm_bf16_v4_kernel(const
 template <bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED> tt_status launch_cfg4(core3::Params3 &p, hipStream_t s)
 {
     auto kern = gemm_bf16_v4_kernel<A_KC, B_KC, OUT_BF16, STAGED>;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)core4::kSmem4) != hipSuccess)
-            return TT_EDEVICE;
-        configured = true;
-    }
+    if (ensure_dynamic_lds(reinterpret_cast<const void *>(kern), core4::kSmem4) != TT_OK) return TT_EDEVICE;
     hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * core::kXcds), dim3(core4::kThreads4), core4::kSmem4, s, p);
     return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
 }
@@ -58,6 +55,22 @@ template <bool A_KC, bool B_KC> tt_status launch_layout4(core3::Params3 &p, int 
     const bool bf = out_dtype == TT_BF16;
     if (bf && vec) return launch_cfg4<A_KC, B_KC, true, true>(p, s);
     return bf ? launch_cfg4<A_KC, B_KC, true, false>(p, s) : launch_cfg4<A_KC, B_KC, false, false>(p, s);
+}
+
+// short-K products with the left operand's panel held in registers (gemm_core5.h); two workgroups per CU
+template <int KT, bool NTS> __global__ __launch_bounds__(core5::kThreads5, 2) void gemm_bf16_v5_kernel(const core5::Params5 p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem3[];
+    core5::run_panels<KT, NTS>(p, smem3);
+}
+
+template <int KT, bool NTS> tt_status launch_cfg5(core5::Params5 &p, hipStream_t s)
+{
+    auto kern = gemm_bf16_v5_kernel<KT, NTS>;
+    constexpr size_t smem = core5::smem_bytes5<KT>();
+    if (ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem) != TT_OK) return TT_EDEVICE;
+    hipLaunchKernelGGL(kern, dim3((uint32_t)p.grid), dim3(core5::kThreads5), smem, s, p);
+    return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
 }
 
 int cu_count()
@@ -76,12 +89,7 @@ tt_status launch_cfg(core3::Params3 &p, hipStream_t s)
 {
     auto kern = gemm_bf16_v3_kernel<BK, NS, A_KC, B_KC, OUT_BF16, STAGED, ILV>;
     constexpr size_t smem = core3::smem_bytes3<BK, NS, STAGED>();
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return TT_EDEVICE;
-        configured = true;
-    }
+    if (ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem) != TT_OK) return TT_EDEVICE;
     hipLaunchKernelGGL(kern, dim3((uint32_t)p.wg_per_xcd * core::kXcds), dim3(core3::kThreads3), smem, s, p);
     return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
 }
@@ -90,7 +98,7 @@ template <bool A_KC, bool B_KC> tt_status launch_layout(core3::Params3 &p, int o
 {
     // bf16 results with 16-byte rows: staged epilogue (ring + 18 KB).  Everything else (fp32 partial sums, odd pitches)
     // stores element-wise from registers.  Ring: two stages of 64 (TT_V3_RING=324: four stages of 32; tuning aid).
-    static const int ring = [] { const char *e = std::getenv("TT_V3_RING"); return e ? std::atoi(e) : 642; }();
+    const int ring = tuning_int("TT_V3_RING", 642);
     const bool bf = out_dtype == TT_BF16;
     if (ring == 324) {
         if (bf && vec) return launch_cfg<32, 4, A_KC, B_KC, true, true>(p, s);
@@ -99,7 +107,7 @@ template <bool A_KC, bool B_KC> tt_status launch_layout(core3::Params3 &p, int o
     // short K loops (the weight gradients at batch 256): loads issued between the k-steps, see run_tiles
     // Loads issued between the k-steps (see run_tiles) measured faster for the products with bf16 results (the weight
     // gradients: short K loops) ...  (TT_V3_ILV=0: never; tuning aid.)
-    static const bool ilv = [] { const char *e = std::getenv("TT_V3_ILV"); return !e || std::atoi(e) != 0; }();
+    const bool ilv = tuning_int("TT_V3_ILV", 1) != 0;
     if (bf && vec) return ilv ? launch_cfg<64, 2, A_KC, B_KC, true, true, true>(p, s) : launch_cfg<64, 2, A_KC, B_KC, true, true>(p, s);
     // ... and, among the products that write fp32 partial sums, for the NN layout (B read with LDS transpose reads)
     if constexpr (A_KC && !B_KC)
@@ -108,6 +116,37 @@ template <bool A_KC, bool B_KC> tt_status launch_layout(core3::Params3 &p, int o
 }
 
 } // namespace
+
+// C_s = A_s^T B_s, A_s stored K x M, B_s stored K x N, K = 128 or 256, bf16 result with 16-byte rows.
+// TT_EUNSUPPORTED when the engine does not take the product.
+tt_status launch_gemm_v5(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
+                         int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int relu, void *stream)
+{
+    if ((K != 128 && K != 256) || N < core5::NT5 || N % core5::NT5 || M < 8 || M % 8 || count < 1 || count > 64)
+        return TT_EUNSUPPORTED;
+    if (lda % 8 || ldb % 8 || ldc % 8 || lda < M || ldb < N || ldc < N) return TT_EUNSUPPORTED; // 16-byte chunks and rows
+    if (K * lda >= (int64_t(1) << 30) || K * ldb >= (int64_t(1) << 30)) return TT_EUNSUPPORTED; // 32-bit byte offsets
+    core5::Params5 p;
+    for (int i = 0; i < 64; ++i) {
+        p.A[i] = i < count ? A[i] : nullptr;
+        p.B[i] = i < count ? B[i] : nullptr;
+        p.C[i] = i < count ? C[i] : nullptr;
+    }
+    p.M = (int32_t)M; p.N = (int32_t)N;
+    p.lda = (int32_t)lda; p.ldb = (int32_t)ldb; p.ldc = (int32_t)ldc;
+    p.panels = (int32_t)((M + core5::PM5 - 1) / core5::PM5);
+    p.ntiles = (int32_t)(N / core5::NT5);
+    const int64_t total = (int64_t)count * p.panels * p.ntiles;
+    if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
+    p.total = (int32_t)total;
+    const int64_t resident = 2 * (int64_t)cu_count(); // two workgroups per CU
+    p.grid = (int32_t)(total < resident ? total : resident);
+    p.relu = relu;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const bool nts = tuning_int("TT_V5_NT", 1) != 0;
+    if (K == 256) return nts ? launch_cfg5<16, true>(p, s) : launch_cfg5<16, false>(p, s);
+    return nts ? launch_cfg5<8, true>(p, s) : launch_cfg5<8, false>(p, s);
+}
 
 tt_status launch_gemm_v4(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
                          int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool a_kc, bool b_kc, int out_dtype, int relu,

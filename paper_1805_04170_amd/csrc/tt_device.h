@@ -36,6 +36,15 @@ __device__ __forceinline__ void lds_dma16(uint32_t lane_offset, uint64_t uniform
     asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_offset), "s"(uniform_base), "{m0}"(lds_wave_addr) : "memory");
 }
 
+// 16-byte global store.  A named function because kernels that leave stores in flight over a wait count them
+// (s_waitcnt vmcnt(n) counts a wave's loads and stores alike, in issue order), and the host emulation counts them here.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+template <bool NON_TEMPORAL> __device__ __forceinline__ void store16(void *p, u32x4_t v)
+{
+    if constexpr (NON_TEMPORAL) __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(p));
+    else *reinterpret_cast<u32x4_t *>(p) = v;
+}
+
 // LDS transpose read: 8 bytes per lane at a, handed out transposed over each group of 16 lanes (four bf16 per lane)
 __device__ __forceinline__ s16x4 lds_read_tr16_b64(const char *a)
 {

@@ -120,6 +120,8 @@ tt_status launch_gemm_v3(int count, const void *const *A, const void *const *B, 
                          bool vec, int ksplit, int64_t kchunk, void *stream);
 
 // Same contract for the 256 x 128 engine with two workgroups per CU (gemm_core4.h); K a multiple of 32.
+tt_status launch_gemm_v5(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
+                         int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int relu, void *stream);
 tt_status launch_gemm_v4(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
                          int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool a_kc, bool b_kc, int out_dtype, int relu,
                          bool vec, int ksplit, int64_t kchunk, void *stream);

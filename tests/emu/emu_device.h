@@ -172,6 +172,16 @@ inline void lds_dma16(uint32_t lane_offset, uint64_t uniform_base, uint32_t lds_
     land16(reinterpret_cast<const char *>(uniform_base) + lane_offset, lds_wave_addr);
 }
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+template <bool NON_TEMPORAL> inline void store16(void *p, u32x4_t v)
+{
+    if ((uintptr_t)p % 16) fail("misaligned 16-byte global store", p, 16);
+    std::memcpy(p, &v, 16);
+#ifdef TT_EMU_LOCKSTEP
+    emu::issue_counted_store();
+#endif
+}
+
 inline s16x4 lds_read_tr16_b64(const char *a)
 {
     if (a < g_lds || a + 8 > g_lds + g_lds_bytes) fail("LDS transpose read outside LDS", a, 8);

@@ -11,8 +11,9 @@
 //     (the 4 x 16 block of 16-bit values the group addressed, transposed).
 // Global -> LDS loads land late: a lane's loads stay pending, in order, until a wait count of that lane lets them
 // through (s_waitcnt vmcnt(n) lands all but the newest n), which is the latest the hardware may deliver them; its
-// stores and register loads, which the hardware counts as well, are not seen here, so the model never lands more than
-// the hardware has.  A kernel that reads a stage before waiting for it therefore reads stale data here, and one that
+// register loads, which the hardware counts as well, are not seen here, so the model never lands more than the hardware
+// has; stores are counted where a kernel issues them through dev::store16 (kernels that keep stores in flight over a
+// wait and subtract them in its count), and not seen otherwise.  A kernel that reads a stage before waiting for it therefore reads stale data here, and one that
 // ends with loads still in flight towards LDS is reported.  With this the kernels produce values, which the tests
 // compare with the oracle's.
 #pragma once
@@ -79,6 +80,9 @@ template <class F> inline void wave_collective(int kind, F &&complete)
 inline void wave_sync() { wave_collective(1, [](WaveState &) {}); }
 
 inline void issue_lds_load(char *dst, const char *src) { g_block.pending[g_block.cur].push_back({dst, src}); }
+// a global store that the kernel leaves in flight over a wait: it takes a place in the lane's queue of vector-memory
+// operations (its data is written at once: nothing here reads it back)
+inline void issue_counted_store() { g_block.pending[g_block.cur].push_back({nullptr, nullptr}); }
 
 // s_waitcnt with the gfx9 encoding of its operand: vmcnt in bits 3:0 and 15:14
 inline void wait_counts(unsigned imm)
@@ -89,7 +93,7 @@ inline void wait_counts(unsigned imm)
     const unsigned vmcnt = ((imm & 15u) | (((imm >> 14) & 3u) << 4)) + slack;
     std::deque<PendingLoad> &q = g_block.pending[g_block.cur];
     while (q.size() > vmcnt) {
-        std::memcpy(q.front().dst, q.front().src, 16);
+        if (q.front().dst) std::memcpy(q.front().dst, q.front().src, 16);
         q.pop_front();
     }
     wave_sync();
@@ -159,7 +163,8 @@ inline void trampoline()
     Block &b = g_block;
     b.body();
     const int t = b.cur;
-    if (!b.pending[t].empty()) die("the kernel ended with global -> LDS loads still in flight");
+    for (const PendingLoad &l : b.pending[t])
+        if (l.dst) die("the kernel ended with global -> LDS loads still in flight");
     b.done[t] = 1;
     --b.live;
     WaveState &w = b.waves[t / kWave];

@@ -11,7 +11,8 @@ CLANG = shutil.which("clang++", path="/opt/rocm/llvm/bin") or shutil.which("clan
 EMU = os.path.join(ROOT, "tests", "emu")
 CSRC = os.path.join(ROOT, "paper_1805_04170_amd", "csrc")
 INCLUDES = ["-I" + EMU, "-I" + CSRC, "-I" + os.path.join(ROOT, "include")]
-BASE = ["-std=c++17", "-x", "c++"]
+# -DTT_TUNING: the environment overrides of the launch heuristics (absent from the product build) let a test force an engine
+BASE = ["-std=c++17", "-x", "c++", "-DTT_TUNING"]
 ASAN = ["-fsanitize=address", "-fno-omit-frame-pointer"]
 # -O1 where the checked launches are long (unoptimised code runs them several times slower), -O0 where the optimiser
 # would need minutes (all four engines' instantiations in one unit)

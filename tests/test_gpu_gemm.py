@@ -105,6 +105,14 @@ def test_bf16_two_workgroups_per_cu_engine(ta, tb, out_dt):
     check(1, 136, 264, 32, ta, tb, "bf16", out_dt, False, 47)
 
 
+@pytest.mark.parametrize("K", [256, 128])
+def test_bf16_panel_in_registers_engine(K):
+    # weight-gradient shaped products (both operands stored K-major, K = 128 / 256, large bf16 result): the engine that
+    # keeps the left operand's panel in registers; 8 shards x 5 panels (the last with 8 of 256 rows) x 52 column tiles
+    # on 512 resident workgroups, so runs change panel and shard mid-way
+    check(8, 1032, 3328, K, 1, 0, "bf16", "bf16", K == 128, 48)
+
+
 def test_k_zero_and_empty():
     C = [torch.full((8, 8), 5.0, dtype=torch.float32, device=DEV)]
     A = [torch.zeros((8, 1), dtype=torch.bfloat16, device=DEV)]

@@ -227,7 +227,9 @@ def emu_shard_gemm(emulators):
 # then the number of threads the launch must have run (which names the engine: workgroups x their size)
 SHARD_CASES = [
     ((8, 256, 512, 4096, 0, 0, 1, 1, 1, 1), 32 * 256),      # hidden layer forward at batch 256: 256 x 128 tiles, two workgroups per CU
-    ((8, 3136, 4096, 256, 1, 0, 1, 1, 0, 1), 256 * 512),    # VGG-16 first weight gradient: the persistent engine, one workgroup per CU
+    ((8, 3136, 4096, 256, 1, 0, 1, 1, 0, 1), 512 * 256),    # VGG-16 first weight gradient: the panel-in-registers engine, two workgroups of four waves per CU
+    ((8, 1152, 4096, 128, 1, 0, 1, 1, 0, 1), 512 * 256),    # the same engine at a per-shard batch of 128
+    ((8, 3136, 4096, 192, 1, 0, 1, 1, 0, 1), 256 * 512),    # a batch it does not take: the persistent engine, one workgroup per CU
     ((16, 256, 4096, 512, 0, 1, 1, 0, 0, 1), 256 * 512),    # skinny data gradient: 256 x 256 tiles loaded straight into LDS
     ((16, 256, 2048, 512, 0, 0, 1, 0, 0, 1), 128 * 512),    # skinny NN product: the persistent engine, 128 tiles
     ((4, 256, 128, 1024, 0, 0, 1, 1, 0, 1), 8 * 256),       # one narrow column of tiles: register-staged 256 x 128

@@ -96,6 +96,30 @@ def test_persistent_engine_values_as_the_library_chooses_it(lockstep_gemm, tmp_p
     assert int(out.split()[3]) == 240 * 512
 
 
+@pytest.mark.parametrize("relu", [False, True])
+def test_panel_in_registers_engine_values(lockstep_gemm, tmp_path, relu):
+    # the short-K engine of the weight gradients (left operand's panel in registers, stores left in flight over the next
+    # unit's wait), forced on small products on a stand-in device of one CU (two workgroups): K = 256, two shards of two
+    # panels (the second with 72 of its 256 rows: one wave full, one partly masked, two idle) by three column tiles, so
+    # every workgroup changes panel and runs units behind stores that are still counted; then K = 128
+    env = {"EMU_CUS": "1", "TT_GEMM_ENGINE": "5"}
+    out = check(lockstep_gemm, str(tmp_path), 2, 328, 192, 256, 1, 0, "bf16", "bf16", relu, 81, env=env)
+    assert int(out.split()[3]) == 2 * 256
+    check(lockstep_gemm, str(tmp_path), 1, 264, 128, 128, 1, 0, "bf16", "bf16", relu, 82, env=env)
+    # more workgroups than units to spare: runs of one unit, and a run that ends inside a panel
+    check(lockstep_gemm, str(tmp_path), 1, 512, 320, 256, 1, 0, "bf16", "bf16", relu, 83, env={"EMU_CUS": "3", "TT_GEMM_ENGINE": "5"})
+
+
+def test_panel_in_registers_engine_counts_its_stores(lockstep_gemm, tmp_path):
+    # its waits leave the previous unit's eight stores in flight; letting two more operations stay in flight than it
+    # asks for must give stale operand tiles, and the order in which waves run must not matter
+    env = {"EMU_CUS": "1", "TT_GEMM_ENGINE": "5"}
+    shape = (1, 256, 512, 256, 1, 0, "bf16", "bf16", False, 84)
+    check(lockstep_gemm, str(tmp_path), *shape, env=dict(env, EMU_ORDER="reverse"))
+    with pytest.raises(AssertionError):
+        check(lockstep_gemm, str(tmp_path), *shape, env=dict(env, EMU_VMCNT_SLACK="2"))
+
+
 @pytest.mark.parametrize("ta,tb", LAYOUTS)
 def test_direct_to_lds_engine_values(lockstep_gemm, tmp_path, ta, tb):
     # the eight-wave 256 x 256 engine that loads tiles straight into LDS, forced by the tuning switches on small
