@@ -22,14 +22,21 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM traffic per launch (read + write bytes) of the large shard products from the rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs summarised in profiles/vgg16_fc_step_hbm_traffic_pmc.txt (counters scaled by what the same counters
-# read for the W_1 retile, a copy of known size).  Keyed by workload, kernel and per-shard M x N x K; None if not measured.
-MEASURED_TRAFFIC_BYTES = {
-    "vgg16_fc:gemm_tn:3136x4096x256": int((30.10 + 205.61) * 1e6),
-    "vgg16_fc:gemm_nn:256x4096x3136": int((218.66 + 67.11) * 1e6),
-    "vgg16_fc:gemm_nt:256x3136x4096": int((222.41 + 51.44) * 1e6),
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def measured_traffic(workload, rec):
+    """HBM bytes per launch (read + written) of one launch shape, as the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+    this workload measured them (profiles/hbm_traffic.json, written by profile_summary.py from those runs; the counters
+    are scaled by what they read for a retile of known size).  None if that shape was not measured."""
+    try:
+        with open(TRAFFIC_FILE) as fh:
+            table = json.load(fh)
+    except (OSError, ValueError):
+        return None
+    key = "%s count=%d %dx%dx%d" % (rec["kernel"], rec["count"], rec["d0"], rec["d1"], rec["d2"])
+    hit = table.get(workload, {}).get("launches", {}).get(key)
+    return None if hit is None else int(hit["read_bytes"] + hit["write_bytes"])
 
 
 def parse():
@@ -38,9 +45,15 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vgg16_fc",
-                    choices=["vgg16_fc", "alexnet_fc", "wide_mlp", "tiny_mlp", "vgg16_conv4", "shape_study"])
+                    choices=["vgg16_fc", "alexnet_fc", "wide_mlp", "wide_mlp_f3", "tiny_mlp", "vgg16_conv4", "shape_study"])
     ap.add_argument("--conv-split", default="planner", choices=["planner", "batch", "out_channel"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="measure only --workload; default: the headline workload plus one block per other configuration")
+    ap.add_argument("--other-steps", type=int, default=10, help="timed steps of each of the other configurations")
+    ap.add_argument("--launch-log", default=None,
+                    help="write the launches of one step (kernel, shape, algorithmic bytes and flops, in launch order) to "
+                         "this JSON file: what profile_summary.py needs to attribute profiler dispatches to launches")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
     ap.add_argument("--overlap", action="store_true",
                     help="weight-gradient products on a second stream (tt_fc_backward_overlapped); default: one stream, "
@@ -191,6 +204,7 @@ def block_of(t, s):
 
 
 def aggregate(records):
+    """launch shapes of a profiled pass, most time first (time summed over the launches of a shape)"""
     agg = {}
     for r in records:
         key = (r["kernel"], r["count"], r["d0"], r["d1"], r["d2"])
@@ -259,12 +273,13 @@ def counted_cross_shard_elems(tt, cfg, chain, is_conv):
     return tt.tt_fc_chain_cross_elems(chain.layers, cfg.batch, cfg.k, chain.tx, chain.tg, chain.tw, chain.forms)
 
 
-def shape_study(args, tt, torch):
+def shape_study(args, tt, torch, steps=None):
     """Sec. 6.3 / Table 1 of the paper asked again on one MI355X: a 4-layer MLP with 8K x 8K weights, one step untiled
     (k = 0) against the same step cut into 8 shards under the planner's tiling, all shards on this GPU.  Same flops."""
     from synthetic.configs import FcChain
     paper = {512: (0.31, 0.19), 1024: (0.56, 0.39), 2048: (1.13, 0.73)}  # seconds per batch, the paper's GPU and fp32
     rows = []
+    steps = steps or args.steps
     for b in (512, 1024, 2048):
         res = {}
         for k in (0, 3):
@@ -279,10 +294,10 @@ def shape_study(args, tt, torch):
             graph.replay()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(args.steps):
+            for _ in range(steps):
                 graph.replay()
             torch.cuda.synchronize()
-            ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            ms = (time.perf_counter() - t0) * 1e3 / steps
             res[k] = dict(ms=ms, tflops=cfg.flops() / (ms * 1e-3) / 1e12, tiling_w=chain.tw, tiling_x=chain.tx,
                           plan_cost_elems=chain.plan_cost)
             del chain, graph
@@ -292,48 +307,76 @@ def shape_study(args, tt, torch):
                      "tiled_over_untiled_time": res[3]["ms"] / res[0]["ms"], "tiling_w": res[3]["tiling_w"],
                      "tiling_x": res[3]["tiling_x"], "paper_untiled_s": paper[b][0], "paper_tiled_s": paper[b][1],
                      "paper_tiled_over_untiled_time": paper[b][1] / paper[b][0]})
-    print(json.dumps({"metric": "fwd+bwd time per batch of a 4-layer 8K x 8K MLP: untiled vs cut into 8 shards on one GPU",
-                      "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16",
-                      "data": "synthetic", "config": {"workload": "shape_study: 8192->8192 x4, k=0 vs k=3 planner EXACT"},
-                      "rows": rows}))
+    return {"metric": "fwd+bwd time per batch of a 4-layer 8K x 8K MLP: untiled vs cut into 8 shards on one GPU",
+            "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": args.warmup, "dtype": "bf16",
+            "data": "synthetic", "config": {"workload": "shape_study: 8192->8192 x4, k=0 vs k=3 planner EXACT"},
+            "rows": rows}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (all 2^k shards are simulated in one HBM); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-    import torch
-    import paper_1805_04170_amd as tt
+def build_workload(name, args, tt, torch, conv_split):
+    """(cfg, device state, description of the tiling) of one workload"""
     from synthetic import CONFIGS
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
-    tt.binding.lib()
-    torch.cuda.set_device(0)
-    if args.workload == "shape_study":
-        shape_study(args, tt, torch)
-        return
-    cfg = CONFIGS[args.workload]
-    is_conv = not hasattr(cfg, "widths")
-    if is_conv:
-        chain = ConvLayerBench(cfg, tt, torch, args.conv_split)
-    elif args.workload == "wide_mlp":
+    cfg = CONFIGS["wide_mlp" if name == "wide_mlp_f3" else name]
+    if not hasattr(cfg, "widths"):
+        return cfg, ConvLayerBench(cfg, tt, torch, conv_split), "%s split" % conv_split
+    L = cfg.n_layers
+    if name == "wide_mlp":
         # forced tiling: every tensor stored as a 4 x 4 grid; forward / dgrad split the reduction dimension twice
-        L = cfg.n_layers
-        chain = Chain(cfg, tt, torch, tilings=(["RRCC"] * (L + 1), ["RRCC"] * (L + 1), ["RRCC"] * L,
-                                               [["3322", "2233", "1122"]] * L))
-    else:
-        chain = Chain(cfg, tt, torch)
-    K, W = args.steps, args.warmup
+        return cfg, Chain(cfg, tt, torch, tilings=(["RRCC"] * (L + 1), ["RRCC"] * (L + 1), ["RRCC"] * L,
+                                                   [["3322", "2233", "1122"]] * L)), "forced RRCC grid"
+    if name == "wide_mlp_f3":
+        # all four cuts on the reduction dimension of the forward product: 16 partial sums of 512 x 8192 fp32 per layer
+        return cfg, Chain(cfg, tt, torch, tilings=(["CCCC"] * (L + 1), ["rrrr"] * (L + 1), ["RRRR"] * L,
+                                                   [["3333", "2222", "1111"]] * L)), "forced x:CCCC W:RRRR, forward forms F3 x 4"
+    return cfg, Chain(cfg, tt, torch), "planner EXACT"
+
+
+def kernel_line(a, steps):
+    ms = a["ms"] / a["launches"]
+    tf = a["flops"] / (ms * 1e-3) / 1e12 if a["flops"] else None
+    gb = a["bytes"] / (ms * 1e-3) / 1e9
+    return {"kernel": a["kernel"], "count": a["count"], "d": [a["d0"], a["d1"], a["d2"]], "launches_per_step": a["launches"] / steps,
+            "avg_ms": ms, "TFLOPs": tf, "GBps": gb}
+
+
+def roofline_of(workload, a):
+    """Which roof bounds a launch shape: the larger of its two lower bounds on time (flops at the dense bf16 MFMA peak,
+    algorithmic bytes at the HBM peak); both fractions are reported next to it."""
+    ms = a["ms"] / a["launches"]
+    tf = a["flops"] / (ms * 1e-3) / 1e12
+    gb = a["bytes"] / (ms * 1e-3) / 1e9
+    hbm_bound = a["bytes"] / (PEAK_HBM_GBS * 1e9) >= a["flops"] / (PEAK_BF16_TFLOPS * 1e12)
+    return {
+        "bound": "hbm" if hbm_bound else "mfma",
+        "kernel": "%s count=%d M=%d N=%d K=%d" % (a["kernel"], a["count"], a["d0"], a["d1"], a["d2"]),
+        "achieved": gb if hbm_bound else tf, "peak": PEAK_HBM_GBS if hbm_bound else PEAK_BF16_TFLOPS,
+        "unit": "GB/s" if hbm_bound else "TFLOP/s",
+        "frac": gb / PEAK_HBM_GBS if hbm_bound else tf / PEAK_BF16_TFLOPS,
+        "traffic": measured_traffic(workload, a),
+        "avg_ms": ms, "launches": a["launches"],
+        "algorithmic_bytes": a["bytes"], "flops": a["flops"],
+        "flop_per_byte": a["flops"] / a["bytes"] if a["bytes"] else None,
+        "mfma_TFLOPs": tf, "mfma_frac": tf / PEAK_BF16_TFLOPS, "hbm_GBps": gb, "hbm_frac": gb / PEAK_HBM_GBS,
+    }
+
+
+def hbm_line(a):
+    ms = a["ms"] / a["launches"]
+    gb = a["bytes"] / (ms * 1e-3) / 1e9
+    return {"kernel": a["kernel"], "rows": a["d0"], "cols": a["d1"], "bytes": a["bytes"], "avg_ms": ms, "GBps": gb,
+            "peak": PEAK_HBM_GBS, "frac": gb / PEAK_HBM_GBS}
+
+
+def measure(name, args, tt, torch, steps, warmup, conv_split="planner", with_cpu=True, full=False):
+    """One workload: K timed steps (HIP graph replay unless --no-graph), then an eager pass of the same K steps with every
+    kernel bracketed by HIP events on the launch stream.  Returns the report block of the workload."""
+    cfg, chain, tiling_desc = build_workload(name, args, tt, torch, conv_split)
+    is_conv = not hasattr(cfg, "widths")
     if not is_conv and args.overlap:
         chain.aux = torch.cuda.Stream()
-
-    for _ in range(max(W, 1)):
+    for _ in range(max(warmup, 1)):
         chain.step()
     torch.cuda.synchronize()
-
     graph = None
     if not args.no_graph:
         graph = torch.cuda.CUDAGraph()
@@ -342,66 +385,76 @@ def main():
         for _ in range(2):
             graph.replay()
         torch.cuda.synchronize()
-
     run = graph.replay if graph is not None else chain.step
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(K):
+    for _ in range(steps):
         run()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / K
-    tflops = cfg.flops() / (elapsed / K) / 1e12
+    ms_per_step = elapsed * 1e3 / steps
+    flops = cfg.flops()
+    tflops = flops / (elapsed / steps) / 1e12
 
     # per-kernel durations: eager pass on ONE stream (so that durations do not overlap), HIP events around every launch
     if not is_conv:
         chain.aux = None
     tt.tt_profile_begin()
-    for _ in range(K):
+    for _ in range(steps):
         chain.step()
     records = tt.tt_profile_end()
+    if args.launch_log and full:
+        n = len(records) // steps
+        with open(args.launch_log, "w") as fh:
+            json.dump({"workload": name if not is_conv else "%s_%s" % (name, conv_split), "launches_per_step": n,
+                       "launches": records[:n]}, fh)
     agg = aggregate(records)
     is_product = lambda a: a["kernel"].startswith("gemm") or a["kernel"].startswith("conv_")
-    gemm_ms = sum(a["ms"] for a in agg if is_product(a)) / K
-    conv_ms = sum(a["ms"] for a in agg if not is_product(a)) / K
-    dom = agg[0]
-    dom_ms = dom["ms"] / dom["launches"]
-    key = "%s:%s:%dx%dx%d" % (args.workload, dom["kernel"], dom["d0"], dom["d1"], dom["d2"])
-    # Which roof bounds the dominant kernel: the larger of its two lower bounds on time (flops at the dense bf16 MFMA
-    # peak, algorithmic bytes at the HBM peak).  The batch-256 products have fewer than 312 flop per byte and sit under
-    # the HBM roof; both fractions are reported.
-    d_tflops = dom["flops"] / (dom_ms * 1e-3) / 1e12
-    d_gbps = dom["bytes"] / (dom_ms * 1e-3) / 1e9
-    hbm_bound = dom["bytes"] / (PEAK_HBM_GBS * 1e9) >= dom["flops"] / (PEAK_BF16_TFLOPS * 1e12)
-    roofline = {
-        "bound": "hbm" if hbm_bound else "mfma",
-        "kernel": "%s count=%d M=%d N=%d K=%d" % (dom["kernel"], dom["count"], dom["d0"], dom["d1"], dom["d2"]),
-        "achieved": d_gbps if hbm_bound else d_tflops, "peak": PEAK_HBM_GBS if hbm_bound else PEAK_BF16_TFLOPS,
-        "unit": "GB/s" if hbm_bound else "TFLOP/s",
-        "frac": d_gbps / PEAK_HBM_GBS if hbm_bound else d_tflops / PEAK_BF16_TFLOPS,
-        "traffic": MEASURED_TRAFFIC_BYTES.get(key),
-        "avg_ms": dom_ms, "launches": dom["launches"],
-        "algorithmic_bytes": dom["bytes"], "flops": dom["flops"],
-        "flop_per_byte": dom["flops"] / dom["bytes"] if dom["bytes"] else None,
-        "mfma_TFLOPs": d_tflops, "mfma_frac": d_tflops / PEAK_BF16_TFLOPS,
-        "hbm_GBps": d_gbps, "hbm_frac": d_gbps / PEAK_HBM_GBS,
+    products = [a for a in agg if is_product(a)]
+    others = [a for a in agg if not is_product(a)]
+    gemm_ms = sum(a["ms"] for a in products) / steps
+    conv_ms = sum(a["ms"] for a in others) / steps
+    # the dominant kernel: the product launch shape with the most time per step; the conversions and reductions are
+    # reported separately (the one that moves the most bytes of each kind)
+    wl_key = name if not is_conv else "%s_%s" % (name, conv_split)
+    dom = products[0]
+    out = {
+        "workload": ("%s: batch %d, %s, k=%d (%d shards), %s" % (
+            name, cfg.batch, "->".join(str(w) for w in cfg.widths) if len(cfg.widths) < 6 else "%d x (%d->%d)" % (
+                cfg.n_layers, cfg.widths[0], cfg.widths[1]), cfg.k, 1 << cfg.k, tiling_desc)) if not is_conv else (
+            "%s: N=%d C=%d K=%d %dx%d %dx%d pad %d, k=%d (%d shards), %s" % (
+                name, cfg.N, cfg.C, cfg.K, cfg.H, cfg.W, cfg.R, cfg.S, cfg.pad, cfg.k, 1 << cfg.k, tiling_desc)),
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
+        "ms_per_step": ms_per_step, "TFLOPs": tflops, "frac_mfma_peak": tflops / PEAK_BF16_TFLOPS, "steps": steps,
+        "timed": "hip graph replay" if graph is not None else "eager launches",
+        "tiling_x": chain.tx, "tiling_g": chain.tg, "tiling_w": chain.tw, "plan_cost_elems": chain.plan_cost,
+        "roofline": roofline_of(wl_key, dom),
+        "breakdown_ms_per_step": {"products": gemm_ms, "conversions_and_reductions": conv_ms},
     }
-    kernels = [{"kernel": a["kernel"], "count": a["count"], "d": [a["d0"], a["d1"], a["d2"]], "launches_per_step": a["launches"] / K,
-                "avg_ms": a["ms"] / a["launches"],
-                "TFLOPs": (a["flops"] / (a["ms"] / a["launches"] * 1e-3) / 1e12) if a["flops"] else None,
-                "GBps": a["bytes"] / (a["ms"] / a["launches"] * 1e-3) / 1e9} for a in agg]
+    red = [a for a in others if a["kernel"] == "reduce"]
+    cvt = [a for a in others if a["kernel"] in ("convert", "gate")]
+    out["reduce"] = hbm_line(max(red, key=lambda a: a["bytes"])) if red else None
+    out["conversion"] = hbm_line(max(cvt, key=lambda a: a["bytes"])) if cvt else None
+    if full:
+        out["kernels"] = [kernel_line(a, steps) for a in agg]
+        try:
+            out["counted_cross_shard_elems"] = counted_cross_shard_elems(tt, cfg, chain, is_conv)
+        except Exception:  # a report line must not take the measurement down
+            out["counted_cross_shard_elems"] = None
+        out["streams"] = 2 if (not is_conv and args.overlap) else 1
+    else:
+        out["products"] = [kernel_line(a, steps) for a in products[:3]]
+    if with_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    del chain, graph
+    torch.cuda.empty_cache()
+    return out, cfg
 
-    # partial-sum reduce headline: the reduction launch that moves the most bytes in this step
-    red = [a for a in agg if a["kernel"] == "reduce"]
-    reduce_line = None
-    if red:
-        rb = max(red, key=lambda a: a["bytes"])
-        rb_ms = rb["ms"] / rb["launches"]
-        reduce_line = {"rows": rb["d0"], "cols": rb["d1"], "bytes": rb["bytes"], "avg_ms": rb_ms,
-                       "GBps": rb["bytes"] / (rb_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                       "frac": rb["bytes"] / (rb_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
 
-    # retile headline: the largest tensor of the workload between two non-replicated tilings
+def retile_headline(cfg, tt, torch):
+    """retile of the workload's largest tensor between two non-replicated tilings: back-to-back launches between one pair
+    of HIP events on the launch stream"""
+    is_conv = not hasattr(cfg, "widths")
     rows, cols = (cfg.widths[0], cfg.widths[1]) if not is_conv else (cfg.K * cfg.R * cfg.S, cfg.C)
     ka = cfg.k
     A, B = "R" * ka, "C" * ka
@@ -413,7 +466,6 @@ def main():
     dst = [torch.zeros((sr, sc), dtype=tdt, device="cuda:0") for _ in range(1 << ka)]
     for _ in range(3):
         tt.tt_retile(dst, B, src, A, rows, cols, esz)
-    # back-to-back launches between one pair of HIP events on the launch stream
     n_rt = 50
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ev0.record()
@@ -424,38 +476,59 @@ def main():
     r_ms = ev0.elapsed_time(ev1) / n_rt
     r_bytes = 2 * rows * cols * esz
     r_gbs = r_bytes / (r_ms * 1e-3) / 1e9
-    rrec = [{"bytes": r_bytes}]
-    retile = {"tensor": "W_1 %dx%d %s" % (rows, cols, cfg.dtype), "from": A, "to": B, "bytes": rrec[0]["bytes"],
-              "avg_ms": r_ms, "GBps": r_gbs, "peak": PEAK_HBM_GBS, "frac": r_gbs / PEAK_HBM_GBS}
-    del src, dst
+    return {"tensor": "W_1 %dx%d %s" % (rows, cols, cfg.dtype), "from": A, "to": B, "bytes": r_bytes,
+            "avg_ms": r_ms, "GBps": r_gbs, "peak": PEAK_HBM_GBS, "frac": r_gbs / PEAK_HBM_GBS}
 
-    try:
-        counted = counted_cross_shard_elems(tt, cfg, chain, is_conv)
-    except Exception:  # a report line must not take the measurement down
-        counted = None
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (all 2^k shards are simulated in one HBM); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_1805_04170_amd as tt
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    tt.binding.lib()
+    torch.cuda.set_device(0)
+    if args.workload == "shape_study":
+        print(json.dumps(shape_study(args, tt, torch)))
+        return
+    K, W = args.steps, args.warmup
+    head, cfg = measure(args.workload, args, tt, torch, K, W, args.conv_split, with_cpu=not args.no_cpu_baseline, full=True)
+    retile = retile_headline(cfg, tt, torch)
     out = {
         "metric": "tiled fwd+bwd TFLOP/s at VGG-16 FC shapes (% MFMA peak); retile GB/s (% HBM)",
-        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "value": head["TFLOPs"], "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": ("%s: batch %d, %s, k=%d (%d shards), %s tiling" % (
-            cfg.name, cfg.batch, "->".join(str(w) for w in cfg.widths), cfg.k, 1 << cfg.k,
-            "planner EXACT" if chain.plan_cost is not None else "forced RRCC grid")) if not is_conv else (
-            "%s: N=%d C=%d K=%d %dx%d %dx%d pad %d, k=%d (%d shards), %s split" % (
-                cfg.name, cfg.N, cfg.C, cfg.K, cfg.H, cfg.W, cfg.R, cfg.S, cfg.pad, cfg.k, 1 << cfg.k, args.conv_split)),
-            "tiling_x": chain.tx, "tiling_g": chain.tg, "tiling_w": chain.tw, "plan_cost_elems": chain.plan_cost,
-            "counted_cross_shard_elems": counted,
-            "timed": "hip graph replay" if graph is not None else "eager launches",
-            "streams": 2 if (not is_conv and args.overlap) else 1},
-        "frac_mfma_peak": tflops / PEAK_BF16_TFLOPS,
-        "roofline": roofline,
+        "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["workload"], "tiling_x": head["tiling_x"], "tiling_g": head["tiling_g"],
+                   "tiling_w": head["tiling_w"], "plan_cost_elems": head["plan_cost_elems"],
+                   "counted_cross_shard_elems": head["counted_cross_shard_elems"], "timed": head["timed"],
+                   "streams": head["streams"]},
+        "frac_mfma_peak": head["frac_mfma_peak"],
+        "roofline": head["roofline"],
         "retile": retile,
-        "reduce": reduce_line,
-        "breakdown_ms_per_step": {"products": gemm_ms, "conversions_and_reductions": conv_ms},
-        "kernels": kernels,
+        "reduce": head["reduce"],
+        "conversion": head["conversion"],
+        "breakdown_ms_per_step": head["breakdown_ms_per_step"],
+        "kernels": head["kernels"],
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg)
+    if "cpu_baseline" in head:
+        out["cpu_baseline"] = head["cpu_baseline"]
+    if not args.headline_only and args.workload == "vgg16_fc":
+        # the other configurations, one compact block each (fewer timed steps; each with its own CPU sample)
+        others = []
+        for name, split in (("alexnet_fc", None), ("wide_mlp", None), ("wide_mlp_f3", None), ("vgg16_conv4", "planner"),
+                            ("vgg16_conv4", "batch"), ("vgg16_conv4", "out_channel"), ("tiny_mlp", None)):
+            cpu = not args.no_cpu_baseline and name != "wide_mlp_f3" and split in (None, "planner")
+            blk, _ = measure(name, args, tt, torch, args.other_steps, min(W, 2), split or "planner", with_cpu=cpu)
+            others.append(blk)
+        out["others"] = others
+        study = shape_study(args, tt, torch, steps=max(3, args.other_steps // 2))
+        out["shape_study"] = {"workload": study["config"]["workload"], "rows": study["rows"]}
     print(json.dumps(out))
 
 

@@ -168,14 +168,14 @@ template <int BM, int BN> __device__ __forceinline__ bool tile_of(const ConvPara
 }
 
 // OP 0: forward, 1: dgrad
-template <int BM, int BN, int WN, int DEPTH, bool KMASK, int OP, bool OUT_BF16, bool ONE_TAP>
-__global__ __launch_bounds__(WN * 128, WN / 2) void conv_gather_a_kernel(const ConvParams p)
+template <int BM, int BN, int WN, int DEPTH, bool KMASK, int OP, bool OUT_BF16, bool ONE_TAP, int WM = 2>
+__global__ __launch_bounds__(WM * WN * 64, WM * WN / 4) void conv_gather_a_kernel(const ConvParams p)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     TileId t;
     if (!tile_of<BM, BN>(p, &t)) return;
     const ConvGeom &g = p.g;
-    constexpr int NT = WN * 128;
+    constexpr int NT = WM * WN * 64;
     GatherKC<core::Slots<BM, true, NT>::value, ONE_TAP> la;
     la.base = reinterpret_cast<const char *>(p.A[t.shard]);
     la.R = g.R; la.S = g.S;
@@ -186,12 +186,12 @@ __global__ __launch_bounds__(WN * 128, WN / 2) void conv_gather_a_kernel(const C
         core::DenseKC<core::Slots<BN, true, NT>::value> lb;
         lb.base = reinterpret_cast<const char *>(p.B[t.shard]);
         lb.ld = p.K; lb.rows = p.N; lb.K = p.K;
-        core::tile_product<BM, BN, 2, WN, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
+        core::tile_product<BM, BN, WM, WN, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
     } else {
         FilterRC<core::Slots<BN, false, NT>::value> lb;
         lb.base = reinterpret_cast<const char *>(p.B[t.shard]);
         lb.RS = g.R * g.S; lb.Cs = g.Cs; lb.Ks = g.Ks; lb.rows = p.N; lb.K = p.K;
-        core::tile_product<BM, BN, 2, WN, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
+        core::tile_product<BM, BN, WM, WN, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
     }
 }
 
@@ -300,6 +300,14 @@ template <int OP, bool OUT_BF16, bool ONE_TAP> tt_status launch_gather_a_t(ConvP
 {
     const bool kmask = p.K % core::BK != 0;
     const int tile = conv_tile(p.M, p.N, count);
+    // at most 64 output columns per shard (channels cut eight ways): 256 x 64 tiles, four waves of 64 x 64, so that no
+    // wave multiplies columns that do not exist
+    if constexpr (OP == 0) // (the filter loader of the direct data-gradient path needs 128 columns for its 256 threads)
+    if (p.N <= 64 && p.M > 128 && tuning_int("TT_CONV_TILE", -1) < 0) {
+        constexpr size_t sm = core::smem_bytes<256, 64, 2>();
+        return kmask ? launch(conv_gather_a_kernel<256, 64, 1, 2, true, OP, OUT_BF16, ONE_TAP, 4>, sm, p, 256, 64, 256, count, s)
+                     : launch(conv_gather_a_kernel<256, 64, 1, 2, false, OP, OUT_BF16, ONE_TAP, 4>, sm, p, 256, 64, 256, count, s);
+    }
     if (tile == 2) {
         constexpr size_t sm = core::smem_bytes<256, 256>();
         return kmask ? launch(conv_gather_a_kernel<256, 256, 4, 1, true, OP, OUT_BF16, ONE_TAP>, sm, p, 256, 256, 512, count, s)

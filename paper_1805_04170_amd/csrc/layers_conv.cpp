@@ -159,11 +159,31 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
         uint8_t zl[TT_MAX_K];
         for (int j = 0; j < k; ++j) zl[j] = f[j] == TT_F1 ? TT_C : (f[j] == TT_F2 ? TT_R : kRed);
         const tt_tiling tWs = transpose_tiling(a.tW, k);
+        // The reduction of this product runs over every pixel of every image of the shard.  Where the filter block of a
+        // shard gives too few output tiles to occupy the chip (input or output channels cut, the batch not), the images of
+        // a shard are dealt to `split` sub-products, each writing its own fp32 partial sum, which the reduction kernel adds
+        // up together with the partial sums of the F3 cuts.  A sub-product is the same product on a slice of the two
+        // operands: both are image-major, so the slice is an offset into the shard.
+        const int64_t Ns = d.N >> k3, Cs = d.C >> k1, Ks = d.K >> k2;
+        int split = 1;
+        {
+            const int64_t tiles = ((Ks + 255) / 256) * ((rs * Cs + 127) / 128) * n; // 256 x 128 tiles of the filter gradient
+            while (tiles * split < 256 && split < 8 && Ns % (2 * split) == 0 && n * 2 * split <= kMaxShards &&
+                   (Ns / (2 * split)) * pq >= 2048)
+                split *= 2;
+        }
         OutputPlan op;
-        if ((st = plan_output_letters(zl, tWs, a.dW, d.K * rs, d.C, k, a.dtype, TT_ACT_NONE, ws, &op)) != TT_OK) return st;
+        if ((st = plan_output_letters(zl, tWs, a.dW, d.K * rs, d.C, k, a.dtype, TT_ACT_NONE, ws, &op, split)) != TT_OK) return st;
         if (!ws.dry) {
-            st = launch_conv(TT_OP_WGRAD, n, Ga.ptr, Xa.ptr, op.gemm_out, d.N >> k3, d.C >> k1, d.K >> k2, d.H, d.W, d.R, d.S,
-                             d.pad, op.gemm_dtype, TT_ACT_NONE, a.stream);
+            const void *Gs[kMaxShards], *Xs[kMaxShards];
+            const int64_t Nsub = Ns / split;
+            for (int s = 0; s < n; ++s)
+                for (int c = 0; c < split; ++c) {
+                    Gs[s * split + c] = static_cast<const char *>(Ga.ptr[s]) + (size_t)c * Nsub * pq * Ks * 2;
+                    Xs[s * split + c] = static_cast<const char *>(Xa.ptr[s]) + (size_t)c * Nsub * hw * Cs * 2;
+                }
+            st = launch_conv(TT_OP_WGRAD, n * split, Gs, Xs, op.gemm_out, Nsub, Cs, Ks, d.H, d.W, d.R, d.S, d.pad, op.gemm_dtype,
+                             TT_ACT_NONE, a.stream);
             if (st != TT_OK) return st;
             if ((st = finish_output(op, tWs, a.dW, d.K * rs, d.C, k, a.dtype, TT_ACT_NONE, a.stream)) != TT_OK) return st;
         }

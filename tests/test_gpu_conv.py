@@ -114,6 +114,7 @@ def test_other_filter_shapes():
     run_conv(2, 16, 16, 9, 8, 5, 5, 2, 1, False, "R", "r", "R", "R", "R", None, None, None, 131)          # 5x5 "same"
     run_conv(2, 16, 16, 8, 8, 3, 3, 0, 1, False, "C", "R", "r", "r", "C", None, None, None, 132, False)   # no padding, no dX
     run_conv(8, 8, 8, 3, 3, 3, 3, 1, 3, True, "RRR", "rrr", "RRR", "RRR", "RRR", "111", "111", "333", 133)  # 8 channels: K tail
+    run_conv(8, 64, 128, 6, 6, 3, 3, 1, 1, True, "r", "C", "C", "C", "r", "2", "3", "2", 134)           # 64 output channels per shard: 256 x 64 tiles
 
 
 def test_refusals():
