@@ -403,11 +403,6 @@ def measure(name, args, tt, torch, steps, warmup, conv_split="planner", with_cpu
     for _ in range(steps):
         chain.step()
     records = tt.tt_profile_end()
-    if args.launch_log and full:
-        n = len(records) // steps
-        with open(args.launch_log, "w") as fh:
-            json.dump({"workload": name if not is_conv else "%s_%s" % (name, conv_split), "launches_per_step": n,
-                       "launches": records[:n]}, fh)
     agg = aggregate(records)
     is_product = lambda a: a["kernel"].startswith("gemm") or a["kernel"].startswith("conv_")
     products = [a for a in agg if is_product(a)]
@@ -442,6 +437,7 @@ def measure(name, args, tt, torch, steps, warmup, conv_split="planner", with_cpu
         except Exception:  # a report line must not take the measurement down
             out["counted_cross_shard_elems"] = None
         out["streams"] = 2 if (not is_conv and args.overlap) else 1
+        out["_launches"] = (wl_key, records[:len(records) // steps])
     else:
         out["products"] = [kernel_line(a, steps) for a in products[:3]]
     if with_cpu:
@@ -499,6 +495,10 @@ def main():
     K, W = args.steps, args.warmup
     head, cfg = measure(args.workload, args, tt, torch, K, W, args.conv_split, with_cpu=not args.no_cpu_baseline, full=True)
     retile = retile_headline(cfg, tt, torch)
+    wl_key, step_launches = head.pop("_launches")
+    if args.launch_log:
+        with open(args.launch_log, "w") as fh:
+            json.dump({"workload": wl_key, "launches": step_launches, "retile_bytes_each_way": retile["bytes"] // 2}, fh)
     out = {
         "metric": "tiled fwd+bwd TFLOP/s at VGG-16 FC shapes (% MFMA peak); retile GB/s (% HBM)",
         "value": head["TFLOPs"], "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": head["ms_per_step"],
