@@ -150,7 +150,8 @@ inline int pick_ksplit(int64_t M, int64_t N, int64_t K, int count, int dtype, bo
     // chunks stay at least 512 deep, except where the launch would otherwise occupy under a quarter of the CUs (the
     // 1000-wide last layer): there chunks down to 192 still pay for the extra partial sums
     int s = 1;
-    while (blocks * s < 200 && s < 8 && K / (2 * s) >= (blocks * s < 64 ? 192 : 512) && count * 2 * s <= kMaxShards &&
+    static const int min_blocks = tuning_int("TT_KSPLIT_BLOCKS", 200);
+    while (blocks * s < min_blocks && s < 8 && K / (2 * s) >= (blocks * s < 64 ? 192 : 512) && count * 2 * s <= kMaxShards &&
            ksplit_fits(K, 2 * s))
         s *= 2;
     return s;

@@ -6,21 +6,9 @@
 #include <mutex>
 #include <unordered_map>
 #include "tensor_tiling.h"
+#include "tt_internal.h"
 
 namespace tt {
-
-// Launch heuristics can be overridden through environment variables only in development builds (-DTT_TUNING); the
-// product build reads no environment and every launch decision is a pure function of the call's arguments.
-inline int tuning_int(const char *name, int dflt)
-{
-#ifdef TT_TUNING
-    const char *e = std::getenv(name);
-    return e ? std::atoi(e) : dflt;
-#else
-    (void)name;
-    return dflt;
-#endif
-}
 
 // Kernels that use more dynamic LDS than the default limit need the limit raised once per kernel.  The set of kernels
 // already raised is the only state the launch code keeps; it is guarded, and raising twice would be harmless.

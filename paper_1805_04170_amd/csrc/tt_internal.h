@@ -1,10 +1,25 @@
 // Internal host-side helpers shared by the library's translation units.
 #pragma once
+#include <cstdlib>
 #include <cstdint>
 #include <cstddef>
 #include "tensor_tiling.h"
 
 namespace tt {
+
+// Launch heuristics can be overridden through environment variables only in development builds (-DTT_TUNING); the
+// product build reads no environment and every launch decision is a pure function of the call's arguments.
+inline int tuning_int(const char *name, int dflt)
+{
+#ifdef TT_TUNING
+    const char *e = std::getenv(name);
+    return e ? std::atoi(e) : dflt;
+#else
+    (void)name;
+    return dflt;
+#endif
+}
+
 
 constexpr int kMaxShards = 1 << TT_MAX_K;
 
