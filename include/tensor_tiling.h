@@ -145,6 +145,19 @@ tt_status tt_retile_gate(void *const *dst, tt_tiling B, const void *const *src, 
                          const void *const *mask, tt_tiling Am, int k, int64_t rows, int64_t cols, int dtype,
                          void *stream);
 
+/* Tiling conversion between a convolution's and a fully-connected layer's view of the same [batch][channels][pixels]
+ * tensor (Sec. 4.5: convolution tensors are cut along batch and channel only; Sec. 5.2 step 1).  Image side: per
+ * shard a row-major (images * pixels) x channels matrix, the storage of tt_conv_*.  Matrix side: per shard a
+ * row-major images x (channels * pixels) matrix with channel-major columns, so that a column cut (TT_C) is a channel
+ * cut on both sides; TT_R cuts the batch on both sides.  to_matrix != 0: src is the image side under A, dst the matrix
+ * side under B (the flatten in front of the first fully-connected layer); to_matrix == 0: src is the matrix side
+ * under A, dst the image side under B (its gradient on the way back).  dst / src: 2^k dev ptrs.  elem_bytes in {2,4}.
+ * Bit-exact; src and dst must not overlap; replicas in A are assumed identical; every replica in B is written.
+ * Errors: TT_EINVAL, TT_EINFEASIBLE (batch or channels not divisible as a tiling asks), TT_EUNSUPPORTED (batch above
+ * 65535, or batch * pixels >= 2^32). */
+tt_status tt_flatten(void *const *dst, tt_tiling B, const void *const *src, tt_tiling A, int k, int64_t batch,
+                     int64_t channels, int64_t pixels, int elem_bytes, int to_matrix, void *stream);
+
 /* Reduction of the partial sums left by F3 cuts, fused with the output conversion (Sec. 4.2.1 "extra reduction";
  * Sec. 5.2 step 3).  partials: 2^k dev ptrs to fp32 buffers; shard s holds the (rows / 2^k1) x (cols / 2^k2)
  * block selected by its side bits at the F1 cuts (row block) and F2 cuts (column block); its bits at the F3

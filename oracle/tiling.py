@@ -97,3 +97,17 @@ def untile4(shards, t, shape):
     for s, sh in enumerate(shards):
         out[shard_slices(shape[0], shape[1], t, s)] = sh
     return out
+
+
+# ---- between a convolution and a fully-connected layer ----
+
+def flatten_images(T):
+    """[batch, channel, h, w] -> batch x (channel * h * w), channels major: the matrix a fully-connected layer
+    multiplies.  With this column order the first half of the columns is the first half of the channels, so a column
+    cut of the matrix is a channel cut of the images (Sec. 4.5 allows no other cut of an image tensor)."""
+    return np.ascontiguousarray(T).reshape(T.shape[0], -1)
+
+
+def unflatten_images(Mx, shape):
+    """inverse of flatten_images: batch x (channel * h * w) -> [batch, channel, h, w]"""
+    return np.ascontiguousarray(Mx).reshape(shape)

@@ -25,7 +25,7 @@ STATUS_NAMES = {0: "TT_OK", 1: "TT_EINVAL", 2: "TT_EINFEASIBLE", 3: "TT_EUNSUPPO
 
 EXPORTS = [
     "tt_strerror", "tt_shard_shape", "tt_plan_chain", "tt_plan_eval", "tt_plan_k", "tt_plan_layers", "tt_plan_cost",
-    "tt_plan_delta", "tt_plan_tiling", "tt_plan_forms", "tt_plan_free", "tt_retile", "tt_retile_gate", "tt_reduce",
+    "tt_plan_delta", "tt_plan_tiling", "tt_plan_forms", "tt_plan_free", "tt_retile", "tt_flatten", "tt_retile_gate", "tt_reduce",
     "tt_shard_gemm", "tt_fc_workspace_bytes", "tt_fc_forward", "tt_fc_forward_static", "tt_fc_backward", "tt_fc_backward_overlapped",
     "tt_conv_workspace_bytes",
     "tt_conv_forward", "tt_conv_backward", "tt_profile_begin", "tt_profile_end", "tt_profile_get",
@@ -121,6 +121,8 @@ def lib():
         L.tt_graph_plan_free.restype = None
         L.tt_retile.argtypes = [_vpp, tt_tiling, _vpp, tt_tiling, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
                                 ctypes.c_int, ctypes.c_void_p]
+        L.tt_flatten.argtypes = [_vpp, tt_tiling, _vpp, tt_tiling, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                 ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
         L.tt_retile_gate.argtypes = [_vpp, tt_tiling, _vpp, tt_tiling, _vpp, tt_tiling, ctypes.c_int, ctypes.c_int64,
                                      ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
         L.tt_reduce.argtypes = [_vpp, tt_tiling, ctypes.c_int, _vpp, _u8p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
@@ -421,6 +423,12 @@ def tt_retile(dst, B, src, A, rows, cols, elem_bytes, k=None, stream=None):
     k = len(A) if k is None else k
     _check(lib().tt_retile(ptrs(dst), tiling(B), ptrs(src), tiling(A), k, rows, cols, elem_bytes, _stream(stream)),
            "tt_retile")
+
+
+def tt_flatten(dst, B, src, A, batch, channels, pixels, elem_bytes, to_matrix=True, k=None, stream=None):
+    k = len(A) if k is None else k
+    _check(lib().tt_flatten(ptrs(dst), tiling(B), ptrs(src), tiling(A), k, batch, channels, pixels, elem_bytes,
+                            1 if to_matrix else 0, _stream(stream)), "tt_flatten")
 
 
 def tt_retile_gate(dst, B, src, A, mask, Am, rows, cols, dtype, k=None, stream=None):

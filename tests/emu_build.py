@@ -24,7 +24,7 @@ PROGRAMS = {
     "shard_gemm_lockstep": ("emu_shard_gemm.cpp", ["-O0", "-DTT_EMU_LOCKSTEP"]),
 }
 GEMM1_NAMES = ["E1_BM", "E1_BN", "E1_WM", "E1_WN", "E1_DEPTH", "E1_KMASK", "E1_AKC", "E1_BKC", "E1_BF16", "E1_VEC"]
-LIBRARY_UNITS = [os.path.join(EMU, f) for f in ("emu_lib_gemm.cpp", "emu_lib_conv.cpp", "emu_lib_convert.cpp", "emu_lib_static.cpp")] + \
+LIBRARY_UNITS = [os.path.join(EMU, f) for f in ("emu_lib_gemm.cpp", "emu_lib_conv.cpp", "emu_lib_convert.cpp", "emu_lib_flatten.cpp", "emu_lib_static.cpp")] + \
                 [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".cpp")]
 LIBRARY_FLAGS = ["-O0", "-fPIC", "-DTT_EMU_LOCKSTEP", "-DTT_HOST_EMULATION"]
 # the same units in address mode under the sanitizer, linked with the driver of a whole training step

@@ -35,11 +35,12 @@ def on_host(emulated_library, monkeypatch):
     import test_gpu_convert
     import test_gpu_fc
     import test_gpu_gemm
+    import test_gpu_net
     monkeypatch.setattr(binding, "LIB_PATH", emulated_library)
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "_stream", lambda stream: ctypes.c_void_p(0))
     monkeypatch.setattr(torch.cuda, "synchronize", lambda *a, **k: None)
-    for m in (gpu_util, test_gpu_fc, test_gpu_conv, test_gpu_convert, test_gpu_gemm):
+    for m in (gpu_util, test_gpu_fc, test_gpu_conv, test_gpu_convert, test_gpu_gemm, test_gpu_net):
         if hasattr(m, "DEV"):
             monkeypatch.setattr(m, "DEV", "cpu")
 
@@ -50,7 +51,8 @@ def on_host(emulated_library, monkeypatch):
 
     monkeypatch.setattr(test_gpu_fc, "workspace", aligned_workspace)
     monkeypatch.setattr(test_gpu_conv, "ws", aligned_workspace)
-    return dict(fc=test_gpu_fc, conv=test_gpu_conv, convert=test_gpu_convert, gemm=test_gpu_gemm)
+    monkeypatch.setattr(test_gpu_net, "workspace", aligned_workspace)
+    return dict(fc=test_gpu_fc, conv=test_gpu_conv, convert=test_gpu_convert, gemm=test_gpu_gemm, net=test_gpu_net)
 
 
 def test_every_declared_symbol_is_exported_by_the_host_build(emulated_library):
@@ -261,3 +263,13 @@ def test_random_reductions_and_gated_retiles(on_host):
         got = tl.untile(shards_to_np(dst), tB, rows, cols)
         u = np.uint16 if bf else np.uint32
         assert np.array_equal(got.view(u), want_full.view(u)), (case, tA, tM, tB, rows, cols, bf)
+
+
+def test_flatten_between_convolution_and_fully_connected(on_host):
+    on_host["net"].test_flatten_every_tiling_pair_two_cuts()
+    on_host["net"].test_flatten_tile_tails_and_sizes()
+    on_host["net"].test_flatten_refusals()
+
+
+def test_convolution_flatten_fully_connected_network(on_host):
+    on_host["net"].test_conv_flatten_fc_fc_under_the_planners_tiling()

@@ -94,3 +94,17 @@ def test_tile4_matches_2d_rule():
         for a, b in zip(sh, flat):
             assert np.array_equal(a[:, :, 0, 0], b)
         assert np.array_equal(tl.untile4(sh, t, T.shape), T)
+
+
+def test_flattened_images_column_cut_is_a_channel_cut():
+    # Sec. 4.5: image tensors are cut along batch and channel only.  With channel-major columns the tiles of the
+    # flattened matrix are the flattened tiles of the 4-D tensor, for every tiling (so no other cut ever appears).
+    rng = np.random.default_rng(11)
+    T = rng.integers(0, 1000, size=(4, 8, 3, 5))
+    Mx = tl.flatten_images(T)
+    assert Mx.shape == (4, 120)
+    assert Mx[2, 3 * 15 + 1 * 5 + 4] == T[2, 3, 1, 4]                     # column = (channel, row, column of the image)
+    for t in tl.all_tilings(2) + ["CCC", "RCr"]:
+        for a, b in zip(tl.tile(Mx, t), tl.tile4(T, t)):
+            assert np.array_equal(a, tl.flatten_images(b)), t
+    assert np.array_equal(tl.unflatten_images(Mx, T.shape), T)
