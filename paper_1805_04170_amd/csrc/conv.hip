@@ -15,6 +15,7 @@
 #include <cstdlib>
 #include "tt_device.h"
 #include "gemm_core.h"
+#include "gemm_core2.h"
 #include "tt_internal.h"
 #include "launch_util.h"
 
@@ -210,6 +211,245 @@ __global__ __launch_bounds__(WN * 128, WN / 2) void conv_wgrad_kernel(const Conv
     lb.base = reinterpret_cast<const char *>(p.B[t.shard]);
     lb.H = g.H; lb.W = g.W; lb.P = g.P; lb.Q = g.Q; lb.S = g.S; lb.pad = g.pad; lb.Cs = g.Cs; lb.rows = p.N; lb.K = p.K;
     core::tile_product<BM, BN, 2, WN, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, false, smem);
+}
+
+// ---- weight gradient with the reduction over pixels re-cut evenly --------------------------------------------------
+// The shards that an F3 cut makes add up into the same filter block (Sec. 4.2.1, third aligned form), so the pixels of
+// all of them form ONE reduction range per output block, and how that range is cut into partial sums is free: the
+// reduction kernel adds whatever partial sums it is given.  Cutting it into `parts` equal runs of 64-pixel K tiles
+// (a run may start in one shard and end in the next) makes the number of equal work items a free choice, so a launch
+// can fill the chip in whole rounds where the 2^k3 natural partial sums would leave it a ragged last round.
+struct SplitGeom {
+    int32_t parts;  // partial sums per output block
+    int32_t nred;   // shards per output block (2^k3)
+    int32_t ktps;   // K tiles (64 pixels) per shard
+    uint8_t red_ids[kMaxShards]; // id bits (at the F3 cuts) of the q-th shard of a block
+    uint8_t blk_ids[kMaxShards]; // id bits (at the F1 / F2 cuts) of block b
+};
+struct WgradSplitParams {
+    ConvParams c; // A, B: by shard id; C: partial sum number blk * parts + part
+    SplitGeom sp;
+};
+
+// where K tile g of a block's reduction range lies: its shard's buffer and the pixel it starts at inside that shard.
+// A work item touches at most kSegs consecutive shards (the launcher sees to that); their base addresses are read from
+// the kernel arguments once, so that no table lookup sits between the K tiles' loads.
+constexpr int kSegs = 4;
+struct Segment {
+    const char *b[kSegs];
+    int q0, ktps, g0;
+    __device__ __forceinline__ void bind(const void *const *tab, const uint8_t *red_ids, int blk_bits, int nred, int ktps_, int g0_)
+    {
+        ktps = ktps_;
+        g0 = g0_;
+        q0 = g0 / ktps;
+#pragma unroll
+        for (int j = 0; j < kSegs; ++j) {
+            const int q = q0 + j < nred ? q0 + j : nred - 1;
+            b[j] = reinterpret_cast<const char *>(tab[blk_bits | red_ids[q]]);
+        }
+    }
+    __device__ __forceinline__ const char *locate(int k0, int *kshift) const
+    {
+        const int g = g0 + k0 / core::BK, q = g / ktps;
+        *kshift = (g - q * ktps) * core::BK - k0;
+        const int j = q - q0;
+        return j == 0 ? b[0] : (j == 1 ? b[1] : (j == 2 ? b[2] : b[3]));
+    }
+};
+
+// dY rows (output channels contiguous) over the segmented pixel range; k counts from the start of the work item
+template <int SLOTS> struct SegDenseRC {
+    static constexpr bool KC = false;
+    static constexpr bool kFence = false;
+    Segment seg;
+    const char *base;
+    int kshift;
+    int ld, rows, K;
+    uint32_t off[SLOTS];
+    __device__ __forceinline__ void init(int slot, int row) { off[slot] = (uint32_t)(row < rows ? row : rows - 8) * 2u; }
+    __device__ __forceinline__ void begin_tile(int k0) { base = seg.locate(k0, &kshift); }
+    template <bool KMASK> __device__ __forceinline__ void load4(int slot, int k, u32x4 *out) const
+    {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            out[q] = *reinterpret_cast<const u32x4 *>(base + (size_t)(off[slot] + (uint32_t)(k + kshift + q) * (uint32_t)ld * 2u));
+    }
+};
+
+// the gathered X rows of GatherRC over the segmented pixel range
+template <int SLOTS> struct SegGatherRC {
+    static constexpr bool KC = false;
+    static constexpr bool kFence = false;
+    Segment seg;
+    const char *base;
+    int kshift;
+    int H, W, P, Q, S, pad, Cs, rows, K;
+    int32_t dy[SLOTS], dx[SLOTS], c0[SLOTS];
+    __device__ __forceinline__ void init(int slot, int row)
+    {
+        row = row < rows ? row : rows - 8;
+        const int tap = row / Cs;
+        c0[slot] = row - tap * Cs;
+        const int r = tap / S;
+        dy[slot] = r - pad;
+        dx[slot] = tap - r * S - pad;
+    }
+    __device__ __forceinline__ void begin_tile(int k0) { base = seg.locate(k0, &kshift); }
+    template <bool KMASK> __device__ __forceinline__ void load4(int slot, int k, u32x4 *out) const
+    {
+        const int kl = k + kshift; // pixel inside the shard; the four pixels lie in one K tile, so in one shard
+        int n = kl / (P * Q);
+        const int rem = kl - n * (P * Q);
+        int p = rem / Q, q = rem - p * Q;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int iy = p + dy[slot], ix = q + dx[slot];
+            const bool ok = iy >= 0 && iy < H && ix >= 0 && ix < W;
+            const int32_t o = ((n * H + iy) * W + ix) * Cs + c0[slot];
+            out[j] = and_mask(load16(base, ok ? o : 0), ok);
+            if (++q == Q) { q = 0; if (++p == P) { p = 0; ++n; } }
+        }
+    }
+};
+
+template <int BM, int BN, int WN, int DEPTH>
+__global__ __launch_bounds__(WN * 128, WN / 2) void conv_wgrad_split_kernel(const WgradSplitParams w)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    const ConvParams &p = w.c;
+    const int logical = core::logical_block(p.per_xcd, p.total);
+    if (logical < 0) return;
+    // items that share a pixel run are neighbours: they read the same dY and X rows through one L2
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int bp = logical / tiles, r = logical - bp * tiles;
+    const int blk = bp / w.sp.parts, part = bp - blk * w.sp.parts;
+    const int n0 = (r % p.tiles_n) * BN, m0 = (r / p.tiles_n) * BM;
+    const int G = w.sp.nred * w.sp.ktps;
+    const int g0 = (int)((int64_t)part * G / w.sp.parts), g1 = (int)((int64_t)(part + 1) * G / w.sp.parts);
+    const int K = (g1 - g0) * core::BK; // at least one K tile: the launcher keeps parts <= G
+    const ConvGeom &g = p.g;
+    constexpr int NT = WN * 128;
+    SegDenseRC<core::Slots<BM, false, NT>::value> la;
+    la.seg.bind(w.c.A, w.sp.red_ids, w.sp.blk_ids[blk], w.sp.nred, w.sp.ktps, g0);
+    la.ld = g.Ks; la.rows = p.M; la.K = K;
+    SegGatherRC<core::Slots<BN, false, NT>::value> lb;
+    lb.seg.bind(w.c.B, w.sp.red_ids, w.sp.blk_ids[blk], w.sp.nred, w.sp.ktps, g0);
+    lb.H = g.H; lb.W = g.W; lb.P = g.P; lb.Q = g.Q; lb.S = g.S; lb.pad = g.pad; lb.Cs = g.Cs; lb.rows = p.N; lb.K = K;
+    core::tile_product<BM, BN, 2, WN, DEPTH, false, false, true>(la, lb, p.C[bp], p.ldc, p.M, p.N, K, m0, n0, false, smem);
+}
+
+// The same product on the engine that loads tiles straight into LDS (gemm_core2.h): both operands are stored with the
+// pixels as the slow dimension, so their tiles go into LDS as they lie in memory and the fragments come out through LDS
+// transpose reads; no register transposes and no LDS store instructions.  256 x 256 tiles, eight waves, one workgroup per CU.
+struct SegDenseRC2 {
+    static constexpr bool KC = false;
+    Segment seg;
+    int ld, rows;
+    template <int ROWS> __device__ __forceinline__ void issue(int row0, int k0, char *lds) const
+    {
+        static_assert(ROWS == 256, "tile side");
+        int kshift;
+        const char *base = seg.locate(k0, &kshift);
+        const int tid = threadIdx.x, wave = tid >> 6;
+        const int kr = tid >> 5, pc = tid & 31; // chunk tid + 512 i: k-row kr + 16 i, position pc (see core2::issue_tile)
+        int r0 = row0 + ((pc ^ ((kr & 3) << 1)) << 3);
+        r0 = r0 < rows ? r0 : rows - 8; // rows past the end only feed C rows that are never stored
+        const char *a = base + ((size_t)(k0 + kshift + kr) * (size_t)ld + (size_t)r0) * 2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            core2::load_chunk_to_lds(a + (size_t)i * 16 * (size_t)ld * 2, lds + (size_t)(wave * 64 + i * core2::kThreads2) * 16);
+    }
+};
+
+struct PixelStep { int dn, dp, dq; }; // a run of pixels as whole images, whole rows and columns
+
+struct SegGatherRC2 {
+    static constexpr bool KC = false;
+    Segment seg;
+    int H, W, P, Q, S, pad, Cs, rows, Ns;
+    PixelStep s16, s64;
+    // position (image, row, column) of this thread's first pixel of the K tile it last issued; the tiles of a work item
+    // are issued in order, each 64 pixels after the one before
+    mutable int n_, p_, q_;
+    __device__ __forceinline__ static void step(const PixelStep &d, int P, int Q, int &n, int &p, int &q)
+    {
+        q += d.dq;
+        const int cq = q >= Q;
+        q -= cq ? Q : 0;
+        p += d.dp + cq;
+        const int cp = p >= P;
+        p -= cp ? P : 0;
+        n += d.dn + cp;
+    }
+    template <int ROWS> __device__ __forceinline__ void issue(int row0, int k0, char *lds) const
+    {
+        static_assert(ROWS == 256, "tile side");
+        int kshift;
+        const char *base = seg.locate(k0, &kshift);
+        const int tid = threadIdx.x, wave = tid >> 6;
+        const int kr = tid >> 5, pc = tid & 31;
+        int r0 = row0 + ((pc ^ ((kr & 3) << 1)) << 3);
+        r0 = r0 < rows ? r0 : rows - 8;
+        const int tap = r0 / Cs, c0 = r0 - tap * Cs;
+        const int fr = tap / S, dy = fr - pad, dx = tap - fr * S - pad;
+        if (k0 == 0) {
+            const int kl = kshift + kr; // pixel inside the shard
+            n_ = kl / (P * Q);
+            const int rem = kl - n_ * (P * Q);
+            p_ = rem / Q;
+            q_ = rem - p_ * Q;
+        } else {
+            step(s64, P, Q, n_, p_, q_);
+            n_ -= n_ >= Ns ? Ns : 0; // the run went on into the next shard
+        }
+        int n = n_, p = p_, q = q_;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int iy = p + dy, ix = q + dx;
+            const bool ok = iy >= 0 && iy < H && ix >= 0 && ix < W;
+            const char *a = base + ((size_t)((n * H + iy) * W + ix) * (size_t)Cs + (size_t)c0) * 2;
+            core2::load_chunk_to_lds(ok ? (const void *)a : (const void *)core2::g_zero_chunk,
+                                     lds + (size_t)(wave * 64 + i * core2::kThreads2) * 16);
+            step(s16, P, Q, n, p, q);
+        }
+    }
+};
+
+__device__ __forceinline__ PixelStep pixel_step(int d, int P, int Q)
+{
+    PixelStep s;
+    s.dn = d / (P * Q);
+    const int rem = d - s.dn * (P * Q);
+    s.dp = rem / Q;
+    s.dq = rem - s.dp * Q;
+    return s;
+}
+
+__global__ __launch_bounds__(core2::kThreads2, 2) void conv_wgrad_split2_kernel(const WgradSplitParams w)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    const ConvParams &p = w.c;
+    const int logical = core::logical_block(p.per_xcd, p.total);
+    if (logical < 0) return;
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int bp = logical / tiles, r = logical - bp * tiles;
+    const int blk = bp / w.sp.parts, part = bp - blk * w.sp.parts;
+    const int n0 = (r % p.tiles_n) * 256, m0 = (r / p.tiles_n) * 256;
+    const int G = w.sp.nred * w.sp.ktps;
+    const int g0 = (int)((int64_t)part * G / w.sp.parts), g1 = (int)((int64_t)(part + 1) * G / w.sp.parts);
+    const int K = (g1 - g0) * core::BK;
+    const ConvGeom &g = p.g;
+    SegDenseRC2 la;
+    la.seg.bind(w.c.A, w.sp.red_ids, w.sp.blk_ids[blk], w.sp.nred, w.sp.ktps, g0);
+    la.ld = g.Ks; la.rows = p.M;
+    SegGatherRC2 lb;
+    lb.seg.bind(w.c.B, w.sp.red_ids, w.sp.blk_ids[blk], w.sp.nred, w.sp.ktps, g0);
+    lb.H = g.H; lb.W = g.W; lb.P = g.P; lb.Q = g.Q; lb.S = g.S; lb.pad = g.pad; lb.Cs = g.Cs; lb.rows = p.N; lb.Ns = g.Ns;
+    lb.s16 = pixel_step(16, g.P, g.Q);
+    lb.s64 = pixel_step(64, g.P, g.Q);
+    lb.n_ = lb.p_ = lb.q_ = 0;
+    core2::tile_product2<false, true>(la, lb, p.C[bp], p.ldc, p.M, p.N, K, m0, n0, false, reinterpret_cast<char *>(smem));
 }
 
 // Filters [Ks][R][S][Cs] -> [Cs][R][S][Ks] with the taps reversed: with these the gradient w.r.t. the input IS a forward
@@ -431,6 +671,74 @@ tt_status launch_conv(int op, int count, const void *const *A, const void *const
     }
     if (op == TT_OP_DGRAD) return obf ? launch_gather_a<1, true>(p, count, s) : launch_gather_a<1, false>(p, count, s);
     return obf ? launch_wgrad<true>(p, count, s) : launch_wgrad<false>(p, count, s);
+}
+
+
+// Weight-gradient products of all output blocks with each block's pixel range cut into `parts` partial sums (see
+// SplitGeom).  A, B: dY and X shards by shard id (2^k entries); C: nblk * parts fp32 buffers of Ks x (R*S*Cs), buffer
+// blk * parts + part.  blk_ids / red_ids: id bits of block b / of a block's q-th shard.  Ns images per shard; the pixels
+// of a shard must be a multiple of 64 (TT_EUNSUPPORTED otherwise: the caller takes the per-shard path).
+tt_status launch_conv_wgrad_split(int k, int nblk, int nred, const uint8_t *blk_ids, const uint8_t *red_ids, int parts,
+                                  const void *const *A, const void *const *B, void *const *C, int64_t Ns, int64_t Cs,
+                                  int64_t Ks, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad, int engine,
+                                  void *stream)
+{
+    if (engine != 1 && engine != 2) return TT_EINVAL;
+    if (!A || !B || !C || !blk_ids || !red_ids || !valid_k(k) || nblk < 1 || nred < 1 || nblk * nred != (1 << k)) return TT_EINVAL;
+    if (parts < 1 || nblk * parts > kMaxShards) return TT_EINVAL;
+    if (Ns <= 0 || Cs <= 0 || Ks <= 0 || H <= 0 || W <= 0 || R <= 0 || S <= 0 || pad < 0) return TT_EINVAL;
+    const int64_t P = H + 2 * pad - R + 1, Q = W + 2 * pad - S + 1;
+    if (P <= 0 || Q <= 0) return TT_EINVAL;
+    if (Cs % 8 || Ks % 8 || R * S > 32 || Ks <= 128) return TT_EUNSUPPORTED;
+    const int64_t lim = int64_t(1) << 30, pixels = Ns * P * Q;
+    if (Ns * H * W * Cs >= lim || pixels * Ks >= lim || Ks * R * S * Cs >= lim) return TT_EUNSUPPORTED;
+    if (pixels % core::BK || (int64_t)nred * (pixels / core::BK) < parts) return TT_EUNSUPPORTED;
+    {
+        // shards one work item can touch: its K tiles, rounded up to whole shards, plus one for a start inside a shard
+        const int64_t ktps = pixels / core::BK, len = (nred * ktps + parts - 1) / parts;
+        if ((len + ktps - 1) / ktps + 1 > kSegs && nred > kSegs) return TT_EUNSUPPORTED;
+    }
+    const int n = 1 << k;
+    if (!aligned16(A, n) || !aligned16(B, n) || !aligned16(const_cast<const void *const *>(C), nblk * parts)) return TT_EUNSUPPORTED;
+
+    WgradSplitParams w;
+    ConvParams &p = w.c;
+    for (int i = 0; i < kMaxShards; ++i) {
+        p.A[i] = i < n ? A[i] : nullptr;
+        p.B[i] = i < n ? B[i] : nullptr;
+        p.C[i] = i < nblk * parts ? C[i] : nullptr;
+        w.sp.red_ids[i] = i < nred ? red_ids[i] : 0;
+        w.sp.blk_ids[i] = i < nblk ? blk_ids[i] : 0;
+        if ((i < nred && red_ids[i] >= n) || (i < nblk && blk_ids[i] >= n)) return TT_EINVAL;
+    }
+    p.g = ConvGeom{(int32_t)Ns, (int32_t)H, (int32_t)W, (int32_t)P, (int32_t)Q, (int32_t)R, (int32_t)S, (int32_t)pad,
+                   (int32_t)Cs, (int32_t)Ks};
+    p.relu = 0;
+    p.M = (int32_t)Ks; p.N = (int32_t)(R * S * Cs); p.K = (int32_t)pixels; p.ldc = p.N;
+    w.sp.parts = parts; w.sp.nred = nred; w.sp.ktps = (int32_t)(pixels / core::BK);
+    const uint64_t x_b = (uint64_t)(Ns * H * W * Cs) * 2, y_b = (uint64_t)(pixels * Ks) * 2, w_b = (uint64_t)(Ks * R * S * Cs) * 4;
+    ProfileScope scope(stream, TT_K_CONV_WGRAD, n, p.M, p.N, p.K, (x_b + y_b) * (uint64_t)n + w_b * (uint64_t)(nblk * parts),
+                       2ull * (uint64_t)p.M * (uint64_t)p.N * (uint64_t)p.K * (uint64_t)n);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    // engine 1: register-staged, 256 x 128 tiles, four waves, two workgroups per CU (the tile the per-shard weight
+    // gradient uses); engine 2: straight into LDS, 256 x 256 tiles, eight waves, one workgroup per CU
+    p.tiles_m = (p.M + 255) / 256;
+    p.tiles_n = (p.N + (engine == 2 ? 255 : 127)) / (engine == 2 ? 256 : 128);
+    const int64_t total = (int64_t)p.tiles_m * p.tiles_n * nblk * parts;
+    if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
+    p.total = (int32_t)total;
+    p.per_xcd = (int32_t)((total + kXcds - 1) / kXcds);
+    if (engine == 2) {
+        auto kern = conv_wgrad_split2_kernel;
+        if (ensure_dynamic_lds(reinterpret_cast<const void *>(kern), core2::kSmemBytes) != TT_OK) return TT_EDEVICE;
+        hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * kXcds), dim3(core2::kThreads2), core2::kSmemBytes, s, w);
+    } else {
+        auto kern = conv_wgrad_split_kernel<256, 128, 2, 2>;
+        constexpr size_t sm = core::smem_bytes<256, 128>();
+        if (ensure_dynamic_lds(reinterpret_cast<const void *>(kern), sm) != TT_OK) return TT_EDEVICE;
+        hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * kXcds), dim3(256), sm, s, w);
+    }
+    return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
 }
 
 } // namespace tt

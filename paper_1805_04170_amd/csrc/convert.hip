@@ -183,8 +183,8 @@ template <int EV> struct FVec;
 template <> struct FVec<4> { using type = f32x4; };
 template <> struct FVec<1> { using type = float; };
 
-// CHUNK partial buffers are read per round with all loads in flight together (the partial count is a power of two and
-// a multiple of CHUNK); lanes past the end of a piece read a clamped in-range address and store nothing.
+// CHUNK partial buffers are read per round with all loads in flight together (a last round may be shorter: the count
+// need not be a multiple of CHUNK); lanes past the end of a piece read a clamped in-range address and store nothing.
 template <int EV, bool OUT_BF16, int U, int CHUNK>
 __global__ __launch_bounds__(kThreads) void reduce_kernel(const ReduceParams p)
 {
@@ -221,11 +221,12 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(const ReduceParams p)
         if (cv >= p.piece_cv) { cv -= p.piece_cv; ++row; }
     }
     // partial sums are added in increasing partial number: a fixed order, independent of the launch shape
-    for (uint32_t q0 = 0; q0 < p.nred * p.ksplit; q0 += CHUNK) {
+    const uint32_t total = p.nred * p.ksplit;
+    for (uint32_t q0 = 0; q0 < total; q0 += CHUNK) {
         FV v[CHUNK][U];
 #pragma unroll
         for (int j = 0; j < CHUNK; ++j) {
-            const uint32_t qq = q0 + j, q = qq / p.ksplit, c = qq - q * p.ksplit;
+            const uint32_t qq = q0 + j < total ? q0 + j : total - 1, q = qq / p.ksplit, c = qq - q * p.ksplit;
             const FV *src = reinterpret_cast<const FV *>(p.part[(sz.shard | p.red_ids[q]) * p.ksplit + c]);
 #pragma unroll
             for (int u = 0; u < U; ++u) v[j][u] = __builtin_nontemporal_load(src + soff[u]);
@@ -234,6 +235,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(const ReduceParams p)
         for (int j = 0; j < CHUNK; ++j)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                if (q0 + j >= total) continue; // short last round (wave-uniform): the re-read buffer is not added again
                 if constexpr (EV == 4) {
                     acc[u][0] += v[j][u].x; acc[u][1] += v[j][u].y; acc[u][2] += v[j][u].z; acc[u][3] += v[j][u].w;
                 } else {
@@ -401,8 +403,8 @@ template <int EV, bool OUT_BF16, int U> static tt_status launch_reduce_u(const R
 {
     const uint32_t total = p.nred * p.ksplit;
     if (total >= 8) hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, U, 8>), dim3(blocks), dim3(kThreads), 0, s, p);
-    else if (total == 4) hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, U, 4>), dim3(blocks), dim3(kThreads), 0, s, p);
-    else if (total == 2) hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, U, 2>), dim3(blocks), dim3(kThreads), 0, s, p);
+    else if (total >= 4) hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, U, 4>), dim3(blocks), dim3(kThreads), 0, s, p);
+    else if (total >= 2) hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, U, 2>), dim3(blocks), dim3(kThreads), 0, s, p);
     else hipLaunchKernelGGL((reduce_kernel<EV, OUT_BF16, U, 1>), dim3(blocks), dim3(kThreads), 0, s, p);
     return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
 }
@@ -416,9 +418,10 @@ template <int EV, bool OUT_BF16> static tt_status launch_reduce_e(const ReducePa
 }
 
 tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, const float *const *partials,
-                        const uint8_t *zl, int k, int64_t rows, int64_t cols, int act, int ksplit, void *stream)
+                        const uint8_t *zl, int k, int64_t rows, int64_t cols, int act, int ksplit, void *stream, bool per_block)
 {
-    if (ksplit < 1 || (ksplit & (ksplit - 1)) != 0 || (ksplit << k) > kMaxShards) return TT_EINVAL; // the partial count must be a power of two
+    // in-shard splits come in powers of two (the launch code that cuts K makes no others); per-block partial sums in any number
+    if (ksplit < 1 || (!per_block && (ksplit & (ksplit - 1)) != 0) || (ksplit << k) > kMaxShards) return TT_EINVAL;
     if (!dst || !partials || !valid_k(k) || rows < 0 || cols < 0) return TT_EINVAL;
     if (rows == 0 || cols == 0) return TT_OK;
     if (out_dtype != TT_F32 && out_dtype != TT_BF16) return TT_EINVAL;
@@ -429,19 +432,24 @@ tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, cons
     const int n = 1 << k;
     for (int s = 0; s < n; ++s)
         if (!dst[s]) return TT_EINVAL;
-    for (int s = 0; s < n * ksplit; ++s)
-        if (!partials[s]) return TT_EINVAL;
+    // per_block: only the table entries of shard ids with zero bits at the kRed cuts are used
+    for (int s = 0; s < n; ++s)
+        for (int c = 0; c < ksplit; ++c)
+            if (!(per_block && ((uint32_t)s & Z.maskX)) && !partials[s * ksplit + c]) return TT_EINVAL;
     int64_t piece_rows = Z.srows < B.srows ? Z.srows : B.srows;
     int64_t piece_cols = Z.scols < B.scols ? Z.scols : B.scols;
     const size_t out_b = out_dtype == TT_BF16 ? 2 : 4;
     int ev = 4;
-    if (piece_cols % 4 || !aligned_all(reinterpret_cast<const void *const *>(partials), n * ksplit, 16) ||
+    bool parts_aligned = true;
+    for (int s = 0; s < n * ksplit; ++s)
+        if (!(per_block && ((uint32_t)(s / ksplit) & Z.maskX)) && reinterpret_cast<uintptr_t>(partials[s]) % 16) parts_aligned = false;
+    if (piece_cols % 4 || !parts_aligned ||
         !aligned_all(const_cast<const void *const *>(dst), n, 4 * out_b))
         ev = 1;
 
     ReduceParams p;
     for (int s = 0; s < kMaxShards; ++s) {
-        p.part[s] = s < n * ksplit ? partials[s] : nullptr;
+        p.part[s] = (s < n * ksplit && !(per_block && ((uint32_t)(s / ksplit) & Z.maskX))) ? partials[s] : nullptr;
         p.dst[s] = s < n ? dst[s] : nullptr;
         p.rep_ids[s] = 0;
         p.red_ids[s] = 0;
@@ -450,11 +458,11 @@ tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, cons
     p.B = to_dev(B, ev);
     p.k = (uint32_t)k;
     p.nrep = 1u << B.kX;
-    p.nred = 1u << Z.kX;
+    p.nred = per_block ? 1u : 1u << Z.kX;
     p.ksplit = (uint32_t)ksplit;
     p.relu = act == TT_ACT_RELU;
     for (uint32_t r = 0; r < p.nrep; ++r) p.rep_ids[r] = (uint8_t)deposit(r, B.maskX, k);
-    for (uint32_t q = 0; q < p.nred; ++q) p.red_ids[q] = (uint8_t)deposit(q, Z.maskX, k);
+    for (uint32_t q = 0; q < p.nred; ++q) p.red_ids[q] = per_block ? 0 : (uint8_t)deposit(q, Z.maskX, k);
     const int64_t piece_cv = piece_cols / ev;
     uint64_t piece_vecs = (uint64_t)piece_rows * (uint64_t)piece_cv;
     if (piece_vecs >= (uint64_t(1) << 31)) return TT_EUNSUPPORTED;
@@ -462,7 +470,7 @@ tt_status launch_reduce(void *const *dst, const uint8_t *Bl, int out_dtype, cons
     // Vectors per lane, measured on MI355X (256 x 1000 .. 512 x 8192 outputs, 2 .. 16 partial sums): one below 128 K
     // vectors (more workgroups matter more than loads in flight), two up to a million; above that two for one or two
     // partial sums, four for four (16 loads in flight per lane), one for eight or more (already eight in flight).
-    const uint32_t n_part = (1u << Z.kX) * (uint32_t)ksplit;
+    const uint32_t n_part = p.nred * (uint32_t)ksplit;
     int unroll = 1;
     if (unique_vecs >= (uint64_t)1 << 20) unroll = n_part >= 8 ? 1 : (n_part == 4 ? 4 : 2);
     else if (unique_vecs >= (uint64_t)1 << 17) unroll = 2;

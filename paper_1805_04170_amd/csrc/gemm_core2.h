@@ -33,7 +33,10 @@ using dev::s16x4;
 
 __device__ __attribute__((aligned(16))) const uint32_t g_zero_chunk[4] = {0, 0, 0, 0};
 
-// ---- dense loaders: address of one 16-byte chunk ----
+template <int ROWS, class L> __device__ __forceinline__ void issue_tile(const L &ld, int row0, int k0, char *lds);
+
+// ---- loaders.  A loader issues the global -> LDS loads of one operand tile through issue<ROWS>(row0, k0, lds); the dense
+// ---- ones below name the address of one 16-byte chunk and leave the walk over the tile to issue_tile ----
 // KC: rows of the operand have K contiguous.  chunk(row, k): 8 consecutive k of one row.
 struct DenseKC2 {
     static constexpr bool KC = true;
@@ -45,6 +48,7 @@ struct DenseKC2 {
         const char *p = base + ((size_t)row * ld + k) * 2;
         return k < K ? (const void *)p : (const void *)g_zero_chunk;
     }
+    template <int ROWS> __device__ __forceinline__ void issue(int row0, int k0, char *lds) const { issue_tile<ROWS>(*this, row0, k0, lds); }
 };
 // RC: rows contiguous, K strides.  chunk(k, row0): rows row0..row0+7 at one k.
 struct DenseRC2 {
@@ -57,6 +61,7 @@ struct DenseRC2 {
         const char *p = base + ((size_t)k * ld + row0) * 2;
         return k < K ? (const void *)p : (const void *)g_zero_chunk;
     }
+    template <int ROWS> __device__ __forceinline__ void issue(int row0, int k0, char *lds) const { issue_tile<ROWS>(*this, row0, k0, lds); }
 };
 
 __device__ __forceinline__ void load_chunk_to_lds(const void *g, char *lds_wave_base)
@@ -125,16 +130,16 @@ __device__ __forceinline__ void tile_product2(const LA &la, const LB &lb, void *
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
     const int nk = (K + BK - 1) / BK;
-    issue_tile<BM2>(la, m0, 0, smem);
-    issue_tile<BN2>(lb, n0, 0, smem + A_BYTES);
+    la.template issue<BM2>(m0, 0, smem);
+    lb.template issue<BN2>(n0, 0, smem + A_BYTES);
 
     for (int kt = 0; kt < nk; ++kt) {
         char *cur = smem + (kt & 1) * kStageBytes, *nxt = smem + ((kt & 1) ^ 1) * kStageBytes;
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's chunks of tile kt have landed
         __syncthreads();                     // everyone's have; and everyone is done reading the other stage
         if (kt + 1 < nk) {
-            issue_tile<BM2>(la, m0, (kt + 1) * BK, nxt);
-            issue_tile<BN2>(lb, n0, (kt + 1) * BK, nxt + A_BYTES);
+            la.template issue<BM2>(m0, (kt + 1) * BK, nxt);
+            lb.template issue<BN2>(n0, (kt + 1) * BK, nxt + A_BYTES);
         }
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_iglp_opt(1);

@@ -69,6 +69,36 @@ tt_status filter_view(Sharded *s, const void *const *ptrs, const tt_tiling &t, i
     return TT_OK;
 }
 
+// Number of partial sums per filter block, and the tile engine, for the weight gradient with an evenly cut reduction
+// range; parts = 0 when that path does not apply.  The work items (output tiles times partial sums) run in rounds of as
+// many as the chip holds; a round takes as long as one item's K tiles; every partial sum is written and read once more by
+// the reduction.  Times in microseconds from measured rates on MI355X with the chip full: engine 1 (256 x 128 tiles, 512
+// resident) 3.9 us per K tile, engine 2 (256 x 256 tiles, 256 resident) 2.6 us; partial sums at 4 TB/s.
+struct WgradChoice { int parts, engine; };
+WgradChoice pick_wgrad_parts(int k, int nblk, int nred, int64_t ktps, int64_t Ks, int64_t ncols, size_t blk_bytes)
+{
+    const int64_t total_kt = (int64_t)nred * ktps;
+    const int max_parts = kMaxShards >> k;
+    WgradChoice best{0, 1};
+    double best_us = 0.0;
+    const int forced = tuning_int("TT_WGRAD_PARTS", 0), forced_engine = tuning_int("TT_WGRAD_ENGINE", 0); // development builds only
+    for (int engine = 1; engine <= 2; ++engine) {
+        if (forced_engine && engine != forced_engine) continue;
+        const int64_t tile_n = engine == 2 ? 256 : 128, resident = engine == 2 ? 256 : 512;
+        const double kt_us = engine == 2 ? 2.6 : 3.9;
+        const int64_t tiles = ((Ks + 255) / 256) * ((ncols + tile_n - 1) / tile_n);
+        for (int parts = 1; parts <= max_parts && parts <= total_kt; ++parts) {
+            const int64_t len = (total_kt + parts - 1) / parts;
+            if (nred > 4 && (len + ktps - 1) / ktps + 1 > 4) continue; // an item may touch at most four shards
+            if (parts == forced) return WgradChoice{parts, engine};
+            const int64_t rounds = (nblk * tiles * parts + resident - 1) / resident;
+            const double us = (double)rounds * (double)len * kt_us + (double)nblk * parts * (double)blk_bytes * 2.0 / 4.0e6;
+            if (best.parts == 0 || us < best_us) { best = WgradChoice{parts, engine}; best_us = us; }
+        }
+    }
+    return best;
+}
+
 tt_status forward(const ConvArgs &a, const Dims &d, Workspace &ws)
 {
     const int k = a.k, n = 1 << k;
@@ -159,12 +189,43 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
         uint8_t zl[TT_MAX_K];
         for (int j = 0; j < k; ++j) zl[j] = f[j] == TT_F1 ? TT_C : (f[j] == TT_F2 ? TT_R : kRed);
         const tt_tiling tWs = transpose_tiling(a.tW, k);
-        // The reduction of this product runs over every pixel of every image of the shard.  Where the filter block of a
-        // shard gives too few output tiles to occupy the chip (input or output channels cut, the batch not), the images of
-        // a shard are dealt to `split` sub-products, each writing its own fp32 partial sum, which the reduction kernel adds
-        // up together with the partial sums of the F3 cuts.  A sub-product is the same product on a slice of the two
-        // operands: both are image-major, so the slice is an offset into the shard.
+        // The reduction of this product runs over every pixel of every image of the shard.
         const int64_t Ns = d.N >> k3, Cs = d.C >> k1, Ks = d.K >> k2;
+        // First choice: the pixels of all shards that add up into one filter block form one reduction range, cut into
+        // `parts` equal runs (pick_wgrad_parts; conv.hip says why that is free).  The partial sums then belong to a block,
+        // not to a shard: buffer c of block b sits at table entry (b's shard id with zero F3 bits) * parts + c, which is
+        // where the reduction kernel looks for it.
+        Grid gz;
+        if (!make_grid(zl, k, d.K * rs, d.C, &gz)) return TT_EINFEASIBLE;
+        const int nred = 1 << gz.kX, nblk = n >> gz.kX;
+        const size_t blk_bytes = (size_t)gz.srows * (size_t)gz.scols * 4;
+        const WgradChoice choice = (Ns * pq) % 64 == 0 && Ks > 128 ? pick_wgrad_parts(k, nblk, nred, Ns * pq / 64, Ks, rs * Cs, blk_bytes)
+                                                                     : WgradChoice{0, 1};
+        const int parts = choice.parts;
+        if (parts > 0 && !(parts == 1 && nred == 1)) {
+            uint8_t blk_ids[kMaxShards], red_ids[kMaxShards];
+            const uint32_t mask_blk = ((1u << k) - 1u) & ~gz.maskX;
+            for (int b = 0; b < nblk; ++b) blk_ids[b] = (uint8_t)deposit((uint32_t)b, mask_blk, k);
+            for (int q = 0; q < nred; ++q) red_ids[q] = (uint8_t)deposit((uint32_t)q, gz.maskX, k);
+            void *sums[kMaxShards];        // as the product numbers them: blk * parts + part
+            const float *table[kMaxShards]; // as the reduction looks them up
+            for (int i = 0; i < kMaxShards; ++i) table[i] = nullptr;
+            for (int b = 0; b < nblk; ++b)
+                for (int c = 0; c < parts; ++c) {
+                    sums[b * parts + c] = ws.take(blk_bytes);
+                    table[blk_ids[b] * parts + c] = static_cast<const float *>(sums[b * parts + c]);
+                }
+            if (ws.overflow) return TT_EWORKSPACE;
+            if (ws.dry) return TT_OK;
+            st = launch_conv_wgrad_split(k, nblk, nred, blk_ids, red_ids, parts, Ga.ptr, Xa.ptr, sums, Ns, Cs, Ks, d.H, d.W, d.R,
+                                         d.S, d.pad, choice.engine, a.stream);
+            if (st != TT_OK) return st; // (the shapes were checked above with the launcher's own conditions)
+            return launch_reduce(a.dW, tWs.cut, a.dtype, table, zl, k, d.K * rs, d.C, TT_ACT_NONE, parts, a.stream, true);
+        }
+        // Otherwise: where the filter block of a shard gives too few output tiles to occupy the chip (input or output
+        // channels cut, the batch not), the images of a shard are dealt to `split` sub-products, each writing its own fp32
+        // partial sum, which the reduction kernel adds up together with the partial sums of the F3 cuts.  A sub-product is
+        // the same product on a slice of the two operands: both are image-major, so the slice is an offset into the shard.
         int split = 1;
         {
             const int64_t tiles = ((Ks + 255) / 256) * ((rs * Cs + 127) / 128) * n; // 256 x 128 tiles of the filter gradient

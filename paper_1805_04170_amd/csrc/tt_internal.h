@@ -119,10 +119,12 @@ tt_status launch_convert(void *const *dst, const uint8_t *B, const void *const *
                          const void *const *mask, const uint8_t *Am, int k, int64_t rows, int64_t cols,
                          int elem_bytes, int gate_dtype, bool dst_unique /* replicas of B alias one buffer */,
                          void *stream);
-// ksplit > 1: every shard comes as ksplit partial buffers (partials[s * ksplit + c]) that are summed as well
+// ksplit > 1: every shard comes as ksplit partial buffers (partials[s * ksplit + c]) that are summed as well.
+// per_block: the partial sums of an output block are not held shard by shard but as ksplit buffers per block (any
+// ksplit >= 1), partials[b * ksplit + c] with b the block's shard id with zero bits at the kRed cuts.
 tt_status launch_reduce(void *const *dst, const uint8_t *B, int out_dtype, const float *const *partials,
                         const uint8_t *zletters /* R, C or kRed per cut */, int k, int64_t rows, int64_t cols, int act,
-                        int ksplit, void *stream);
+                        int ksplit, void *stream, bool per_block = false);
 // ksplit > 1: each shard's K range is cut into ksplit chunks; chunk c of shard s writes C[s * ksplit + c]
 tt_status launch_gemm(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
                       int64_t K, int trans_a, int trans_b, int in_dtype, int out_dtype, int act, int ksplit,
@@ -149,6 +151,16 @@ tt_status launch_gemm_v4(int count, const void *const *A, const void *const *B, 
 tt_status launch_conv(int op, int count, const void *const *A, const void *const *B, void *const *C, int64_t Ns,
                       int64_t Cs, int64_t Ks, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad, int out_dtype,
                       int act, void *stream, void *const *flip_ws = nullptr);
+
+// Weight-gradient products with every output block's reduction over pixels (the pixels of all shards that an F3 cut
+// makes add up into that block) cut into `parts` equal runs, one fp32 partial sum each (conv.hip).  A = dY shards and
+// B = X shards by shard id; C[blk * parts + part]; blk_ids[b] / red_ids[q]: id bits of block b / of a block's q-th shard.
+// TT_EUNSUPPORTED when the shapes do not fit (the caller takes launch_conv).
+tt_status launch_conv_wgrad_split(int k, int nblk, int nred, const uint8_t *blk_ids, const uint8_t *red_ids, int parts,
+                                  const void *const *A, const void *const *B, void *const *C, int64_t Ns, int64_t Cs,
+                                  int64_t Ks, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad,
+                                  int engine /* 1: 256 x 128 tiles, two workgroups per CU; 2: 256 x 256, straight into LDS */,
+                                  void *stream);
 
 // ---- optional kernel timing (profile.cpp).  A scope object brackets one launch with two events when the calling
 // thread has recording switched on; otherwise it does nothing.

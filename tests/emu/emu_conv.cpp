@@ -32,6 +32,33 @@ int main(int argc, char **argv)
     const int relu = std::atoi(argv[12]);
     const bool flip = std::atoi(argv[13]) != 0;
     const long P = H + 2 * pad - R + 1, Q = W + 2 * pad - S + 1;
+    if (op == 3) {
+        // the filter gradient with every block's reduction range cut into `parts` runs: the arguments after pad are
+        // parts, shards per block, engine; the F3 cuts are taken to be the innermost ones (low id bits)
+        const int parts = std::atoi(argv[11]), nred = std::atoi(argv[12]), nblk = count / nred, engine = std::atoi(argv[13]);
+        int k = 0;
+        while ((1 << k) < count) ++k;
+        std::vector<uint8_t> blk_ids(nblk), red_ids(nred);
+        for (int b = 0; b < nblk; ++b) blk_ids[b] = (uint8_t)(b * nred);
+        for (int q = 0; q < nred; ++q) red_ids[q] = (uint8_t)q;
+        const size_t xb = (size_t)Ns * H * W * Cs * 2, yb = (size_t)Ns * P * Q * Ks * 2, cb = (size_t)Ks * R * S * Cs * 4;
+        std::vector<std::vector<char>> A(count), B(count), C(nblk * parts);
+        std::vector<const void *> Ap, Bp;
+        std::vector<void *> Cp;
+        for (int s = 0; s < count; ++s) {
+            A[s].assign(yb, 0); B[s].assign(xb, 0);
+            Ap.push_back(A[s].data()); Bp.push_back(B[s].data());
+        }
+        for (auto &c : C) { c.assign(cb, (char)0x5a); Cp.push_back(c.data()); }
+        const tt_status st = tt::launch_conv_wgrad_split(k, nblk, nred, blk_ids.data(), red_ids.data(), parts, Ap.data(), Bp.data(),
+                                                         Cp.data(), Ns, Cs, Ks, H, W, R, S, pad, engine, nullptr);
+        if (st != TT_OK) { std::printf("status %d\n", (int)st); return 2; }
+        for (size_t b = 0; b < C.size(); ++b)
+            for (size_t i = 0; i < C[b].size(); ++i)
+                if (C[b][i] != 0) { std::printf("partial sum %zu byte %zu never written\n", b, i); return 1; }
+        std::printf("ok conv op 3: %llu threads run\n", g_emu_threads_run);
+        return 0;
+    }
     const size_t x_b = (size_t)Ns * H * W * Cs * 2, y_b = (size_t)Ns * P * Q * Ks * 2, w_b = (size_t)Ks * R * S * Cs * 2;
     const size_t ob = obf ? 2 : 4;
     size_t a_b, b_b, c_b;

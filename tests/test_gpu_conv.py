@@ -117,6 +117,15 @@ def test_other_filter_shapes():
     run_conv(8, 64, 128, 6, 6, 3, 3, 1, 1, True, "r", "C", "C", "C", "r", "2", "3", "2", 134)           # 64 output channels per shard: 256 x 64 tiles
 
 
+def test_weight_gradient_with_the_reduction_range_cut_evenly():
+    # more than 128 output channels per shard and a multiple of 64 pixels per shard: the pixels of all shards that add up
+    # into one filter block are cut into equal runs, which may start in one shard and end in the next
+    run_conv(8, 16, 160, 8, 8, 3, 3, 1, 3, False, "RRR", "rrr", "RRR", "RRR", "RRR", "111", "111", "333", 140)     # batch split: one block, eight shards
+    run_conv(8, 32, 320, 8, 8, 3, 3, 1, 2, True, "RC", "Cr", "rR", "CR", "RR", "13", "31", "32", 141)             # two blocks of two shards each
+    run_conv(4, 64, 136, 8, 16, 3, 3, 1, 2, True, "rr", "RR", "rr", "rr", "CC", "33", "22", "11", 142)            # no F3 cut: the range of one shard cut into parts
+    run_conv(16, 16, 264, 4, 4, 1, 1, 0, 1, False, "R", "r", "R", "R", "R", "1", "1", "3", 143)                    # 1x1 filters, 16 pixels per image, two row tiles
+
+
 def test_refusals():
     lay = tt.layer("conv", "none", 12, 16, H=4, W=4, R=3, S=3, pad=1)       # 12 channels: no 16-byte channel vectors
     x = [torch.zeros(4096, dtype=torch.bfloat16, device=DEV)]

@@ -206,6 +206,18 @@ CONV_CASES = [
     (0, 1, 1, 8, 8, 6, 6, 5, 5, 0, 1, 1, 0),           # 25 taps, no padding
     (0, 4, 2, 64, 64, 12, 12, 1, 1, 0, 1, 0, 0),       # 1 x 1 filter: the one-tap loader
     (1, 4, 2, 64, 64, 12, 12, 1, 1, 0, 1, 0, 1),
+    # filter gradient with the reduction range of every block cut into equal runs (after pad: runs, shards per block,
+    # tile engine):
+    (3, 8, 8, 512, 512, 28, 28, 3, 3, 1, 7, 8, 1),     # conv4 cut along the batch: seven runs over the eight shards
+    (3, 8, 8, 512, 512, 28, 28, 3, 3, 1, 7, 8, 2),
+    (3, 8, 64, 64, 512, 28, 28, 3, 3, 1, 6, 1, 1),     # conv4 with the input channels cut: runs inside every shard
+    (3, 8, 64, 64, 512, 28, 28, 3, 3, 1, 8, 1, 2),
+    (3, 4, 3, 16, 136, 8, 8, 3, 3, 1, 5, 2, 1),        # runs of unequal length that cross from one shard into the next
+    (3, 4, 3, 16, 136, 8, 8, 3, 3, 1, 5, 2, 2),
+    (3, 8, 1, 8, 264, 8, 8, 3, 3, 1, 3, 8, 1),         # a run over three shards; two row tiles
+    (3, 8, 1, 8, 264, 8, 8, 3, 3, 1, 3, 8, 2),
+    (3, 2, 64, 8, 136, 7, 5, 5, 3, 2, 3, 2, 2),        # 7 x 5 images, 5 x 3 filter, padding 2: 49 output pixels per image
+    (3, 2, 64, 8, 136, 7, 5, 5, 3, 2, 3, 2, 1),
 ]
 
 

@@ -110,6 +110,22 @@ def test_conv_other_filter_shapes(on_host):
     on_host["conv"].test_other_filter_shapes()
 
 
+@pytest.mark.parametrize("engine", [1, 2])
+def test_conv_weight_gradient_with_the_reduction_range_cut_evenly(on_host, monkeypatch, engine):
+    monkeypatch.setenv("TT_WGRAD_ENGINE", str(engine))
+    on_host["conv"].test_weight_gradient_with_the_reduction_range_cut_evenly()
+
+
+@pytest.mark.parametrize("engine", [1, 2])
+@pytest.mark.parametrize("parts", [1, 2, 3, 5, 6, 7])
+def test_conv_weight_gradient_every_number_of_partial_sums(on_host, monkeypatch, parts, engine):
+    # the development build lets the test choose how many runs the reduction range is cut into: runs of unequal length,
+    # runs that start inside one shard and end inside another, one run over all four shards of a block; on both engines
+    monkeypatch.setenv("TT_WGRAD_PARTS", str(parts))
+    monkeypatch.setenv("TT_WGRAD_ENGINE", str(engine))
+    on_host["conv"].run_conv(12, 16, 272, 8, 8, 3, 3, 1, 3, True, "RRC", "rrR", "RRr", "RRC", "RRr", "112", "113", "332", 150 + parts)
+
+
 def test_conv_refusals(on_host):
     on_host["conv"].test_refusals()
 
