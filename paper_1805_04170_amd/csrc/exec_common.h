@@ -149,6 +149,10 @@ inline int pick_ksplit(int64_t M, int64_t N, int64_t K, int count, int dtype, bo
     const int64_t blocks = ((M + 255) / 256) * ((N + 255) / 256) * count; // 256 x 256 tiles, one per CU
     // chunks stay at least 512 deep, except where the launch would otherwise occupy under a quarter of the CUs (the
     // 1000-wide last layer): there chunks down to 192 still pay for the extra partial sums
+    // enough 256 x 128 tiles for the engine that runs two workgroups per CU: no split, so no partial sums to write and add
+    // (the first-layer data gradient of the VGG-16 classifier: 74 us and no reduction instead of 64 us + 17 us)
+    static const int min_half = tuning_int("TT_KSPLIT_HALF", 192);
+    if (min_half > 0 && ((M + 255) / 256) * ((N + 127) / 128) * count >= min_half) return 1;
     int s = 1;
     static const int min_blocks = tuning_int("TT_KSPLIT_BLOCKS", 200);
     while (blocks * s < min_blocks && s < 8 && K / (2 * s) >= (blocks * s < 64 ? 192 : 512) && count * 2 * s <= kMaxShards &&
