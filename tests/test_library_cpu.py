@@ -400,3 +400,15 @@ def test_counted_traffic_argument_errors():
     bad = [tt.layer("fc", "none", 8, 6), tt.layer("fc", "none", 5, 4)]                                # widths do not chain
     assert status(lambda: tt.tt_fc_chain_cross_elems(bad, 8, 1, ["R"] * 3, ["R"] * 3, ["r"] * 2, [["1", "1", "3"]] * 2)) == 1
     assert tt.tt_fc_chain_cross_elems(two, 8, 0, [""] * 3, [""] * 3, [""] * 2, [["", "", ""]] * 2) == 0   # one device: nothing moves
+
+
+def test_the_product_build_reads_no_environment():
+    # launch decisions are functions of the call's arguments alone: the library as built for use imports no getenv
+    # (tuning overrides exist only in builds with -DTT_TUNING, which the tests' host builds are)
+    import shutil
+    import subprocess
+    nm = shutil.which("nm")
+    if nm is None or not os.path.exists(tt.binding.LIB_PATH):
+        pytest.skip("no nm, or the library is not built")
+    syms = subprocess.run([nm, "-D", "--undefined-only", tt.binding.LIB_PATH], capture_output=True, text=True).stdout
+    assert "getenv" not in syms
