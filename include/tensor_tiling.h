@@ -300,8 +300,11 @@ tt_status tt_fc_backward_overlapped(const tt_layer *layer, int64_t batch, int k,
                                     const void *const *Y, const void *const *dY, void *const *dX, void *const *dW,
                                     void *workspace, size_t ws_bytes, void *stream, void *aux_stream);
 
-/* Convolution layer (layouts in tt_layer).  Supported cuts per product: F1 (batch), F2 (output channels for
- * forward, input channels for dgrad; out-channel / in-channel grid for wgrad), F3 (reduction split). */
+/* Convolution layer (layouts in tt_layer; the textbook stride-1 cross-correlation with zero padding, cut as Sec. 4.5
+ * says: batch and channels only).  Supported cuts per product: F1 (batch), F2 (output channels for forward, input
+ * channels for dgrad; out-channel / in-channel grid for wgrad), F3 (reduction split).  dtype TT_BF16: MFMA kernels,
+ * channel counts per shard multiples of 8 and R * S <= 32 (else TT_EUNSUPPORTED).  dtype TT_F32: plain kernels that
+ * follow the definition term by term, any channel count.  Arguments, ownership and errors as for tt_fc_*. */
 tt_status tt_conv_workspace_bytes(const tt_layer *layer, int64_t batch, int k, int dtype, int op, tt_tiling tX,
                                   tt_tiling tW, tt_tiling tY, tt_tiling tdY, tt_tiling tdX, const uint8_t *forms_a,
                                   const uint8_t *forms_b, int with_dx, size_t *bytes);

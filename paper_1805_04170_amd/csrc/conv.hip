@@ -512,6 +512,72 @@ __global__ __launch_bounds__(256) void filter_flip_tiled_kernel(const FlipParams
     }
 }
 
+// ---- fp32 convolutions: the definition, one output element per thread, fp32 fused multiply-adds in a fixed order
+// (taps outermost, channels or pixels innermost).  No tensor-core path exists for fp32 operands here; these kernels are
+// bound by plain arithmetic and serve small layers (the fp32 workload of the benchmark is a fully-connected stack).
+struct ConvF32Params {
+    const float *A[kMaxShards];
+    const float *B[kMaxShards];
+    void *C[kMaxShards];
+    ConvGeom g;
+    int32_t relu, out_bf16;
+    uint32_t per_shard; // output elements per shard
+};
+
+__device__ __forceinline__ void store_out(void *C, size_t i, float v, bool relu, bool out_bf16)
+{
+    if (relu) v = fmaxf(v, 0.0f);
+    if (out_bf16) reinterpret_cast<uint16_t *>(C)[i] = (uint16_t)core::f32_to_bf16_bits(v);
+    else reinterpret_cast<float *>(C)[i] = v;
+}
+
+// OP 0: Y[(n,p,q)][ko] from X and W;  1: dX[(n,h,w)][c] from dY and W;  2: dW[ko][(r,s,c)] from dY and X
+template <int OP> __global__ __launch_bounds__(256) void conv_f32_kernel(const ConvF32Params p)
+{
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= p.per_shard) return;
+    const int shard = blockIdx.y;
+    const ConvGeom &g = p.g;
+    const float *A = p.A[shard], *B = p.B[shard];
+    float acc = 0.0f;
+    if (OP == 0) {
+        const int ko = i % g.Ks, pix = i / g.Ks;
+        const int n = pix / (g.P * g.Q), rem = pix - n * (g.P * g.Q), oy = rem / g.Q, ox = rem - oy * g.Q;
+        for (int r = 0; r < g.R; ++r)
+            for (int s = 0; s < g.S; ++s) {
+                const int iy = oy + r - g.pad, ix = ox + s - g.pad;
+                if (iy < 0 || iy >= g.H || ix < 0 || ix >= g.W) continue;
+                const float *x = A + ((size_t)(n * g.H + iy) * g.W + ix) * g.Cs;
+                const float *w = B + ((size_t)(ko * g.R + r) * g.S + s) * g.Cs;
+                for (int c = 0; c < g.Cs; ++c) acc = fmaf(x[c], w[c], acc);
+            }
+    } else if (OP == 1) {
+        const int c = i % g.Cs, pix = i / g.Cs;
+        const int n = pix / (g.H * g.W), rem = pix - n * (g.H * g.W), h = rem / g.W, w_ = rem - h * g.W;
+        for (int r = 0; r < g.R; ++r)
+            for (int s = 0; s < g.S; ++s) {
+                const int oy = h + g.pad - r, ox = w_ + g.pad - s;
+                if (oy < 0 || oy >= g.P || ox < 0 || ox >= g.Q) continue;
+                const float *dy = A + ((size_t)(n * g.P + oy) * g.Q + ox) * g.Ks;
+                for (int ko = 0; ko < g.Ks; ++ko) acc = fmaf(dy[ko], B[((size_t)(ko * g.R + r) * g.S + s) * g.Cs + c], acc);
+            }
+    } else {
+        const int c = i % g.Cs, rest = i / g.Cs;
+        const int s = rest % g.S, rest2 = rest / g.S, r = rest2 % g.R, ko = rest2 / g.R;
+        for (int n = 0; n < g.Ns; ++n)
+            for (int oy = 0; oy < g.P; ++oy) {
+                const int iy = oy + r - g.pad;
+                if (iy < 0 || iy >= g.H) continue;
+                for (int ox = 0; ox < g.Q; ++ox) {
+                    const int ix = ox + s - g.pad;
+                    if (ix < 0 || ix >= g.W) continue;
+                    acc = fmaf(A[((size_t)(n * g.P + oy) * g.Q + ox) * g.Ks + ko], B[((size_t)(n * g.H + iy) * g.W + ix) * g.Cs + c], acc);
+                }
+            }
+    }
+    store_out(p.C[shard], i, acc, p.relu != 0, p.out_bf16 != 0);
+}
+
 template <typename Kern> tt_status launch(Kern kern, size_t smem, ConvParams &p, int BM, int BN, int threads, int count, hipStream_t s)
 {
     if (ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem) != TT_OK) return TT_EDEVICE;
@@ -606,13 +672,46 @@ bool aligned16(const void *const *ptrs, int n)
 // Shard geometry: Ns images, Cs input channels, Ks output channels per shard.
 tt_status launch_conv(int op, int count, const void *const *A, const void *const *B, void *const *C, int64_t Ns,
                       int64_t Cs, int64_t Ks, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad, int out_dtype,
-                      int act, void *stream, void *const *flip_ws)
+                      int act, void *stream, void *const *flip_ws, int in_dtype)
 {
     if (!A || !B || !C || count < 1 || count > kMaxShards) return TT_EINVAL;
     if (Ns <= 0 || Cs <= 0 || Ks <= 0 || H <= 0 || W <= 0 || R <= 0 || S <= 0 || pad < 0) return TT_EINVAL;
     const int64_t P = H + 2 * pad - R + 1, Q = W + 2 * pad - S + 1;
     if (P <= 0 || Q <= 0) return TT_EINVAL;
     if (out_dtype != TT_BF16 && out_dtype != TT_F32) return TT_EINVAL;
+    if (in_dtype != TT_BF16 && in_dtype != TT_F32) return TT_EINVAL;
+    if (in_dtype == TT_F32) {
+        if (op != TT_OP_FWD && op != TT_OP_DGRAD && op != TT_OP_WGRAD) return TT_EINVAL;
+        const int64_t lim32 = int64_t(1) << 31;
+        if (Ns * H * W * Cs >= lim32 || Ns * P * Q * Ks >= lim32 || Ks * R * S * Cs >= lim32) return TT_EUNSUPPORTED;
+        ConvF32Params f;
+        for (int i = 0; i < kMaxShards; ++i) {
+            if (i < count && (!A[i] || !B[i] || !C[i])) return TT_EINVAL;
+            f.A[i] = i < count ? static_cast<const float *>(A[i]) : nullptr;
+            f.B[i] = i < count ? static_cast<const float *>(B[i]) : nullptr;
+            f.C[i] = i < count ? C[i] : nullptr;
+        }
+        f.g = ConvGeom{(int32_t)Ns, (int32_t)H, (int32_t)W, (int32_t)P, (int32_t)Q, (int32_t)R, (int32_t)S, (int32_t)pad,
+                       (int32_t)Cs, (int32_t)Ks};
+        f.relu = act == TT_ACT_RELU;
+        f.out_bf16 = out_dtype == TT_BF16;
+        const int64_t outs = op == TT_OP_FWD ? Ns * P * Q * Ks : (op == TT_OP_DGRAD ? Ns * H * W * Cs : Ks * R * S * Cs);
+        f.per_shard = (uint32_t)outs;
+        const int64_t Mg = op == TT_OP_FWD ? Ns * P * Q : (op == TT_OP_DGRAD ? Ns * H * W : Ks);
+        const int64_t Ng = op == TT_OP_FWD ? Ks : (op == TT_OP_DGRAD ? Cs : R * S * Cs);
+        const int64_t Kg = op == TT_OP_FWD ? R * S * Cs : (op == TT_OP_DGRAD ? R * S * Ks : Ns * P * Q);
+        const uint64_t ob32 = out_dtype == TT_BF16 ? 2 : 4;
+        const uint64_t xb = (uint64_t)(Ns * H * W * Cs), yb = (uint64_t)(Ns * P * Q * Ks), wb = (uint64_t)(Ks * R * S * Cs);
+        const uint64_t bytes32 = op == TT_OP_FWD ? 4 * (xb + wb) + ob32 * yb : (op == TT_OP_DGRAD ? 4 * (yb + wb) + ob32 * xb : 4 * (yb + xb) + ob32 * wb);
+        ProfileScope scope(stream, op == TT_OP_FWD ? TT_K_CONV_FWD : (op == TT_OP_DGRAD ? TT_K_CONV_DGRAD : TT_K_CONV_WGRAD), count, Mg,
+                           Ng, Kg, bytes32 * (uint64_t)count, 2ull * (uint64_t)Mg * (uint64_t)Ng * (uint64_t)Kg * (uint64_t)count);
+        const dim3 grid((uint32_t)((outs + 255) / 256), (uint32_t)count);
+        hipStream_t s32 = reinterpret_cast<hipStream_t>(stream);
+        if (op == TT_OP_FWD) hipLaunchKernelGGL(conv_f32_kernel<0>, grid, dim3(256), 0, s32, f);
+        else if (op == TT_OP_DGRAD) hipLaunchKernelGGL(conv_f32_kernel<1>, grid, dim3(256), 0, s32, f);
+        else hipLaunchKernelGGL(conv_f32_kernel<2>, grid, dim3(256), 0, s32, f);
+        return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
+    }
     // the MFMA engine moves 16-byte vectors along channels and keeps offsets in 32 bits
     if (Cs % 8 || Ks % 8 || R * S > 32) return TT_EUNSUPPORTED;
     const int64_t lim = int64_t(1) << 30;

@@ -34,7 +34,6 @@ tt_status check(const ConvArgs &a, Dims *d)
     if (l.n_in <= 0 || l.n_out <= 0 || l.H <= 0 || l.W <= 0 || l.R <= 0 || l.S <= 0 || l.pad < 0) return TT_EINVAL;
     *d = Dims{a.batch, l.n_in, l.n_out, l.H, l.W, l.R, l.S, l.pad, l.H + 2 * l.pad - l.R + 1, l.W + 2 * l.pad - l.S + 1};
     if (d->P <= 0 || d->Q <= 0) return TT_EINVAL;
-    if (a.dtype != TT_BF16) return TT_EUNSUPPORTED; // the implicit-GEMM kernels are bf16 / fp32-accumulate only
     return TT_OK;
 }
 
@@ -115,13 +114,14 @@ tt_status forward(const ConvArgs &a, const Dims &d, Workspace &ws)
     Sharded X, W, Xa, Wa;
     if ((st = act_view(&X, a.X, a.tX, k, d.N, hw, d.C)) != TT_OK) return st;
     if ((st = filter_view(&W, a.W, a.tW, k, d)) != TT_OK) return st;
-    if ((st = prepare_operand(X, aX, k, 2, nullptr, a.dtype, ws, a.stream, &Xa)) != TT_OK) return st;
-    if ((st = prepare_operand(W, transpose_tiling(aW, k), k, 2, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
+    const int esz = a.dtype == TT_BF16 ? 2 : 4;
+    if ((st = prepare_operand(X, aX, k, esz, nullptr, a.dtype, ws, a.stream, &Xa)) != TT_OK) return st;
+    if ((st = prepare_operand(W, transpose_tiling(aW, k), k, esz, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
     OutputPlan op;
     if ((st = plan_output(f, a.tY, a.Yout, d.N * pq, d.K, k, a.dtype, a.layer->act, ws, &op)) != TT_OK) return st;
     if (ws.dry) return TT_OK;
     st = launch_conv(TT_OP_FWD, n, Xa.ptr, Wa.ptr, op.gemm_out, d.N >> k1, d.C >> k3, d.K >> k2, d.H, d.W, d.R, d.S, d.pad,
-                     op.gemm_dtype, op.gemm_act, a.stream);
+                     op.gemm_dtype, op.gemm_act, a.stream, nullptr, a.dtype);
     if (st != TT_OK) return st;
     return finish_output(op, a.tY, a.Yout, d.N * pq, d.K, k, a.dtype, a.layer->act, a.stream);
 }
@@ -134,6 +134,8 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
     if (relu && !valid_tiling(a.tY, k)) return TT_EINVAL;
     if (a.with_dx && !valid_tiling(a.tdX, k)) return TT_EINVAL;
     const int64_t hw = d.H * d.W, pq = d.P * d.Q, rs = d.R * d.S;
+    const int esz = a.dtype == TT_BF16 ? 2 : 4;
+    const bool bf16 = a.dtype == TT_BF16;
     tt_status st;
     Sharded dY, Y, X, W;
     if ((st = act_view(&dY, a.dY, a.tdY, k, d.N, pq, d.K)) != TT_OK) return st;
@@ -154,20 +156,22 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
         int k1, k2, k3;
         form_counts(f, k, &k1, &k2, &k3);
         Sharded Ga, Wa;
-        if ((st = prepare_operand(G, aG, k, 2, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga)) != TT_OK) return st;
+        if ((st = prepare_operand(G, aG, k, esz, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga)) != TT_OK) return st;
         if (!gated) { G = Ga; gated = true; }
         // aligned tiling of W^T, expressed on W, then on the filter storage matrix: two swaps cancel
-        if ((st = prepare_operand(W, aWt, k, 2, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
+        if ((st = prepare_operand(W, aWt, k, esz, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
         OutputPlan op;
         if ((st = plan_output(f, a.tdX, a.dX, d.N * hw, d.C, k, a.dtype, TT_ACT_NONE, ws, &op)) != TT_OK) return st;
-        // scratch for the flipped filters of every shard (the dX product then runs as a forward convolution of dY)
+        // scratch for the flipped filters of every shard (the dX product then runs as a forward convolution of dY;
+        // bf16 only: the fp32 kernels read the filters as they are)
         void *flip[kMaxShards];
         const size_t fbytes = (size_t)(d.K >> k3) * (size_t)rs * (size_t)(d.C >> k2) * 2;
-        for (int s = 0; s < n; ++s) flip[s] = ws.take(fbytes);
+        if (bf16)
+            for (int s = 0; s < n; ++s) flip[s] = ws.take(fbytes);
         if (ws.overflow) return TT_EWORKSPACE;
         if (!ws.dry) {
             st = launch_conv(TT_OP_DGRAD, n, Ga.ptr, Wa.ptr, op.gemm_out, d.N >> k1, d.C >> k2, d.K >> k3, d.H, d.W, d.R, d.S,
-                             d.pad, op.gemm_dtype, TT_ACT_NONE, a.stream, flip);
+                             d.pad, op.gemm_dtype, TT_ACT_NONE, a.stream, bf16 ? flip : nullptr, a.dtype);
             if (st != TT_OK) return st;
             if ((st = finish_output(op, a.tdX, a.dX, d.N * hw, d.C, k, a.dtype, TT_ACT_NONE, a.stream)) != TT_OK) return st;
         }
@@ -183,8 +187,8 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
         int k1, k2, k3;
         form_counts(f, k, &k1, &k2, &k3);
         Sharded Xa, Ga;
-        if ((st = prepare_operand(X, transpose_tiling(aXt, k), k, 2, nullptr, a.dtype, ws, a.stream, &Xa)) != TT_OK) return st;
-        if ((st = prepare_operand(G, aG, k, 2, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga)) != TT_OK) return st;
+        if ((st = prepare_operand(X, transpose_tiling(aXt, k), k, esz, nullptr, a.dtype, ws, a.stream, &Xa)) != TT_OK) return st;
+        if ((st = prepare_operand(G, aG, k, esz, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga)) != TT_OK) return st;
         // the output grid on the filter storage matrix (K*R*S) x C: F1 cuts its columns, F2 its rows
         uint8_t zl[TT_MAX_K];
         for (int j = 0; j < k; ++j) zl[j] = f[j] == TT_F1 ? TT_C : (f[j] == TT_F2 ? TT_R : kRed);
@@ -199,7 +203,7 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
         if (!make_grid(zl, k, d.K * rs, d.C, &gz)) return TT_EINFEASIBLE;
         const int nred = 1 << gz.kX, nblk = n >> gz.kX;
         const size_t blk_bytes = (size_t)gz.srows * (size_t)gz.scols * 4;
-        const WgradChoice choice = (Ns * pq) % 64 == 0 && Ks > 128 ? pick_wgrad_parts(k, nblk, nred, Ns * pq / 64, Ks, rs * Cs, blk_bytes)
+        const WgradChoice choice = bf16 && (Ns * pq) % 64 == 0 && Ks > 128 ? pick_wgrad_parts(k, nblk, nred, Ns * pq / 64, Ks, rs * Cs, blk_bytes)
                                                                      : WgradChoice{0, 1};
         const int parts = choice.parts;
         if (parts > 0 && !(parts == 1 && nred == 1)) {
@@ -240,11 +244,11 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
             const int64_t Nsub = Ns / split;
             for (int s = 0; s < n; ++s)
                 for (int c = 0; c < split; ++c) {
-                    Gs[s * split + c] = static_cast<const char *>(Ga.ptr[s]) + (size_t)c * Nsub * pq * Ks * 2;
-                    Xs[s * split + c] = static_cast<const char *>(Xa.ptr[s]) + (size_t)c * Nsub * hw * Cs * 2;
+                    Gs[s * split + c] = static_cast<const char *>(Ga.ptr[s]) + (size_t)c * Nsub * pq * Ks * esz;
+                    Xs[s * split + c] = static_cast<const char *>(Xa.ptr[s]) + (size_t)c * Nsub * hw * Cs * esz;
                 }
             st = launch_conv(TT_OP_WGRAD, n * split, Gs, Xs, op.gemm_out, Nsub, Cs, Ks, d.H, d.W, d.R, d.S, d.pad, op.gemm_dtype,
-                             TT_ACT_NONE, a.stream);
+                             TT_ACT_NONE, a.stream, nullptr, a.dtype);
             if (st != TT_OK) return st;
             if ((st = finish_output(op, tWs, a.dW, d.K * rs, d.C, k, a.dtype, TT_ACT_NONE, a.stream)) != TT_OK) return st;
         }

@@ -145,12 +145,13 @@ tt_status launch_gemm_v4(int count, const void *const *A, const void *const *B, 
 
 // Convolution shard products (conv.hip).  op TT_OP_FWD: A = X shards, B = filter shards, C = Y shards;
 // TT_OP_DGRAD: A = dY, B = filters, C = dX;  TT_OP_WGRAD: A = dY, B = X, C = dW.  Ns images, Cs input channels and
-// Ks output channels per shard; bf16 operands.
+// Ks output channels per shard; bf16 operands on the MFMA engines, fp32 operands (in_dtype TT_F32) on plain kernels
+// that follow the definition term by term.
 // flip_ws (TT_OP_DGRAD only, optional): per shard a 16-byte aligned scratch buffer of the filter shard's size; when
 // given (and R == S, pad <= R - 1) the filters are flipped into it and the product runs on the forward kernel.
 tt_status launch_conv(int op, int count, const void *const *A, const void *const *B, void *const *C, int64_t Ns,
                       int64_t Cs, int64_t Ks, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad, int out_dtype,
-                      int act, void *stream, void *const *flip_ws = nullptr);
+                      int act, void *stream, void *const *flip_ws = nullptr, int in_dtype = TT_BF16);
 
 // Weight-gradient products with every output block's reduction over pixels (the pixels of all shards that an F3 cut
 // makes add up into that block) cut into `parts` equal runs, one fp32 partial sum each (conv.hip).  A = dY shards and

@@ -37,15 +37,15 @@ def filt_from_matrix(Mx, k, c, r, s):
 
 
 def up(Mx, t):
-    return [np_to_dev(s, True) for s in tl.tile(Mx, t)]
+    return [np_to_dev(s, Mx.dtype == np.uint16) for s in tl.tile(Mx, t)]
 
 
 def ws(nbytes):
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=DEV)
 
 
-def close(got, want, mag, what):
-    tol = 1e-2 * mag                                               # the stated bound, nothing added
+def close(got, want, mag, what, rel=1e-2):
+    tol = rel * mag                                                # the stated bound, nothing added
     err = np.abs(got - want)
     assert np.all(np.isfinite(got)), what
     assert np.all(err <= tol + 1e-30), (what, float(err.max()), float((err / (tol + 1e-30)).max()))
@@ -55,36 +55,40 @@ def conv_mag_fwd(X, W, pad):
     return ly.conv_forward(np.abs(X), np.abs(W), pad)
 
 
-def run_conv(N, C, K, H, Wd, R, S, pad, k, relu, tX, tW, tY, tdY, tdX, f_fwd, f_dg, f_wg, seed, with_dx=True):
+def run_conv(N, C, K, H, Wd, R, S, pad, k, relu, tX, tW, tY, tdY, tdX, f_fwd, f_dg, f_wg, seed, with_dx=True, dt="bf16"):
     lay = tt.layer("conv", "relu" if relu else "none", C, K, H=H, W=Wd, R=R, S=S, pad=pad)
     P, Q = H + 2 * pad - R + 1, Wd + 2 * pad - S + 1
-    Xb = to_bf16_bits(normal_f32(seed, 0, (N, C, H, Wd), 1.0))
-    Wb = to_bf16_bits(normal_f32(seed, 1, (K, C, R, S), 0.05))
-    dYb = to_bf16_bits(normal_f32(seed, 2, (N, K, P, Q), 1.0))
-    X, W, dY = bf16_bits_to_f64(Xb), bf16_bits_to_f64(Wb), bf16_bits_to_f64(dYb)
+    bf = dt == "bf16"
+    store = to_bf16_bits if bf else (lambda a: a.astype(np.float32))
+    wide = bf16_bits_to_f64 if bf else (lambda a: a.astype(np.float64))
+    tdt, rel = (torch.bfloat16, 1e-2) if bf else (torch.float32, 1e-5)
+    Xb = store(normal_f32(seed, 0, (N, C, H, Wd), 1.0))
+    Wb = store(normal_f32(seed, 1, (K, C, R, S), 0.05))
+    dYb = store(normal_f32(seed, 2, (N, K, P, Q), 1.0))
+    X, W, dY = wide(Xb), wide(Wb), wide(dYb)
     tWs = ex.transpose_tiling(tW)                      # letters on the filter storage matrix
     Xs, Ws_, dYs = up(act_matrix(Xb), tX), up(filt_matrix(Wb), tWs), up(act_matrix(dYb), tdY)
-    Ys = alloc_shards(N * P * Q, K, tY, torch.bfloat16, fill=float("nan"))
-    nb = tt.tt_conv_workspace_bytes(lay, N, k, "bf16", tt.TT_OP_FWD, tX, tW, tY, forms_a=f_fwd)
-    tt.tt_conv_forward(lay, N, k, "bf16", tX, tW, tY, f_fwd, Xs, Ws_, Ys, ws(nb))
+    Ys = alloc_shards(N * P * Q, K, tY, tdt, fill=float("nan"))
+    nb = tt.tt_conv_workspace_bytes(lay, N, k, dt, tt.TT_OP_FWD, tX, tW, tY, forms_a=f_fwd)
+    tt.tt_conv_forward(lay, N, k, dt, tX, tW, tY, f_fwd, Xs, Ws_, Ys, ws(nb))
     torch.cuda.synchronize()
-    Ym = bf16_bits_to_f64(tl.untile(shards_to_np(Ys), tY, N * P * Q, K))
+    Ym = wide(tl.untile(shards_to_np(Ys), tY, N * P * Q, K))
     Yg = act_from_matrix(Ym, N, K, P, Q)
     want = ly.conv_forward(X, W, pad)
     if relu:
         want = np.maximum(want, 0)
-    close(Yg, want, conv_mag_fwd(X, W, pad), ("fwd", tX, tW, tY, f_fwd))
-    dXs = alloc_shards(N * H * Wd, C, tdX, torch.bfloat16, fill=float("nan")) if with_dx else None
-    dWs = alloc_shards(K * R * S, C, tWs, torch.bfloat16, fill=float("nan"))
-    nb = tt.tt_conv_workspace_bytes(lay, N, k, "bf16", tt.TT_OP_DGRAD, tX, tW, tY, tdY, tdX, f_dg, f_wg, with_dx)
-    tt.tt_conv_backward(lay, N, k, "bf16", tX, tW, tY, tdY, tdX, f_dg, f_wg, Xs, Ws_, Ys, dYs, dXs, dWs, ws(nb))
+    close(Yg, want, conv_mag_fwd(X, W, pad), ("fwd", tX, tW, tY, f_fwd), rel)
+    dXs = alloc_shards(N * H * Wd, C, tdX, tdt, fill=float("nan")) if with_dx else None
+    dWs = alloc_shards(K * R * S, C, tWs, tdt, fill=float("nan"))
+    nb = tt.tt_conv_workspace_bytes(lay, N, k, dt, tt.TT_OP_DGRAD, tX, tW, tY, tdY, tdX, f_dg, f_wg, with_dx)
+    tt.tt_conv_backward(lay, N, k, dt, tX, tW, tY, tdY, tdX, f_dg, f_wg, Xs, Ws_, Ys, dYs, dXs, dWs, ws(nb))
     torch.cuda.synchronize()
     G = dY * (Yg > 0) if relu else dY
     if with_dx:
-        dXg = act_from_matrix(bf16_bits_to_f64(tl.untile(shards_to_np(dXs), tdX, N * H * Wd, C)), N, C, H, Wd)
-        close(dXg, ly.conv_dgrad(G, W, pad, H, Wd), ly.conv_dgrad(np.abs(G), np.abs(W), pad, H, Wd), ("dgrad", tdY, tW, tdX, f_dg))
-    dWg = filt_from_matrix(bf16_bits_to_f64(tl.untile(shards_to_np(dWs), tWs, K * R * S, C)), K, C, R, S)
-    close(dWg, ly.conv_wgrad(X, G, pad, R, S), ly.conv_wgrad(np.abs(X), np.abs(G), pad, R, S), ("wgrad", tX, tdY, tW, f_wg))
+        dXg = act_from_matrix(wide(tl.untile(shards_to_np(dXs), tdX, N * H * Wd, C)), N, C, H, Wd)
+        close(dXg, ly.conv_dgrad(G, W, pad, H, Wd), ly.conv_dgrad(np.abs(G), np.abs(W), pad, H, Wd), ("dgrad", tdY, tW, tdX, f_dg), rel)
+    dWg = filt_from_matrix(wide(tl.untile(shards_to_np(dWs), tWs, K * R * S, C)), K, C, R, S)
+    close(dWg, ly.conv_wgrad(X, G, pad, R, S), ly.conv_wgrad(np.abs(X), np.abs(G), pad, R, S), ("wgrad", tX, tdY, tW, f_wg), rel)
 
 
 def test_single_shard_and_one_cut():
@@ -126,6 +130,18 @@ def test_weight_gradient_with_the_reduction_range_cut_evenly():
     run_conv(16, 16, 264, 4, 4, 1, 1, 0, 1, False, "R", "r", "R", "R", "R", "1", "1", "3", 143)                    # 1x1 filters, 16 pixels per image, two row tiles
 
 
+def test_fp32_convolutions():
+    # fp32 operands and results on the plain kernels: no cut, every form at one cut, mixed forms and stored tilings at
+    # two cuts (partial sums, gate, conversions as for bf16), odd channel counts (no 16-byte vectors needed), 5 x 3 taps
+    run_conv(2, 5, 7, 6, 5, 3, 3, 1, 0, True, "", "", "", "", "", "", "", "", 170, dt="f32")
+    run_conv(4, 6, 10, 5, 5, 3, 3, 1, 1, True, "R", "r", "R", "R", "R", "1", "1", "3", 171, dt="f32")
+    run_conv(4, 6, 10, 5, 5, 3, 3, 1, 1, False, "r", "C", "C", "C", "r", "2", "3", "2", 172, dt="f32")
+    run_conv(4, 6, 10, 5, 5, 3, 3, 1, 1, True, "C", "R", "r", "r", "C", "3", "2", "1", 173, dt="f32")
+    for i, f in enumerate(["12", "31", "23", "33"]):
+        run_conv(4, 12, 8, 4, 6, 5, 3, 2, 2, bool(i % 2), "RC", "Cr", "rR", "CR", "RR", f, f, f, 174 + i, dt="f32")
+    run_conv(8, 16, 16, 4, 4, 3, 3, 1, 3, True, "RRR", "rrr", "RRR", "RRR", "RRR", None, None, None, 179, dt="f32")
+
+
 def test_refusals():
     lay = tt.layer("conv", "none", 12, 16, H=4, W=4, R=3, S=3, pad=1)       # 12 channels: no 16-byte channel vectors
     x = [torch.zeros(4096, dtype=torch.bfloat16, device=DEV)]
@@ -133,9 +149,6 @@ def test_refusals():
         tt.tt_conv_forward(lay, 2, 0, "bf16", "", "", "", "", x, x, x)
     assert e.value.status == 3
     lay = tt.layer("conv", "none", 16, 16, H=4, W=4, R=3, S=3, pad=1)
-    with pytest.raises(tt.TilingError) as e:                                  # fp32 convolutions are not built
-        tt.tt_conv_forward(lay, 2, 0, "f32", "", "", "", "", x, x, x)
-    assert e.value.status == 3
     with pytest.raises(tt.TilingError) as e:                                  # batch 2 cannot be cut twice
         tt.tt_conv_forward(lay, 2, 2, "bf16", "RR", "rr", "RR", "11", x * 4, x * 4, x * 4)
     assert e.value.status == 2
