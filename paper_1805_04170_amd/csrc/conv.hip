@@ -39,6 +39,11 @@ struct ConvParams {
     ConvGeom g;
     int32_t M, N, K, ldc;
     int32_t tiles_m, tiles_n, per_xcd, total, relu;
+    // Fused shards (forward kernel only): members > 1 means one product covers `members` shards that share the left
+    // operand; its N columns are those shards' column blocks side by side, member_cols (a multiple of 64) each, B is
+    // their filter blocks lying one after the other in memory, and the result columns of member m of group g go to
+    // C[g * members + m], a matrix of member_cols columns.
+    int32_t members, member_cols;
 };
 
 __device__ __forceinline__ u32x4 load16(const char *base, int32_t elem_off)
@@ -185,9 +190,21 @@ __global__ __launch_bounds__(WM * WN * 64, WM * WN / 4) void conv_gather_a_kerne
     else         { la.IH = g.P; la.IW = g.Q; la.OH = g.H; la.OW = g.W; la.off = g.pad;  la.sgn = -1; la.Ch = g.Ks; }
     if constexpr (OP == 0) {
         core::DenseKC<core::Slots<BN, true, NT>::value> lb;
-        lb.base = reinterpret_cast<const char *>(p.B[t.shard]);
+        lb.base = reinterpret_cast<const char *>(p.B[t.shard * p.members]);
         lb.ld = p.K; lb.rows = p.N; lb.K = p.K;
-        core::tile_product<BM, BN, WM, WN, DEPTH, KMASK, OUT_BF16, true>(la, lb, p.C[t.shard], p.ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
+        // every wave owns 64 columns of the tile, which lie in one member's block: the wave writes through that member's
+        // pointer, moved back by the block's first column so that the tile's own column numbers address it
+        static_assert(BN / WN == 64, "a wave's columns lie in one member block");
+        void *Cw = p.C[t.shard];
+        int ldc = p.ldc;
+        if (p.members > 1) {
+            const int col0 = t.n0 + ((threadIdx.x >> 6) % WN) * 64;
+            int m = col0 / p.member_cols;
+            m = m < p.members ? m : p.members - 1; // columns past N are never stored
+            Cw = reinterpret_cast<char *>(p.C[t.shard * p.members + m]) - (ptrdiff_t)m * p.member_cols * (OUT_BF16 ? 2 : 4);
+            ldc = p.member_cols;
+        }
+        core::tile_product<BM, BN, WM, WN, DEPTH, KMASK, OUT_BF16, true>(la, lb, Cw, ldc, p.M, p.N, p.K, t.m0, t.n0, p.relu != 0, smem);
     } else {
         FilterRC<core::Slots<BN, false, NT>::value> lb;
         lb.base = reinterpret_cast<const char *>(p.B[t.shard]);
@@ -727,6 +744,8 @@ tt_status launch_conv(int op, int count, const void *const *A, const void *const
     p.g = ConvGeom{(int32_t)Ns, (int32_t)H, (int32_t)W, (int32_t)P, (int32_t)Q, (int32_t)R, (int32_t)S, (int32_t)pad,
                    (int32_t)Cs, (int32_t)Ks};
     p.relu = act == TT_ACT_RELU;
+    p.members = 1;
+    p.member_cols = 0;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const bool obf = out_dtype == TT_BF16;
     const uint64_t ob = obf ? 2 : 4;
@@ -813,6 +832,8 @@ tt_status launch_conv_wgrad_split(int k, int nblk, int nred, const uint8_t *blk_
     p.g = ConvGeom{(int32_t)Ns, (int32_t)H, (int32_t)W, (int32_t)P, (int32_t)Q, (int32_t)R, (int32_t)S, (int32_t)pad,
                    (int32_t)Cs, (int32_t)Ks};
     p.relu = 0;
+    p.members = 1;
+    p.member_cols = 0;
     p.M = (int32_t)Ks; p.N = (int32_t)(R * S * Cs); p.K = (int32_t)pixels; p.ldc = p.N;
     w.sp.parts = parts; w.sp.nred = nred; w.sp.ktps = (int32_t)(pixels / core::BK);
     const uint64_t x_b = (uint64_t)(Ns * H * W * Cs) * 2, y_b = (uint64_t)(pixels * Ks) * 2, w_b = (uint64_t)(Ks * R * S * Cs) * 4;
@@ -838,6 +859,86 @@ tt_status launch_conv_wgrad_split(int k, int nblk, int nred, const uint8_t *blk_
         hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * kXcds), dim3(256), sm, s, w);
     }
     return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
+}
+
+
+// Forward products (op TT_OP_FWD), or data gradients run as forward products of dY with flipped filters (op TT_OP_DGRAD),
+// of `groups` groups of `members` shards each that share their left operand (X resp. dY replicated over the cuts that split
+// the output channels resp. the input channels): one product per group with all members' columns side by side, so that a
+// group reads its left operand once instead of once per member (with 64 columns per shard the per-shard products take in
+// four times the bytes per flop of a 256-wide tile).
+//   A[g]: the group's left operand (Ns images);  B[g * members + m]: member m's filter block;  C[g * members + m]: its result
+//   cols: columns per member (output channels for FWD, input channels for DGRAD), a multiple of 64;  red: channels of the
+//   contraction per pixel (input channels for FWD, output channels for DGRAD).
+//   flip_ws (DGRAD): per member a scratch buffer of its filter block's size.
+// The members' filter blocks (FWD) resp. scratch buffers (DGRAD) must lie one after the other in memory; if they do not,
+// or a shape does not fit, TT_EUNSUPPORTED: the caller runs the members one by one.
+tt_status launch_conv_fused(int op, int groups, int members, const void *const *A, const void *const *B, void *const *C,
+                            int64_t Ns, int64_t cols, int64_t red, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad,
+                            int out_dtype, int act, void *stream, void *const *flip_ws)
+{
+    if (!A || !B || !C || groups < 1 || members < 2 || groups * members > kMaxShards) return TT_EINVAL;
+    if (op != TT_OP_FWD && op != TT_OP_DGRAD) return TT_EINVAL;
+    if (Ns <= 0 || cols <= 0 || red <= 0 || H <= 0 || W <= 0 || R <= 0 || S <= 0 || pad < 0) return TT_EINVAL;
+    const int64_t P = H + 2 * pad - R + 1, Q = W + 2 * pad - S + 1;
+    if (P <= 0 || Q <= 0) return TT_EINVAL;
+    if (out_dtype != TT_BF16 && out_dtype != TT_F32) return TT_EINVAL;
+    if (op == TT_OP_DGRAD && (!flip_ws || R != S || pad > R - 1)) return TT_EUNSUPPORTED;
+    if (cols % 64 || red % 8 || R * S > 32) return TT_EUNSUPPORTED;
+    const int n = groups * members;
+    const int64_t N = cols * members, K = R * S * red, lim = int64_t(1) << 30;
+    const int64_t in_px = op == TT_OP_FWD ? H * W : P * Q, out_px = op == TT_OP_FWD ? P * Q : H * W; // per image
+    if (Ns * in_px * red >= lim || Ns * out_px * N >= lim || N * K >= lim) return TT_EUNSUPPORTED;
+    if (!aligned16(A, groups) || !aligned16(B, n) || !aligned16(const_cast<const void *const *>(C), n)) return TT_EUNSUPPORTED;
+    const void *const *blocks = op == TT_OP_FWD ? B : const_cast<const void *const *>(flip_ws);
+    const size_t block_bytes = (size_t)cols * (size_t)K * 2;
+    for (int g = 0; g < groups; ++g)
+        for (int m = 0; m < members; ++m) {
+            const void *b = blocks[g * members + m];
+            if (!b || (reinterpret_cast<uintptr_t>(b) & 15)) return op == TT_OP_FWD ? TT_EUNSUPPORTED : TT_EINVAL;
+            if (m > 0 && static_cast<const char *>(b) != static_cast<const char *>(blocks[g * members]) + (size_t)m * block_bytes)
+                return TT_EUNSUPPORTED;
+        }
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const bool obf = out_dtype == TT_BF16;
+    const int64_t M = Ns * out_px;
+    const uint64_t ob = obf ? 2 : 4;
+    // algorithmic bytes as the per-shard launches count them: each shard's tensors touched once
+    const uint64_t bytes = ((uint64_t)(Ns * in_px * red) * 2 + (uint64_t)(cols * K) * 2 + (uint64_t)(M * cols) * ob) * (uint64_t)n;
+    ProfileScope scope(stream, op == TT_OP_FWD ? TT_K_CONV_FWD : TT_K_CONV_DGRAD, n, M, cols, K, bytes,
+                       2ull * (uint64_t)M * (uint64_t)cols * (uint64_t)K * (uint64_t)n);
+    ConvParams p;
+    for (int i = 0; i < kMaxShards; ++i) {
+        p.A[i] = i < groups ? A[i] : nullptr;
+        p.B[i] = i < n ? blocks[i] : nullptr;
+        p.C[i] = i < n ? C[i] : nullptr;
+    }
+    if (op == TT_OP_DGRAD) {
+        // member m's filters [red][R][S][cols] -> [cols][R][S][red] with the taps reversed, into its scratch buffer
+        FlipParams f;
+        for (int i = 0; i < kMaxShards; ++i) {
+            f.src[i] = i < n ? B[i] : nullptr;
+            f.dst[i] = i < n ? flip_ws[i] : nullptr;
+        }
+        f.Ks = (int32_t)red; f.RS = (int32_t)(R * S); f.Cs = (int32_t)cols;
+        if (red % 64 == 0) {
+            hipLaunchKernelGGL(filter_flip_tiled_kernel, dim3((uint32_t)((cols / 64) * (red / 64) * R * S), (uint32_t)n), dim3(256), 0, s, f);
+        } else {
+            const int64_t threads = cols * R * S * (red / 8);
+            hipLaunchKernelGGL(filter_flip_kernel, dim3((uint32_t)((threads + 255) / 256), (uint32_t)n), dim3(256), 0, s, f);
+        }
+        if (hipGetLastError() != hipSuccess) return TT_EDEVICE;
+        p.g = ConvGeom{(int32_t)Ns, (int32_t)P, (int32_t)Q, (int32_t)H, (int32_t)W, (int32_t)R, (int32_t)S,
+                       (int32_t)(R - 1 - pad), (int32_t)red, (int32_t)N};
+    } else {
+        p.g = ConvGeom{(int32_t)Ns, (int32_t)H, (int32_t)W, (int32_t)P, (int32_t)Q, (int32_t)R, (int32_t)S, (int32_t)pad,
+                       (int32_t)red, (int32_t)N};
+    }
+    p.relu = act == TT_ACT_RELU;
+    p.members = members;
+    p.member_cols = (int32_t)cols;
+    p.M = (int32_t)M; p.N = (int32_t)N; p.K = (int32_t)K; p.ldc = (int32_t)N;
+    return obf ? launch_gather_a<0, true>(p, groups, s) : launch_gather_a<0, false>(p, groups, s);
 }
 
 } // namespace tt

@@ -98,6 +98,32 @@ WgradChoice pick_wgrad_parts(int k, int nblk, int nred, int64_t ktps, int64_t Ks
     return best;
 }
 
+// Shards that differ only in their side at the F2 cuts read the same left operand (its aligned tiling replicates it
+// there).  Where each of them has few columns (at most 128: narrow tiles take in the left operand once per 64 or 128
+// columns), they are run as one product per group, `members` column blocks side by side.  Fills the per-group and
+// per-member pointer lists in the order launch_conv_fused wants; returns the number of members, or 1 for "run them shard by
+// shard".
+int fuse_f2(const uint8_t *forms, int k, int64_t cols_per_shard, int dtype, const Sharded &left, const Sharded &right,
+            void *const *out, const void **A, const void **B, void **C)
+{
+    uint32_t mask2 = 0;
+    for (int j = 0; j < k; ++j)
+        if (forms[j] == TT_F2) mask2 |= 1u << (k - 1 - j);
+    const int k2 = __builtin_popcount(mask2), members = 1 << k2, groups = (1 << k) >> k2;
+    if (k2 == 0 || dtype != TT_BF16 || cols_per_shard > 128 || cols_per_shard % 64 || tuning_int("TT_CONV_FUSE", 1) == 0) return 1;
+    const uint32_t mask_g = ((1u << k) - 1u) & ~mask2;
+    for (int g = 0; g < groups; ++g) {
+        const uint32_t gid = deposit((uint32_t)g, mask_g, k);
+        A[g] = left.ptr[gid];
+        for (int m = 0; m < members; ++m) {
+            const uint32_t sid = gid | deposit((uint32_t)m, mask2, k);
+            B[g * members + m] = right.ptr[sid];
+            C[g * members + m] = out[sid];
+        }
+    }
+    return members;
+}
+
 tt_status forward(const ConvArgs &a, const Dims &d, Workspace &ws)
 {
     const int k = a.k, n = 1 << k;
@@ -120,8 +146,17 @@ tt_status forward(const ConvArgs &a, const Dims &d, Workspace &ws)
     OutputPlan op;
     if ((st = plan_output(f, a.tY, a.Yout, d.N * pq, d.K, k, a.dtype, a.layer->act, ws, &op)) != TT_OK) return st;
     if (ws.dry) return TT_OK;
-    st = launch_conv(TT_OP_FWD, n, Xa.ptr, Wa.ptr, op.gemm_out, d.N >> k1, d.C >> k3, d.K >> k2, d.H, d.W, d.R, d.S, d.pad,
-                     op.gemm_dtype, op.gemm_act, a.stream, nullptr, a.dtype);
+    {
+        const void *fa[kMaxShards], *fb[kMaxShards];
+        void *fc[kMaxShards];
+        const int members = fuse_f2(f, k, d.K >> k2, a.dtype, Xa, Wa, op.gemm_out, fa, fb, fc);
+        st = members > 1 ? launch_conv_fused(TT_OP_FWD, n / members, members, fa, fb, fc, d.N >> k1, d.K >> k2, d.C >> k3, d.H, d.W,
+                                             d.R, d.S, d.pad, op.gemm_dtype, op.gemm_act, a.stream, nullptr)
+                         : TT_EUNSUPPORTED;
+    }
+    if (st == TT_EUNSUPPORTED)
+        st = launch_conv(TT_OP_FWD, n, Xa.ptr, Wa.ptr, op.gemm_out, d.N >> k1, d.C >> k3, d.K >> k2, d.H, d.W, d.R, d.S, d.pad,
+                         op.gemm_dtype, op.gemm_act, a.stream, nullptr, a.dtype);
     if (st != TT_OK) return st;
     return finish_output(op, a.tY, a.Yout, d.N * pq, d.K, k, a.dtype, a.layer->act, a.stream);
 }
@@ -166,12 +201,39 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
         // bf16 only: the fp32 kernels read the filters as they are)
         void *flip[kMaxShards];
         const size_t fbytes = (size_t)(d.K >> k3) * (size_t)rs * (size_t)(d.C >> k2) * 2;
-        if (bf16)
-            for (int s = 0; s < n; ++s) flip[s] = ws.take(fbytes);
+        if (bf16) {
+            // handed out group by group (shards that differ only at the F2 cuts, in the order of their column blocks), so
+            // that a group's buffers lie one after the other: the fused product reads them as one filter matrix
+            uint32_t mask2 = 0;
+            for (int j = 0; j < k; ++j)
+                if (f[j] == TT_F2) mask2 |= 1u << (k - 1 - j);
+            const uint32_t mask_g = ((1u << k) - 1u) & ~mask2;
+            const int members = 1 << __builtin_popcount(mask2);
+            for (int g = 0; g < n / members; ++g)
+                for (int m = 0; m < members; ++m)
+                    flip[deposit((uint32_t)g, mask_g, k) | deposit((uint32_t)m, mask2, k)] = ws.take(fbytes);
+        }
         if (ws.overflow) return TT_EWORKSPACE;
         if (!ws.dry) {
-            st = launch_conv(TT_OP_DGRAD, n, Ga.ptr, Wa.ptr, op.gemm_out, d.N >> k1, d.C >> k2, d.K >> k3, d.H, d.W, d.R, d.S,
-                             d.pad, op.gemm_dtype, TT_ACT_NONE, a.stream, bf16 ? flip : nullptr, a.dtype);
+            {
+                const void *fa[kMaxShards], *fb[kMaxShards];
+                void *fc[kMaxShards], *ff[kMaxShards];
+                const int members = fuse_f2(f, k, d.C >> k2, a.dtype, Ga, Wa, op.gemm_out, fa, fb, fc);
+                if (members > 1) { // the scratch buffers in the same order as the filter blocks
+                    Sharded fl;
+                    for (int s = 0; s < n; ++s) fl.ptr[s] = flip[s];
+                    const void *dummy_a[kMaxShards], *fbf[kMaxShards];
+                    void *dummy_c[kMaxShards];
+                    (void)fuse_f2(f, k, d.C >> k2, a.dtype, Ga, fl, op.gemm_out, dummy_a, fbf, dummy_c);
+                    for (int i = 0; i < n; ++i) ff[i] = const_cast<void *>(fbf[i]);
+                }
+                st = members > 1 ? launch_conv_fused(TT_OP_DGRAD, n / members, members, fa, fb, fc, d.N >> k1, d.C >> k2, d.K >> k3,
+                                                     d.H, d.W, d.R, d.S, d.pad, op.gemm_dtype, TT_ACT_NONE, a.stream, ff)
+                                 : TT_EUNSUPPORTED;
+            }
+            if (st == TT_EUNSUPPORTED)
+                st = launch_conv(TT_OP_DGRAD, n, Ga.ptr, Wa.ptr, op.gemm_out, d.N >> k1, d.C >> k2, d.K >> k3, d.H, d.W, d.R, d.S,
+                                 d.pad, op.gemm_dtype, TT_ACT_NONE, a.stream, bf16 ? flip : nullptr, a.dtype);
             if (st != TT_OK) return st;
             if ((st = finish_output(op, a.tdX, a.dX, d.N * hw, d.C, k, a.dtype, TT_ACT_NONE, a.stream)) != TT_OK) return st;
         }

@@ -153,6 +153,15 @@ tt_status launch_conv(int op, int count, const void *const *A, const void *const
                       int64_t Cs, int64_t Ks, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad, int out_dtype,
                       int act, void *stream, void *const *flip_ws = nullptr, int in_dtype = TT_BF16);
 
+// Forward products (TT_OP_FWD) or data gradients (TT_OP_DGRAD, run as forward products of dY with flipped filters) of
+// groups of `members` shards that share their left operand, one product per group with the members' columns side by side
+// (conv.hip).  A[g]; B[g * members + m]; C[g * members + m]; cols: columns per member; red: contraction channels per pixel.
+// TT_EUNSUPPORTED when the members' filter blocks do not lie one after the other or a shape does not fit (the caller runs
+// launch_conv shard by shard).
+tt_status launch_conv_fused(int op, int groups, int members, const void *const *A, const void *const *B, void *const *C,
+                            int64_t Ns, int64_t cols, int64_t red, int64_t H, int64_t W, int64_t R, int64_t S, int64_t pad,
+                            int out_dtype, int act, void *stream, void *const *flip_ws);
+
 // Weight-gradient products with every output block's reduction over pixels (the pixels of all shards that an F3 cut
 // makes add up into that block) cut into `parts` equal runs, one fp32 partial sum each (conv.hip).  A = dY shards and
 // B = X shards by shard id; C[blk * parts + part]; blk_ids[b] / red_ids[q]: id bits of block b / of a block's q-th shard.

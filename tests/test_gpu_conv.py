@@ -130,6 +130,15 @@ def test_weight_gradient_with_the_reduction_range_cut_evenly():
     run_conv(16, 16, 264, 4, 4, 1, 1, 0, 1, False, "R", "r", "R", "R", "R", "1", "1", "3", 143)                    # 1x1 filters, 16 pixels per image, two row tiles
 
 
+def test_shards_that_share_their_left_operand_run_as_one_product():
+    # 64 or 128 columns per shard and the left operand replicated over the cuts that split them: forward and data gradient
+    # run one product per group of shards, every wave writing into its own shard's result
+    run_conv(4, 256, 256, 6, 6, 3, 3, 1, 2, True, "rr", "RR", "CC", "rr", "CC", "22", "22", "11", 180)    # the planner's kind of tiling
+    run_conv(4, 64, 256, 5, 7, 3, 3, 1, 1, False, "r", "C", "C", "C", "r", "2", "3", "2", 181)            # 128 columns per shard, forward only fused
+    run_conv(8, 128, 128, 4, 4, 3, 3, 1, 2, True, "Rr", "rC", "RC", "Rr", "RC", "12", "12", "31", 182)    # two groups of two members
+    run_conv(4, 128, 256, 4, 4, 1, 1, 0, 2, False, "rC", "RC", "Cr", "rr", "CC", "23", "22", "12", 183)   # partial sums per member (F3 beside F2), 1 x 1 filters
+
+
 def test_fp32_convolutions():
     # fp32 operands and results on the plain kernels: no cut, every form at one cut, mixed forms and stored tilings at
     # two cuts (partial sums, gate, conversions as for bf16), odd channel counts (no 16-byte vectors needed), 5 x 3 taps

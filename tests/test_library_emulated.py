@@ -126,6 +126,10 @@ def test_conv_weight_gradient_every_number_of_partial_sums(on_host, monkeypatch,
     on_host["conv"].run_conv(12, 16, 272, 8, 8, 3, 3, 1, 3, True, "RRC", "rrR", "RRr", "RRC", "RRr", "112", "113", "332", 150 + parts)
 
 
+def test_conv_shards_that_share_their_left_operand(on_host):
+    on_host["conv"].test_shards_that_share_their_left_operand_run_as_one_product()
+
+
 def test_conv_fp32(on_host):
     on_host["conv"].test_fp32_convolutions()
 
