@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Turns the rocprofv3 output of four runs of bench.py on one workload into the short text summaries under profiles/
+"""Turns the rocprofv3 output of four (or five) runs of bench.py on one workload into the short text summaries under profiles/
 and into the entry of profiles/hbm_traffic.json that bench.py reads for `roofline.traffic`.
 
 The four runs (each from /tmp on the MI355X machine, `export TMPDIR=/tmp` first; R = the repository, O = an output folder,
@@ -11,6 +11,8 @@ W = the workload arguments, e.g. `--workload vgg16_fc` or `--workload vgg16_conv
       --no-graph --headline-only --no-cpu-baseline
   rocprofv3 --pmc WRITE_SIZE --output-format csv -d O/write -o run -- python3 R/bench.py W (same arguments)
   rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES --output-format csv -d O/mfma -o run -- python3 R/bench.py W (same)
+  (optional) rocprofv3 --pmc SQ_WAVE_CYCLES SQ_WAIT_ANY SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS SQ_ACTIVE_INST_LDS SQ_ACTIVE_INST_VMEM \\
+      --output-format csv -d O/sq -o run -- python3 R/bench.py W (same)
 
 then, anywhere:   python3 profile_summary.py O
 
@@ -178,6 +180,23 @@ def main():
                 tfl = rec["flops"] / (dur[i] * 1e-6) / 1e12
                 f.write("%-3d %-44s %16.0f %16.0f %8.3f %9.1f %8.3f\n" % (i, key(rec), busy[i], cu[i], busy[i] / (4.0 * cu[i]) if cu[i] else 0.0,
                                                                        tfl, tfl / PEAK_TFLOPS))
+    # ---- where the waves' cycles go (optional fifth run)
+    sp = glob.glob(os.path.join(O, "sq", "**", "*counter_collection.csv"), recursive=True)
+    if sp:
+        c = counters(sp[0], n)
+        names_sq = ["SQ_WAVE_CYCLES", "SQ_WAIT_ANY", "SQ_WAIT_INST_ANY", "SQ_WAIT_INST_LDS", "SQ_ACTIVE_INST_LDS", "SQ_ACTIVE_INST_VMEM"]
+        with open(os.path.join(PROFILES, "%s_step_wave_cycles_pmc.txt" % wl), "w") as f:
+            f.write("# Where the waves' cycles go per launch of workload %s (rocprofv3 --pmc %s;\n"
+                    "# command: see profile_summary.py).  Shares of SQ_WAVE_CYCLES (cycles waves spend resident): waiting at a wait\n"
+                    "# count or barrier (WAIT_ANY), waiting for an instruction to be issued (WAIT_INST_ANY), of which for an LDS\n"
+                    "# instruction (WAIT_INST_LDS); cycles an LDS / a vector-memory instruction is being issued.\n" % (wl, " ".join(names_sq)))
+            f.write("%-3s %-44s %14s %10s %14s %14s %12s %12s\n" % ("#", "launch", "WAVE_CYCLES", "WAIT_ANY", "WAIT_INST_ANY", "WAIT_INST_LDS",
+                                                                    "ACTIVE_LDS", "ACTIVE_VMEM"))
+            for i, rec in enumerate(launches):
+                wc = c["SQ_WAVE_CYCLES"][0][i] or 1.0
+                f.write("%-3d %-44s %14.0f %10.3f %14.3f %14.3f %12.3f %12.3f\n" % (
+                    i, key(rec), wc, c["SQ_WAIT_ANY"][0][i] / wc, c["SQ_WAIT_INST_ANY"][0][i] / wc, c["SQ_WAIT_INST_LDS"][0][i] / wc,
+                    c["SQ_ACTIVE_INST_LDS"][0][i] / wc, c["SQ_ACTIVE_INST_VMEM"][0][i] / wc))
     print("wrote profiles for", wl)
 
 
