@@ -100,28 +100,25 @@ WgradChoice pick_wgrad_parts(int k, int nblk, int nred, int64_t ktps, int64_t Ks
 
 // Shards that differ only in their side at the F2 cuts read the same left operand (its aligned tiling replicates it
 // there).  Where each of them has few columns (at most 128: narrow tiles take in the left operand once per 64 or 128
-// columns), they are run as one product per group, `members` column blocks side by side.  Fills the per-group and
-// per-member pointer lists in the order launch_conv_fused wants; returns the number of members, or 1 for "run them shard by
-// shard".
-int fuse_f2(const uint8_t *forms, int k, int64_t cols_per_shard, int dtype, const Sharded &left, const Sharded &right,
-            void *const *out, const void **A, const void **B, void **C)
+// columns), they are run as one product per group, `members` column blocks side by side.
+struct F2Group {
+    int members = 1, groups = 0; // members == 1: run the shards one by one
+    uint32_t mask2 = 0, mask_g = 0;
+    uint32_t shard(int g, int m, int k) const { return deposit((uint32_t)g, mask_g, k) | deposit((uint32_t)m, mask2, k); }
+};
+F2Group f2_group(const uint8_t *forms, int k, int64_t cols_per_shard, int dtype)
 {
-    uint32_t mask2 = 0;
+    F2Group r;
     for (int j = 0; j < k; ++j)
-        if (forms[j] == TT_F2) mask2 |= 1u << (k - 1 - j);
-    const int k2 = __builtin_popcount(mask2), members = 1 << k2, groups = (1 << k) >> k2;
-    if (k2 == 0 || dtype != TT_BF16 || cols_per_shard > 128 || cols_per_shard % 64 || tuning_int("TT_CONV_FUSE", 1) == 0) return 1;
-    const uint32_t mask_g = ((1u << k) - 1u) & ~mask2;
-    for (int g = 0; g < groups; ++g) {
-        const uint32_t gid = deposit((uint32_t)g, mask_g, k);
-        A[g] = left.ptr[gid];
-        for (int m = 0; m < members; ++m) {
-            const uint32_t sid = gid | deposit((uint32_t)m, mask2, k);
-            B[g * members + m] = right.ptr[sid];
-            C[g * members + m] = out[sid];
-        }
-    }
-    return members;
+        if (forms[j] == TT_F2) r.mask2 |= 1u << (k - 1 - j);
+    r.mask_g = ((1u << k) - 1u) & ~r.mask2;
+    const int k2 = __builtin_popcount(r.mask2);
+    r.groups = (1 << k) >> k2;
+    if (k2 > 0 && dtype == TT_BF16 && cols_per_shard <= 128 && cols_per_shard % 64 == 0 && tuning_int("TT_CONV_FUSE", 1) != 0)
+        r.members = 1 << k2;
+    else
+        r.groups = 1 << k;
+    return r;
 }
 
 tt_status forward(const ConvArgs &a, const Dims &d, Workspace &ws)
@@ -141,22 +138,45 @@ tt_status forward(const ConvArgs &a, const Dims &d, Workspace &ws)
     if ((st = act_view(&X, a.X, a.tX, k, d.N, hw, d.C)) != TT_OK) return st;
     if ((st = filter_view(&W, a.W, a.tW, k, d)) != TT_OK) return st;
     const int esz = a.dtype == TT_BF16 ? 2 : 4;
+    // With fused shards the filters are converted to the aligned tiling with the F2 cuts replicated instead: every group
+    // then holds ONE matrix of all its members' filter rows, member blocks one after the other.
+    const F2Group fg = f2_group(f, k, d.K >> k2, a.dtype);
+    tt_tiling aWs = transpose_tiling(aW, k);
+    if (fg.members > 1)
+        for (int j = 0; j < k; ++j)
+            if (f[j] == TT_F2) aWs.cut[j] = TT_REP;
     if ((st = prepare_operand(X, aX, k, esz, nullptr, a.dtype, ws, a.stream, &Xa)) != TT_OK) return st;
-    if ((st = prepare_operand(W, transpose_tiling(aW, k), k, esz, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
+    if ((st = prepare_operand(W, aWs, k, esz, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
     OutputPlan op;
     if ((st = plan_output(f, a.tY, a.Yout, d.N * pq, d.K, k, a.dtype, a.layer->act, ws, &op)) != TT_OK) return st;
     if (ws.dry) return TT_OK;
-    {
+    if (fg.members > 1) {
         const void *fa[kMaxShards], *fb[kMaxShards];
         void *fc[kMaxShards];
-        const int members = fuse_f2(f, k, d.K >> k2, a.dtype, Xa, Wa, op.gemm_out, fa, fb, fc);
-        st = members > 1 ? launch_conv_fused(TT_OP_FWD, n / members, members, fa, fb, fc, d.N >> k1, d.K >> k2, d.C >> k3, d.H, d.W,
-                                             d.R, d.S, d.pad, op.gemm_dtype, op.gemm_act, a.stream, nullptr)
-                         : TT_EUNSUPPORTED;
-    }
-    if (st == TT_EUNSUPPORTED)
+        const size_t block_bytes = (size_t)(d.K >> k2) * (size_t)rs * (size_t)(d.C >> k3) * 2;
+        for (int g = 0; g < fg.groups; ++g) {
+            fa[g] = Xa.ptr[fg.shard(g, 0, k)];
+            for (int m = 0; m < fg.members; ++m) {
+                fb[g * fg.members + m] = static_cast<const char *>(Wa.ptr[fg.shard(g, 0, k)]) + (size_t)m * block_bytes;
+                fc[g * fg.members + m] = op.gemm_out[fg.shard(g, m, k)];
+            }
+        }
+        st = launch_conv_fused(TT_OP_FWD, fg.groups, fg.members, fa, fb, fc, d.N >> k1, d.K >> k2, d.C >> k3, d.H, d.W, d.R, d.S,
+                               d.pad, op.gemm_dtype, op.gemm_act, a.stream, nullptr);
+        if (st == TT_EUNSUPPORTED) { // shard by shard on the same buffers: member m's filters are block m of its group's matrix
+            const void *xs[kMaxShards], *wsh[kMaxShards];
+            for (int g = 0; g < fg.groups; ++g)
+                for (int m = 0; m < fg.members; ++m) {
+                    xs[fg.shard(g, m, k)] = fa[g];
+                    wsh[fg.shard(g, m, k)] = fb[g * fg.members + m];
+                }
+            st = launch_conv(TT_OP_FWD, n, xs, wsh, op.gemm_out, d.N >> k1, d.C >> k3, d.K >> k2, d.H, d.W, d.R, d.S, d.pad,
+                             op.gemm_dtype, op.gemm_act, a.stream, nullptr, a.dtype);
+        }
+    } else {
         st = launch_conv(TT_OP_FWD, n, Xa.ptr, Wa.ptr, op.gemm_out, d.N >> k1, d.C >> k3, d.K >> k2, d.H, d.W, d.R, d.S, d.pad,
                          op.gemm_dtype, op.gemm_act, a.stream, nullptr, a.dtype);
+    }
     if (st != TT_OK) return st;
     return finish_output(op, a.tY, a.Yout, d.N * pq, d.K, k, a.dtype, a.layer->act, a.stream);
 }
@@ -215,23 +235,24 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
         }
         if (ws.overflow) return TT_EWORKSPACE;
         if (!ws.dry) {
-            {
+            const F2Group fg = f2_group(f, k, d.C >> k2, a.dtype);
+            st = TT_EUNSUPPORTED;
+            if (fg.members > 1) {
                 const void *fa[kMaxShards], *fb[kMaxShards];
                 void *fc[kMaxShards], *ff[kMaxShards];
-                const int members = fuse_f2(f, k, d.C >> k2, a.dtype, Ga, Wa, op.gemm_out, fa, fb, fc);
-                if (members > 1) { // the scratch buffers in the same order as the filter blocks
-                    Sharded fl;
-                    for (int s = 0; s < n; ++s) fl.ptr[s] = flip[s];
-                    const void *dummy_a[kMaxShards], *fbf[kMaxShards];
-                    void *dummy_c[kMaxShards];
-                    (void)fuse_f2(f, k, d.C >> k2, a.dtype, Ga, fl, op.gemm_out, dummy_a, fbf, dummy_c);
-                    for (int i = 0; i < n; ++i) ff[i] = const_cast<void *>(fbf[i]);
+                for (int g = 0; g < fg.groups; ++g) {
+                    fa[g] = Ga.ptr[fg.shard(g, 0, k)];
+                    for (int m = 0; m < fg.members; ++m) {
+                        const uint32_t sid = fg.shard(g, m, k);
+                        fb[g * fg.members + m] = Wa.ptr[sid];
+                        fc[g * fg.members + m] = op.gemm_out[sid];
+                        ff[g * fg.members + m] = flip[sid];
+                    }
                 }
-                st = members > 1 ? launch_conv_fused(TT_OP_DGRAD, n / members, members, fa, fb, fc, d.N >> k1, d.C >> k2, d.K >> k3,
-                                                     d.H, d.W, d.R, d.S, d.pad, op.gemm_dtype, TT_ACT_NONE, a.stream, ff)
-                                 : TT_EUNSUPPORTED;
+                st = launch_conv_fused(TT_OP_DGRAD, fg.groups, fg.members, fa, fb, fc, d.N >> k1, d.C >> k2, d.K >> k3, d.H, d.W, d.R,
+                                       d.S, d.pad, op.gemm_dtype, TT_ACT_NONE, a.stream, ff);
             }
-            if (st == TT_EUNSUPPORTED)
+            if (st == TT_EUNSUPPORTED) // filters that the flipped-filter path does not take: shard by shard
                 st = launch_conv(TT_OP_DGRAD, n, Ga.ptr, Wa.ptr, op.gemm_out, d.N >> k1, d.C >> k2, d.K >> k3, d.H, d.W, d.R, d.S,
                                  d.pad, op.gemm_dtype, TT_ACT_NONE, a.stream, bf16 ? flip : nullptr, a.dtype);
             if (st != TT_OK) return st;
