@@ -139,6 +139,15 @@ def test_shards_that_share_their_left_operand_run_as_one_product():
     run_conv(4, 128, 256, 4, 4, 1, 1, 0, 2, False, "rC", "RC", "Cr", "rr", "CC", "23", "22", "12", 183)   # partial sums per member (F3 beside F2), 1 x 1 filters
 
 
+def test_weight_gradient_of_shards_that_share_the_images_runs_as_one_product():
+    # at most 128 output channels per shard and X replicated over the cuts that split them: the weight gradient runs as
+    # one product over all output channels of a group (dY converted with those cuts replicated), its pixel range cut evenly
+    run_conv(4, 64, 256, 8, 8, 3, 3, 1, 2, True, "rr", "CC", "CC", "CC", "rr", "22", "33", "22", 185)    # the output-channel split: one group
+    run_conv(8, 32, 256, 8, 8, 3, 3, 1, 2, False, "Rr", "rC", "RC", "RC", "Rr", "12", "13", "32", 186)   # a batch cut beside it: two shards add up
+    run_conv(4, 64, 512, 8, 8, 3, 3, 1, 2, True, "Cr", "RC", "rC", "rC", "Cr", "32", "23", "12", 187)    # an input-channel cut beside it: two blocks
+    run_conv(4, 16, 384, 4, 16, 1, 1, 0, 3, False, "rrR", "CCr", "CCR", "CCR", "rrR", "221", "331", "223", 188)  # 96 channels per shard, three cuts
+
+
 def test_fp32_convolutions():
     # fp32 operands and results on the plain kernels: no cut, every form at one cut, mixed forms and stored tilings at
     # two cuts (partial sums, gate, conversions as for bf16), odd channel counts (no 16-byte vectors needed), 5 x 3 taps

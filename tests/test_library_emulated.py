@@ -130,6 +130,10 @@ def test_conv_shards_that_share_their_left_operand(on_host):
     on_host["conv"].test_shards_that_share_their_left_operand_run_as_one_product()
 
 
+def test_conv_weight_gradient_of_shards_that_share_the_images(on_host):
+    on_host["conv"].test_weight_gradient_of_shards_that_share_the_images_runs_as_one_product()
+
+
 def test_conv_fp32(on_host):
     on_host["conv"].test_fp32_convolutions()
 
