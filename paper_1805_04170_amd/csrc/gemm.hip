@@ -323,6 +323,17 @@ tt_status launch_gemm(int count, const void *const *A, const void *const *B, voi
             const tt_status st = launch_gemm_v5(count, A, B, C, M, N, K, a_contig, b_contig, N, act == TT_ACT_RELU, stream);
             if (st != TT_EUNSUPPORTED) return st;
         }
+        //  - of those, the products A B^T with both operands K-contiguous (the data gradients) that give between half a
+        //    tile and one 256 x 128 tile per CU: the same tile with K tiles of 64, which fetches whole 128-byte lines of the
+        //    streamed weights (gemm_core6.h says what that is worth: 74 -> 66 us for the first VGG-16 data gradient; with
+        //    more tiles than CUs, with fewer than half as many, and for the NN layout it measured equal or slower)
+        const int64_t tiles128 = ((M + 255) / 256) * ((N + 127) / 128) * count * ksplit;
+        if (a_kc && (engine == 6 || (engine == 0 && b_kc && big_tiles < 200 && M > 128 && N >= 256 && tiles128 >= 128 &&
+                                     tiles128 <= 256 && (ksplit > 1 ? kchunk : K) >= 256))) {
+            const tt_status st = launch_gemm_v6(count, A, B, C, M, N, K, a_contig, b_contig, N, b_kc, out_dtype, act == TT_ACT_RELU,
+                                                vec, ksplit, kchunk, stream);
+            if (st != TT_EUNSUPPORTED) return st;
+        }
         if (engine == 4 || (engine == 0 && big_tiles < 200 && M > 128 && N >= 256)) {
             const tt_status st = launch_gemm_v4(count, A, B, C, M, N, K, a_contig, b_contig, N, a_kc, b_kc, out_dtype,
                                                 act == TT_ACT_RELU, vec, ksplit, kchunk, stream);

@@ -7,6 +7,7 @@
 #include "gemm_core3.h"
 #include "gemm_core4.h"
 #include "gemm_core5.h"
+#include "gemm_core6.h"
 #include "gemm3_params.h"
 #include "tt_internal.h"
 #include "launch_util.h"
@@ -55,6 +56,35 @@ template <bool A_KC, bool B_KC> tt_status launch_layout4(core3::Params3 &p, int 
     const bool bf = out_dtype == TT_BF16;
     if (bf && vec) return launch_cfg4<A_KC, B_KC, true, true>(p, s);
     return bf ? launch_cfg4<A_KC, B_KC, true, false>(p, s) : launch_cfg4<A_KC, B_KC, false, false>(p, s);
+}
+
+// skinny products with both operands K-contiguous: 256 x 128 tiles, K tiles of 64, one workgroup per CU (gemm_core6.h)
+template <bool B_KC, bool OUT_BF16, bool STAGED>
+__global__ __launch_bounds__(core6::kThreads6, 1) void gemm_bf16_v6_kernel(const core3::Params3 p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem4[];
+    const int logical = core::logical_block(p.per_xcd, p.total);
+    if (logical < 0) return;
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int vshard = logical / tiles;
+    const int t = logical - vshard * tiles;
+    int tm, tn;
+    core::grouped_tile(t, p.tiles_m, p.tiles_n, &tm, &tn);
+    const int shard = vshard / p.ksplit;
+    const int kbeg = (vshard - shard * p.ksplit) * p.kchunk;
+    const int klen = p.K - kbeg < p.kchunk ? p.K - kbeg : p.kchunk;
+    const char *abase = reinterpret_cast<const char *>(p.A[shard]) + (size_t)kbeg * 2;
+    const char *bbase = reinterpret_cast<const char *>(p.B[shard]) + (size_t)kbeg * (B_KC ? 2 : 2 * (size_t)p.ldb);
+    core6::tile_product6<B_KC, OUT_BF16, STAGED>(abase, p.lda, bbase, p.ldb, p.C[vshard], p.ldc, p.M, p.N, klen, tm * core6::BM6,
+                                           tn * core6::BN6, p.relu != 0, smem4);
+}
+
+template <bool B_KC, bool OUT_BF16, bool STAGED> tt_status launch_cfg6(core3::Params3 &p, hipStream_t s)
+{
+    auto kern = gemm_bf16_v6_kernel<B_KC, OUT_BF16, STAGED>;
+    if (ensure_dynamic_lds(reinterpret_cast<const void *>(kern), core6::kSmem6) != TT_OK) return TT_EDEVICE;
+    hipLaunchKernelGGL(kern, dim3((uint32_t)p.per_xcd * core::kXcds), dim3(core6::kThreads6), core6::kSmem6, s, p);
+    return hipGetLastError() == hipSuccess ? TT_OK : TT_EDEVICE;
 }
 
 // short-K products with the left operand's panel held in registers (gemm_core5.h); two workgroups per CU
@@ -161,6 +191,25 @@ tt_status launch_gemm_v4(int count, const void *const *A, const void *const *B, 
     if (a_kc && !b_kc) return launch_layout4<true, false>(p, out_dtype, vec, s);
     if (!a_kc && !b_kc) return launch_layout4<false, false>(p, out_dtype, vec, s);
     return launch_layout4<false, true>(p, out_dtype, vec, s);
+}
+
+// C_s = A_s B_s with A's rows K-contiguous (B either way), K (and a K chunk) a multiple of 64.
+tt_status launch_gemm_v6(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
+                         int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool b_kc, int out_dtype, int relu, bool vec,
+                         int ksplit, int64_t kchunk, void *stream)
+{
+    core3::Params3 p;
+    const tt_status st = fill_params3(&p, core6::BM6, core6::BN6, core6::BK6, 0, count, A, B, C, M, N, K, lda, ldb, ldc, true, b_kc,
+                                      relu, ksplit, kchunk);
+    if (st != TT_OK) return st;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const bool bf = out_dtype == TT_BF16;
+    if (b_kc) {
+        if (bf && vec) return launch_cfg6<true, true, true>(p, s);
+        return bf ? launch_cfg6<true, true, false>(p, s) : launch_cfg6<true, false, false>(p, s);
+    }
+    if (bf && vec) return launch_cfg6<false, true, true>(p, s);
+    return bf ? launch_cfg6<false, true, false>(p, s) : launch_cfg6<false, false, false>(p, s);
 }
 
 tt_status launch_gemm_v3(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,

@@ -92,6 +92,75 @@ template <int ROWS, bool KC> __device__ __forceinline__ bf16x8 read_frag4(const 
     }
 }
 
+// Write-out of a workgroup's 256 x 128 accumulator tile (four waves as 2 x 2, 128 x 64 per wave: the wave tile of this
+// engine and of gemm_core6.h).  The ring must be drained and idle: STAGED turns bf16 results round in a wave-private
+// strip at the start of smem (at least 4 * 16 * 72 * 2 bytes), 16 rows at a time; everything else is stored element-wise.
+template <bool OUT_BF16, bool STAGED>
+__device__ __forceinline__ void write_tile4(f32x16 (&acc)[4][2], void *Cv, int ldc, int M, int N, int m0, int n0, bool relu,
+                                            char *smem)
+{
+    constexpr int TM = 4, TN = 2, WN = 2;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm0 = (wave / WN) * (TM * 32), wn0 = (wave % WN) * (TN * 32);
+    // ---- epilogue.  A lane holds column (lane & 31) and rows 8*(e/4) + 4*(lane/32) + e%4 of each 32 x 32 block.
+    const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+    if constexpr (!STAGED) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + wn0 + j * 32 + col_l;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wm0 + i * 32 + 8 * (e >> 2) + row_l + (e & 3);
+                    float v = acc[i][j][e];
+                    if (relu) v = fmaxf(v, 0.0f);
+                    if (row < M && col < N) {
+                        if constexpr (OUT_BF16)
+                            reinterpret_cast<uint16_t *>(Cv)[(size_t)row * ldc + col] = (uint16_t)core::f32_to_bf16_bits(v);
+                        else
+                            __builtin_nontemporal_store(v, reinterpret_cast<float *>(Cv) + (size_t)row * ldc + col);
+                    }
+                }
+            }
+    } else {
+        constexpr int ER = 16, ELD = 64 + 8; // strip of one wave: 16 rows x 64 columns of bf16, padded
+        static_assert(4 * ER * ELD * 2 <= kSmem4, "strips fit in the ring");
+        uint16_t *strip = reinterpret_cast<uint16_t *>(smem) + wave * (ER * ELD);
+        uint16_t *Cs = reinterpret_cast<uint16_t *>(Cv);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int eg = 0; eg < 2; ++eg)
+#pragma unroll
+                        for (int ee = 0; ee < 4; ee += 2) {
+                            float v0 = acc[i][j][(2 * h + eg) * 4 + ee], v1 = acc[i][j][(2 * h + eg) * 4 + ee + 1];
+                            if (relu) { v0 = fmaxf(v0, 0.0f); v1 = fmaxf(v1, 0.0f); }
+                            const uint32_t pk = core::pack_bf16x2(v0, v1);
+                            uint16_t *d = strip + (8 * eg + row_l + ee) * ELD + j * 32 + col_l;
+                            d[0] = (uint16_t)(pk & 0xffffu);
+                            d[ELD] = (uint16_t)(pk >> 16);
+                        }
+                // Wave-private data: LDS operations of one wave execute in order, so the reads below see the writes above and the
+                // next strip's writes cannot overtake them; no wait is needed, only a fence for the compiler's scheduler.
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int v = 0; v < 2; ++v) {
+                    const int idx = lane + 64 * v, lrow = idx >> 3, vc = (idx & 7) * 8;
+                    const int row = m0 + wm0 + i * 32 + 16 * h + lrow, col = n0 + wn0 + vc;
+                    const u32x4 o = *reinterpret_cast<const u32x4 *>(strip + lrow * ELD + vc);
+                    if (row < M && col < N) // N is a multiple of 8 on this path: a vector is all in or all out
+                        __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(Cs + (size_t)row * ldc + col));
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+    }
+}
+
 // C tile (m0, n0) of C = A B over K = klen (a multiple of 32) starting at the operands' k = 0 as given by abase / bbase.
 // 256 threads; smem: kSmem4 bytes, 16-byte aligned.  STAGED: bf16 result, 16-byte stores legal.
 template <bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED>
@@ -160,64 +229,7 @@ __device__ __forceinline__ void tile_product4(const char *abase, int lda, const 
     // the re-fetches issued past the end have landed and every wave is done with the ring: it can be reused / given up
     __builtin_amdgcn_s_waitcnt(core3::waitcnt_vm(0));
     __syncthreads();
-
-    // ---- epilogue.  A lane holds column (lane & 31) and rows 8*(e/4) + 4*(lane/32) + e%4 of each 32 x 32 block.
-    const int col_l = lane & 31, row_l = (lane >> 5) * 4;
-    if constexpr (!STAGED) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + wn0 + j * 32 + col_l;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = m0 + wm0 + i * 32 + 8 * (e >> 2) + row_l + (e & 3);
-                    float v = acc[i][j][e];
-                    if (relu) v = fmaxf(v, 0.0f);
-                    if (row < M && col < N) {
-                        if constexpr (OUT_BF16)
-                            reinterpret_cast<uint16_t *>(Cv)[(size_t)row * ldc + col] = (uint16_t)core::f32_to_bf16_bits(v);
-                        else
-                            __builtin_nontemporal_store(v, reinterpret_cast<float *>(Cv) + (size_t)row * ldc + col);
-                    }
-                }
-            }
-    } else {
-        constexpr int ER = 16, ELD = 64 + 8; // strip of one wave: 16 rows x 64 columns of bf16, padded
-        static_assert(4 * ER * ELD * 2 <= kSmem4, "strips fit in the ring");
-        uint16_t *strip = reinterpret_cast<uint16_t *>(smem) + wave * (ER * ELD);
-        uint16_t *Cs = reinterpret_cast<uint16_t *>(Cv);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int eg = 0; eg < 2; ++eg)
-#pragma unroll
-                        for (int ee = 0; ee < 4; ee += 2) {
-                            float v0 = acc[i][j][(2 * h + eg) * 4 + ee], v1 = acc[i][j][(2 * h + eg) * 4 + ee + 1];
-                            if (relu) { v0 = fmaxf(v0, 0.0f); v1 = fmaxf(v1, 0.0f); }
-                            const uint32_t pk = core::pack_bf16x2(v0, v1);
-                            uint16_t *d = strip + (8 * eg + row_l + ee) * ELD + j * 32 + col_l;
-                            d[0] = (uint16_t)(pk & 0xffffu);
-                            d[ELD] = (uint16_t)(pk >> 16);
-                        }
-                // Wave-private data: LDS operations of one wave execute in order, so the reads below see the writes above and the
-                // next strip's writes cannot overtake them; no wait is needed, only a fence for the compiler's scheduler.
-                __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                for (int v = 0; v < 2; ++v) {
-                    const int idx = lane + 64 * v, lrow = idx >> 3, vc = (idx & 7) * 8;
-                    const int row = m0 + wm0 + i * 32 + 16 * h + lrow, col = n0 + wn0 + vc;
-                    const u32x4 o = *reinterpret_cast<const u32x4 *>(strip + lrow * ELD + vc);
-                    if (row < M && col < N) // N is a multiple of 8 on this path: a vector is all in or all out
-                        __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(Cs + (size_t)row * ldc + col));
-                }
-                __builtin_amdgcn_wave_barrier();
-            }
-    }
+    write_tile4<OUT_BF16, STAGED>(acc, Cv, ldc, M, N, m0, n0, relu, smem);
 }
 
 } // namespace core4

@@ -142,6 +142,11 @@ tt_status launch_gemm_v5(int count, const void *const *A, const void *const *B, 
 tt_status launch_gemm_v4(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
                          int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool a_kc, bool b_kc, int out_dtype, int relu,
                          bool vec, int ksplit, int64_t kchunk, void *stream);
+// The same tile with K tiles of 64 and one workgroup per CU for products whose left operand has K contiguous
+// (gemm_core6.h); K and a K chunk multiples of 64.
+tt_status launch_gemm_v6(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
+                         int64_t K, int64_t lda, int64_t ldb, int64_t ldc, bool b_kc, int out_dtype, int relu, bool vec,
+                         int ksplit, int64_t kchunk, void *stream);
 
 // Convolution shard products (conv.hip).  op TT_OP_FWD: A = X shards, B = filter shards, C = Y shards;
 // TT_OP_DGRAD: A = dY, B = filters, C = dX;  TT_OP_WGRAD: A = dY, B = X, C = dW.  Ns images, Cs input channels and

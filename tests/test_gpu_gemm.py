@@ -105,6 +105,16 @@ def test_bf16_two_workgroups_per_cu_engine(ta, tb, out_dt):
     check(1, 136, 264, 32, ta, tb, "bf16", out_dt, False, 47)
 
 
+@pytest.mark.parametrize("out_dt", ["bf16", "f32"])
+def test_bf16_line_wide_k_tiles_engine(out_dt):
+    # skinny A B^T products with at most one 256 x 128 tile per CU and K a multiple of 64 (the data gradients at batch
+    # 256): the 256 x 128 engine with K tiles of 64 (two stages of A, three of B); ragged N, ragged M, K loops of 8, 4
+    # and 64 tiles, the last at the shape of the VGG-16 first data gradient
+    check(16, 256, 1064, 512, 0, 1, "bf16", out_dt, True, 49)
+    check(32, 200, 392, 256, 0, 1, "bf16", out_dt, False, 50)
+    check(6, 256, 3136, 4096, 0, 1, "bf16", out_dt, False, 51)
+
+
 @pytest.mark.parametrize("K", [256, 128])
 def test_bf16_panel_in_registers_engine(K):
     # weight-gradient shaped products (both operands stored K-major, K = 128 / 256, large bf16 result): the engine that

@@ -239,7 +239,9 @@ def emu_shard_gemm(emulators):
 # then the number of threads the launch must have run (which names the engine: workgroups x their size)
 SHARD_CASES = [
     ((8, 256, 512, 4096, 0, 0, 1, 1, 1, 1), 32 * 256),      # hidden layer forward at batch 256: 256 x 128 tiles, two workgroups per CU
-    ((8, 256, 3136, 4096, 0, 1, 1, 1, 0, 1), 200 * 256),    # VGG-16 first data gradient, not split: 200 tiles of 256 x 128
+    ((8, 256, 3136, 4096, 0, 1, 1, 1, 0, 1), 200 * 256),    # VGG-16 first data gradient, not split: 200 tiles of 256 x 128, K tiles of 64
+    ((8, 256, 1024, 2048, 0, 1, 1, 0, 0, 1), 64 * 256),     # ... second one, fp32 partial sums: too few tiles for that, K tiles of 32
+    ((8, 256, 4608, 1024, 0, 1, 1, 1, 0, 1), 288 * 256),    # AlexNet first data gradient: more tiles than CUs, K tiles of 32, two workgroups per CU
     ((8, 256, 4096, 3136, 0, 0, 1, 0, 0, 1), 256 * 256),    # ... first forward product (fp32 partial sums of the F3 cuts): one workgroup per CU
     ((8, 3136, 4096, 256, 1, 0, 1, 1, 0, 1), 512 * 256),    # VGG-16 first weight gradient: the panel-in-registers engine, two workgroups of four waves per CU
     ((8, 1152, 4096, 128, 1, 0, 1, 1, 0, 1), 512 * 256),    # the same engine at a per-shard batch of 128

@@ -90,6 +90,29 @@ def test_persistent_engine_values(lockstep_gemm, tmp_path, ta, tb, out_dt):
     check(lockstep_gemm, str(tmp_path), 1, 264, 520, 192, ta, tb, "bf16", out_dt, False, 44, env=env)
 
 
+@pytest.mark.parametrize("tb", [1, 0])
+@pytest.mark.parametrize("out_dt", ["bf16", "f32"])
+def test_line_wide_k_tiles_engine_values(lockstep_gemm, tmp_path, out_dt, tb):
+    # the 256 x 128 engine with K tiles of 64 for A B^T products (two stages of A, three of B, waits that count loads):
+    # ragged M and N, K loops of one tile (shorter than either ring), three and seven tiles, a K split inside the launch
+    env = {"TT_GEMM_ENGINE": "6"}
+    out = check(lockstep_gemm, str(tmp_path), 1, 264, 392, 192, 0, tb, "bf16", out_dt, True, 48, env=env)
+    assert int(out.split()[3]) == 8 * 256      # 2 x 4 tiles of 256 x 128, 256 threads each
+    check(lockstep_gemm, str(tmp_path), 2, 136, 264, 64, 0, tb, "bf16", out_dt, False, 49, env=env)
+    check(lockstep_gemm, str(tmp_path), 1, 256, 256, 448, 0, tb, "bf16", out_dt, False, 50, env=env)
+    if out_dt == "f32":
+        check(lockstep_gemm, str(tmp_path), 2, 256, 136, 320, 0, tb, "bf16", "f32", False, 51, ksplit=2, env=env)   # chunks of 192 and 128
+
+
+def test_line_wide_k_tiles_engine_as_the_library_chooses_it(lockstep_gemm, tmp_path):
+    # a skinny data-gradient shaped product (one row of tiles, 128 of them for 256 CUs, K of four tiles): no switch set
+    check(lockstep_gemm, str(tmp_path), 32, 256, 392, 256, 0, 1, "bf16", "bf16", False, 52)
+    # ... and with every wait letting two more loads stay in flight than the kernel asks for it must not get away with it
+    with pytest.raises(AssertionError):
+        check(lockstep_gemm, str(tmp_path), 32, 256, 392, 256, 0, 1, "bf16", "bf16", False, 52, env={"EMU_VMCNT_SLACK": "2"})
+    check(lockstep_gemm, str(tmp_path), 32, 256, 392, 256, 0, 1, "bf16", "bf16", False, 52, env={"EMU_ORDER": "reverse"})
+
+
 def test_persistent_engine_values_as_the_library_chooses_it(lockstep_gemm, tmp_path):
     # 240 tiles on 256 CUs: the weight-gradient layout, bf16 results (loads interleaved with the K steps)
     out = check(lockstep_gemm, str(tmp_path), 8, 1288, 1272, 64, 1, 0, "bf16", "bf16", False, 43)
@@ -156,7 +179,7 @@ def test_random_products_values(lockstep_gemm, tmp_path):
     # seeded random shapes, layouts, types and tuning switches (sizes mostly multiples of eight, some odd): whatever
     # engine the launch code picks or falls back to has to give the product
     rng = np.random.default_rng(2024)
-    switches = [{}, {}, {"TT_GEMM_ENGINE": "4"}, {"TT_GEMM_ENGINE": "3", "TT_GEMM_TILE": "5", "EMU_CUS": "8"},
+    switches = [{}, {}, {"TT_GEMM_ENGINE": "4"}, {"TT_GEMM_ENGINE": "6"}, {"TT_GEMM_ENGINE": "3", "TT_GEMM_TILE": "5", "EMU_CUS": "8"},
                 {"TT_GEMM_ENGINE": "1", "TT_GEMM_TILE": "8"}] + [{"TT_GEMM_ENGINE": "1", "TT_GEMM_TILE": str(t)} for t in range(6)]
 
     def dim(hi):
