@@ -107,10 +107,17 @@ def test_line_wide_k_tiles_engine_values(lockstep_gemm, tmp_path, out_dt, tb):
 def test_line_wide_k_tiles_engine_as_the_library_chooses_it(lockstep_gemm, tmp_path):
     # a skinny data-gradient shaped product (one row of tiles, 128 of them for 256 CUs, K of four tiles): no switch set
     check(lockstep_gemm, str(tmp_path), 32, 256, 392, 256, 0, 1, "bf16", "bf16", False, 52)
-    # ... and with every wait letting two more loads stay in flight than the kernel asks for it must not get away with it
+
+
+def test_line_wide_k_tiles_engine_waits_exactly_as_long_as_it_must(lockstep_gemm, tmp_path):
+    # with every wait letting two more loads stay in flight than the kernel asks for it must not get away with it; and
+    # its results do not depend on which wave runs ahead
+    env = {"TT_GEMM_ENGINE": "6"}
+    shape = (1, 264, 392, 320, 0, 1, "bf16", "f32", False, 53)
+    check(lockstep_gemm, str(tmp_path), *shape, env=env)
     with pytest.raises(AssertionError):
-        check(lockstep_gemm, str(tmp_path), 32, 256, 392, 256, 0, 1, "bf16", "bf16", False, 52, env={"EMU_VMCNT_SLACK": "2"})
-    check(lockstep_gemm, str(tmp_path), 32, 256, 392, 256, 0, 1, "bf16", "bf16", False, 52, env={"EMU_ORDER": "reverse"})
+        check(lockstep_gemm, str(tmp_path), *shape, env=dict(env, EMU_VMCNT_SLACK="2"))
+    check(lockstep_gemm, str(tmp_path), *shape, env=dict(env, EMU_ORDER="reverse"))
 
 
 def test_persistent_engine_values_as_the_library_chooses_it(lockstep_gemm, tmp_path):

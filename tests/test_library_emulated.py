@@ -117,7 +117,7 @@ def test_conv_weight_gradient_with_the_reduction_range_cut_evenly(on_host, monke
 
 
 @pytest.mark.parametrize("engine", [1, 2])
-@pytest.mark.parametrize("parts", [1, 2, 3, 5, 6, 7])
+@pytest.mark.parametrize("parts", [1, 3, 7])
 def test_conv_weight_gradient_every_number_of_partial_sums(on_host, monkeypatch, parts, engine):
     # the development build lets the test choose how many runs the reduction range is cut into: runs of unequal length,
     # runs that start inside one shard and end inside another, one run over all four shards of a block; on both engines
