@@ -316,10 +316,11 @@ tt_status launch_gemm(int count, const void *const *A, const void *const *B, voi
         const int engine = tuning_int("TT_GEMM_ENGINE", 0);
         const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * count * ksplit;
         //  - weight-gradient shaped products (both operands stored with K as the slow dimension, K = 128 or 256, a bf16
-        //    result large enough to give every resident workgroup several 256 x 64 units): the engine that keeps the left
-        //    operand's panel in registers and is bound by writing the result (gemm_core5.h)
+        //    result large enough to give every resident workgroup at least two 256 x 64 units; measured down to the second
+        //    VGG-16 weight gradient, 8 x 1024 x 2048 x 256: 16 us against 20 us on the persistent engine): the engine that
+        //    keeps the left operand's panel in registers and is bound by writing the result (gemm_core5.h)
         if ((engine == 5 || engine == 0) && !a_kc && !b_kc && ksplit == 1 && out_dtype == TT_BF16 && vec && in_dtype == TT_BF16 &&
-            (engine == 5 || ((M + 255) / 256) * (N / 64) * count >= 4 * 512)) {
+            (engine == 5 || ((M + 255) / 256) * (N / 64) * count >= 2 * 512)) {
             const tt_status st = launch_gemm_v5(count, A, B, C, M, N, K, a_contig, b_contig, N, act == TT_ACT_RELU, stream);
             if (st != TT_EUNSUPPORTED) return st;
         }
