@@ -315,7 +315,7 @@ tt_status launch_gemm(int count, const void *const *A, const void *const *B, voi
         //    layout measured 6 % faster on the persistent engine, the others equal or faster on the direct-to-LDS engine.
         const int engine = tuning_int("TT_GEMM_ENGINE", 0);
         const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * count * ksplit;
-        //  - weight-gradient shaped products (both operands stored with K as the slow dimension, K = 128 or 256, a bf16
+        //  - weight-gradient shaped products (both operands stored with K as the slow dimension, K = 128, 256 or 512, a bf16
         //    result large enough to give every resident workgroup at least two 256 x 64 units; measured down to the second
         //    VGG-16 weight gradient, 8 x 1024 x 2048 x 256: 16 us against 20 us on the persistent engine): the engine that
         //    keeps the left operand's panel in registers and is bound by writing the result (gemm_core5.h)

@@ -88,7 +88,7 @@ template <bool B_KC, bool OUT_BF16, bool STAGED> tt_status launch_cfg6(core3::Pa
 }
 
 // short-K products with the left operand's panel held in registers (gemm_core5.h); two workgroups per CU
-template <int KT, bool NTS> __global__ __launch_bounds__(core5::kThreads5, 2) void gemm_bf16_v5_kernel(const core5::Params5 p)
+template <int KT, bool NTS> __global__ __launch_bounds__(core5::kThreads5, KT <= 16 ? 2 : 1) void gemm_bf16_v5_kernel(const core5::Params5 p)
 {
     extern __shared__ __attribute__((aligned(16))) char smem3[];
     core5::run_panels<KT, NTS>(p, smem3);
@@ -147,12 +147,12 @@ template <bool A_KC, bool B_KC> tt_status launch_layout(core3::Params3 &p, int o
 
 } // namespace
 
-// C_s = A_s^T B_s, A_s stored K x M, B_s stored K x N, K = 128 or 256, bf16 result with 16-byte rows.
+// C_s = A_s^T B_s, A_s stored K x M, B_s stored K x N, K = 128, 256 or 512, bf16 result with 16-byte rows.
 // TT_EUNSUPPORTED when the engine does not take the product.
 tt_status launch_gemm_v5(int count, const void *const *A, const void *const *B, void *const *C, int64_t M, int64_t N,
                          int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int relu, void *stream)
 {
-    if ((K != 128 && K != 256) || N < core5::NT5 || N % core5::NT5 || M < 8 || M % 8 || count < 1 || count > 64)
+    if ((K != 128 && K != 256 && K != 512) || N < core5::NT5 || N % core5::NT5 || M < 8 || M % 8 || count < 1 || count > 64)
         return TT_EUNSUPPORTED;
     if (lda % 8 || ldb % 8 || ldc % 8 || lda < M || ldb < N || ldc < N) return TT_EUNSUPPORTED; // 16-byte chunks and rows
     if (K * lda >= (int64_t(1) << 30) || K * ldb >= (int64_t(1) << 30)) return TT_EUNSUPPORTED; // 32-bit byte offsets
@@ -169,11 +169,12 @@ tt_status launch_gemm_v5(int count, const void *const *A, const void *const *B, 
     const int64_t total = (int64_t)count * p.panels * p.ntiles;
     if (total >= (int64_t(1) << 30)) return TT_EUNSUPPORTED;
     p.total = (int32_t)total;
-    const int64_t resident = 2 * (int64_t)cu_count(); // two workgroups per CU
+    const int64_t resident = (K <= 256 ? 2 : 1) * (int64_t)cu_count(); // two workgroups per CU; one at K = 512
     p.grid = (int32_t)(total < resident ? total : resident);
     p.relu = relu;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const bool nts = tuning_int("TT_V5_NT", 1) != 0;
+    if (K == 512) return nts ? launch_cfg5<32, true>(p, s) : launch_cfg5<32, false>(p, s);
     if (K == 256) return nts ? launch_cfg5<16, true>(p, s) : launch_cfg5<16, false>(p, s);
     return nts ? launch_cfg5<8, true>(p, s) : launch_cfg5<8, false>(p, s);
 }

@@ -1,5 +1,5 @@
 // Fifth bf16 MFMA engine: products with a SHORT contraction and a LARGE result, C_s = A_s^T B_s with A_s stored K x M and
-// B_s stored K x N (both with K as the slow dimension) and K = 128 or 256.  These are the weight gradients
+// B_s stored K x N (both with K as the slow dimension) and K = 128, 256 or 512.  These are the weight gradients
 // dC/dW_l = x_l^T df(dC/dx_{l+1}) of Sec. 2.1 of arXiv 1805.04170 at a per-shard batch of 128 / 256: 2 K flops per result
 // element, so the product is bound by writing C, and the job of the kernel is to keep the chip writing.
 //
@@ -17,6 +17,10 @@
 //     partly past M store under a row mask, where the number of issued stores is not fixed: they wait for zero instead;
 //   - 80 KB of LDS and at most 256 registers per lane, so TWO workgroups share a CU and cover each other's panel
 //     changes, barriers and epilogues;
+//   - K = 512 (weight gradients at a per-shard batch of 512: compute-bound, 4 K flops per result element) runs the same
+//     way with ONE workgroup per CU: the panel takes 256 registers per lane and the two B stages 128 KB.  What it buys
+//     there is LDS traffic: only B goes through LDS (two fragment reads per four products instead of six per eight),
+//     where the tile engines that read both operands through LDS transpose reads are bound by LDS;
 //   - the grid is persistent: each workgroup takes a contiguous run of units (shard-major, panel, column tile).
 //
 // LDS layouts (XOR-swizzled by the choice of which global chunk a lane fetches, as in gemm_core2.h):
@@ -87,10 +91,10 @@ __device__ __forceinline__ uint64_t uniform64(const char *p)
     return ((uint64_t)hi << 32) | (uint64_t)lo;
 }
 
-// KT = K / 16 (8 or 16).  NTS: non-temporal stores.  256 threads; smem: smem_bytes5<KT>() bytes, 16-byte aligned.
+// KT = K / 16 (8, 16 or 32).  NTS: non-temporal stores.  256 threads; smem: smem_bytes5<KT>() bytes, 16-byte aligned.
 template <int KT, bool NTS> __device__ __forceinline__ void run_panels(const Params5 &p, char *smem)
 {
-    static_assert(KT == 8 || KT == 16, "K = 128 or 256");
+    static_assert(KT == 8 || KT == 16 || KT == 32, "K = 128, 256 or 512");
     constexpr int STB = stage_bytes5<KT>();
     constexpr int NLB = KT / 2; // B loads per thread and unit: k-rows tid / 8 + 32 i
     constexpr int ACH = KT * 8; // k-rows per A staging step (half of K): fills both stages
@@ -195,17 +199,22 @@ template <int KT, bool NTS> __device__ __forceinline__ void run_panels(const Par
                 for (int j = 0; j < 2; ++j)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-            // the B fragments are requested two k-steps before the products that use them are issued: under load the LDS
-            // latency of the transpose reads is longer than the four products of one step
-            bf16x8 bq[3][2];
-            bq[0][0] = read_frag_b5(Bs, 0, 0, lane); bq[0][1] = read_frag_b5(Bs, 32, 0, lane);
-            bq[1][0] = read_frag_b5(Bs, 0, 1, lane); bq[1][1] = read_frag_b5(Bs, 32, 1, lane);
+            // the B fragments are requested LOOK k-steps before the products that use them are issued: under load the LDS
+            // latency of the transpose reads is longer than the four products of one step (with one workgroup per CU,
+            // K = 512, no other wave of the SIMD fills the gap: four steps ahead there, two otherwise)
+            constexpr int LOOK = KT > 16 ? 4 : 2;
+            bf16x8 bq[LOOK + 1][2];
+#pragma unroll
+            for (int a = 0; a < LOOK; ++a) {
+                bq[a][0] = read_frag_b5(Bs, 0, a, lane);
+                bq[a][1] = read_frag_b5(Bs, 32, a, lane);
+            }
 #pragma unroll
             for (int ks = 0; ks < KT; ++ks) {
-                const bf16x8 b0 = bq[ks % 3][0], b1 = bq[ks % 3][1];
-                if (ks + 2 < KT) {
-                    bq[(ks + 2) % 3][0] = read_frag_b5(Bs, 0, ks + 2, lane);
-                    bq[(ks + 2) % 3][1] = read_frag_b5(Bs, 32, ks + 2, lane);
+                const bf16x8 b0 = bq[ks % (LOOK + 1)][0], b1 = bq[ks % (LOOK + 1)][1];
+                if (ks + LOOK < KT) {
+                    bq[(ks + LOOK) % (LOOK + 1)][0] = read_frag_b5(Bs, 0, ks + LOOK, lane);
+                    bq[(ks + LOOK) % (LOOK + 1)][1] = read_frag_b5(Bs, 32, ks + LOOK, lane);
                 }
                 __builtin_amdgcn_sched_barrier(0); // (left alone, the scheduler starts the next step's products early and waits for these reads)
                 // operands exchanged: the accumulators hold blocks of C^T (see the strip above)

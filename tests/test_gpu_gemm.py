@@ -115,7 +115,7 @@ def test_bf16_line_wide_k_tiles_engine(out_dt):
     check(6, 256, 3136, 4096, 0, 1, "bf16", out_dt, False, 51)
 
 
-@pytest.mark.parametrize("K", [256, 128])
+@pytest.mark.parametrize("K", [256, 128, 512])
 def test_bf16_panel_in_registers_engine(K):
     # weight-gradient shaped products (both operands stored K-major, K = 128 / 256, large bf16 result): the engine that
     # keeps the left operand's panel in registers; 8 shards x 5 panels (the last with 8 of 256 rows) x 52 column tiles

@@ -140,6 +140,18 @@ def test_panel_in_registers_engine_values(lockstep_gemm, tmp_path, relu):
     check(lockstep_gemm, str(tmp_path), 1, 512, 320, 256, 1, 0, "bf16", "bf16", relu, 83, env={"EMU_CUS": "3", "TT_GEMM_ENGINE": "5"})
 
 
+def test_panel_in_registers_engine_values_at_k_512(lockstep_gemm, tmp_path):
+    # K = 512: the panel takes twice the registers and the two stages 128 KB, one workgroup per CU (stand-in device of two
+    # CUs: two workgroups); two panels (the second with 40 rows) by five column tiles, so runs change panel mid-way
+    env = {"EMU_CUS": "2", "TT_GEMM_ENGINE": "5"}
+    out = check(lockstep_gemm, str(tmp_path), 1, 296, 320, 512, 1, 0, "bf16", "bf16", True, 85, env=env)
+    assert int(out.split()[3]) == 2 * 256
+    shape = (1, 256, 192, 512, 1, 0, "bf16", "bf16", False, 86)
+    check(lockstep_gemm, str(tmp_path), *shape, env=dict(env, EMU_ORDER="reverse"))
+    with pytest.raises(AssertionError):
+        check(lockstep_gemm, str(tmp_path), *shape, env=dict(env, EMU_VMCNT_SLACK="2"))
+
+
 def test_panel_in_registers_engine_counts_its_stores(lockstep_gemm, tmp_path):
     # its waits leave the previous unit's eight stores in flight; letting two more operations stay in flight than it
     # asks for must give stale operand tiles, and the order in which waves run must not matter
