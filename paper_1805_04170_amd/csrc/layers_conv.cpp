@@ -270,70 +270,75 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
         int k1, k2, k3;
         form_counts(f, k, &k1, &k2, &k3);
         Sharded Xa, Ga;
-        if ((st = prepare_operand(X, transpose_tiling(aXt, k), k, esz, nullptr, a.dtype, ws, a.stream, &Xa)) != TT_OK) return st;
         const int64_t rows_w = d.K * rs; // the filter storage matrix is (K*R*S) x C
-        // Output channels cut so far that a shard keeps at most 128 of them: a shard's product is then a sliver (64 rows
-        // of dY^T against the whole gathered X, which every shard of the group reads again).  The shards that differ only
-        // at those cuts share X (its aligned tiling replicates it there), so they run as ONE product over all their output
-        // channels: dY is brought to the aligned tiling with the F2 cuts replicated instead of split (one more copy of
-        // dY, made by the conversion that gates it anyway), the product is the evenly cut one below with those cuts
-        // taken out of the shard numbering, and the reduction kernel, which scatters whole blocks into the stored tiling,
-        // sees those cuts like cuts whose partial sums are already added up.
-        const int64_t lim = int64_t(1) << 30; // the evenly cut product's own limits (32-bit offsets, 16-byte chunks, tap masks)
-        const bool fits = (d.C >> k1) % 8 == 0 && d.K % 8 == 0 && rs <= 32 && (d.N >> k3) * hw * (d.C >> k1) < lim &&
-                          (d.N >> k3) * pq * d.K < lim && d.K * rs * (d.C >> k1) < lim;
-        if (bf16 && fits && k2 > 0 && (d.K >> k2) <= 128 && d.K > 128 && ((d.N >> k3) * pq) % 64 == 0 && tuning_int("TT_WGRAD_MERGE", 1) != 0) {
+        // Channels cut so far that a shard keeps at most 128 of them leave every shard a sliver of the product: 64 rows of
+        // dY^T against the whole gathered X where the output channels are cut (F2), or the whole dY^T against 64 gathered
+        // channels per tap where the input channels are cut (F1: 576 columns make two and a quarter 256-wide tiles), and
+        // the other operand, which the aligned tiling replicates at those cuts, is read again by every shard of the group.
+        // Such shards run as ONE product over all their channels: the operand that was cut is brought to the aligned
+        // tiling with those cuts replicated instead of split (dY: one more copy, made by the conversion that gates it
+        // anyway; X stored replicated: nothing moves), the product is the evenly cut one below with those cuts taken out
+        // of the shard numbering, and the reduction kernel, which scatters whole blocks into the stored tiling, sees those
+        // cuts like cuts whose partial sums are already added up.
+        if (bf16 && tuning_int("TT_WGRAD_MERGE", 1) != 0) {
+            const bool m1 = k1 > 0 && (d.C >> k1) <= 128 && d.C > 128, m2 = k2 > 0 && (d.K >> k2) <= 128 && d.K > 128;
+            const int64_t Cm = m1 ? d.C : d.C >> k1, Km = m2 ? d.K : d.K >> k2, Ns = d.N >> k3; // per product
+            const int64_t lim = int64_t(1) << 30; // the evenly cut product's own limits (32-bit offsets, 16-byte chunks, tap masks)
+            const bool fits = Cm % 8 == 0 && Km % 8 == 0 && Km > 128 && rs <= 32 && Ns * hw * Cm < lim && Ns * pq * Km < lim &&
+                              Km * rs * Cm < lim && (Ns * pq) % 64 == 0;
             uint32_t mask_m = 0;
-            uint8_t zr[TT_MAX_K], zp[TT_MAX_K]; // letters for the reduction (k cuts) and for the product (k - k2 cuts)
-            tt_tiling aGm = aG;
+            uint8_t zr[TT_MAX_K], zp[TT_MAX_K]; // letters for the reduction (k cuts) and for the product (the cuts kept)
+            tt_tiling aGm = aG, aXm = transpose_tiling(aXt, k);
             int kp = 0;
             for (int j = 0; j < k; ++j) {
-                if (f[j] == TT_F2) {
+                if ((f[j] == TT_F2 && m2) || (f[j] == TT_F1 && m1)) {
                     mask_m |= 1u << (k - 1 - j);
-                    aGm.cut[j] = TT_REP;
+                    (f[j] == TT_F2 ? aGm : aXm).cut[j] = TT_REP;
                     zr[j] = kRed;
                 } else {
-                    zr[j] = zp[kp++] = f[j] == TT_F1 ? TT_C : kRed;
+                    zr[j] = zp[kp++] = f[j] == TT_F1 ? TT_C : (f[j] == TT_F2 ? TT_R : kRed);
                 }
             }
             const uint32_t mask_keep = ((1u << k) - 1u) & ~mask_m;
             Grid gp, gr;
-            if (!make_grid(zp, kp, rows_w, d.C, &gp) || !make_grid(zr, k, rows_w, d.C, &gr)) return TT_EINFEASIBLE;
-            const int nred = 1 << gp.kX, nblk = (1 << kp) >> gp.kX;
-            const int64_t Ns = d.N >> k3, Cs = d.C >> k1;
-            const size_t blk_bytes = (size_t)gp.srows * (size_t)gp.scols * 4;
-            const WgradChoice choice = pick_wgrad_parts(k, nblk, nred, Ns * pq / 64, d.K, rs * Cs, blk_bytes);
-            if (choice.parts > 0) {
-                if ((st = prepare_operand(G, aGm, k, esz, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga)) != TT_OK) return st;
-                const int parts = choice.parts;
-                uint8_t blk_ids[kMaxShards], red_ids[kMaxShards];
-                const uint32_t mask_blk = ((1u << kp) - 1u) & ~gp.maskX;
-                for (int b = 0; b < nblk; ++b) blk_ids[b] = (uint8_t)deposit((uint32_t)b, mask_blk, kp);
-                for (int q = 0; q < nred; ++q) red_ids[q] = (uint8_t)deposit((uint32_t)q, gp.maskX, kp);
-                void *sums[kMaxShards];
-                const float *table[kMaxShards];
-                for (int i = 0; i < kMaxShards; ++i) table[i] = nullptr;
-                for (int b = 0; b < nblk; ++b)
-                    for (int c = 0; c < parts; ++c) {
-                        sums[b * parts + c] = ws.take(blk_bytes);
-                        // block b among the k cuts: its id in the product's numbering, spread over the cuts that were kept
-                        table[deposit((uint32_t)blk_ids[b], mask_keep, k) * parts + c] = static_cast<const float *>(sums[b * parts + c]);
+            if ((m1 || m2) && fits && make_grid(zp, kp, rows_w, d.C, &gp) && make_grid(zr, k, rows_w, d.C, &gr)) {
+                const int nred = 1 << gp.kX, nblk = (1 << kp) >> gp.kX;
+                const size_t blk_bytes = (size_t)gp.srows * (size_t)gp.scols * 4;
+                const WgradChoice choice = pick_wgrad_parts(k, nblk, nred, Ns * pq / 64, Km, rs * Cm, blk_bytes);
+                if (choice.parts > 0) {
+                    if ((st = prepare_operand(X, aXm, k, esz, nullptr, a.dtype, ws, a.stream, &Xa)) != TT_OK) return st;
+                    if ((st = prepare_operand(G, aGm, k, esz, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga)) != TT_OK) return st;
+                    const int parts = choice.parts;
+                    uint8_t blk_ids[kMaxShards], red_ids[kMaxShards];
+                    const uint32_t mask_blk = ((1u << kp) - 1u) & ~gp.maskX;
+                    for (int b = 0; b < nblk; ++b) blk_ids[b] = (uint8_t)deposit((uint32_t)b, mask_blk, kp);
+                    for (int q = 0; q < nred; ++q) red_ids[q] = (uint8_t)deposit((uint32_t)q, gp.maskX, kp);
+                    void *sums[kMaxShards];
+                    const float *table[kMaxShards];
+                    for (int i = 0; i < kMaxShards; ++i) table[i] = nullptr;
+                    for (int b = 0; b < nblk; ++b)
+                        for (int c = 0; c < parts; ++c) {
+                            sums[b * parts + c] = ws.take(blk_bytes);
+                            // block b among the k cuts: its id in the product's numbering, spread over the cuts that were kept
+                            table[deposit((uint32_t)blk_ids[b], mask_keep, k) * parts + c] = static_cast<const float *>(sums[b * parts + c]);
+                        }
+                    if (ws.overflow) return TT_EWORKSPACE;
+                    if (ws.dry) return TT_OK;
+                    const void *Gp[kMaxShards], *Xp[kMaxShards];
+                    for (int s = 0; s < (1 << kp); ++s) {
+                        const uint32_t sid = deposit((uint32_t)s, mask_keep, k);
+                        Gp[s] = Ga.ptr[sid];
+                        Xp[s] = Xa.ptr[sid];
                     }
-                if (ws.overflow) return TT_EWORKSPACE;
-                if (ws.dry) return TT_OK;
-                const void *Gp[kMaxShards], *Xp[kMaxShards];
-                for (int s = 0; s < (1 << kp); ++s) {
-                    const uint32_t sid = deposit((uint32_t)s, mask_keep, k);
-                    Gp[s] = Ga.ptr[sid];
-                    Xp[s] = Xa.ptr[sid];
+                    st = launch_conv_wgrad_split(kp, nblk, nred, blk_ids, red_ids, parts, Gp, Xp, sums, Ns, Cm, Km, d.H, d.W, d.R, d.S,
+                                                 d.pad, choice.engine, a.stream);
+                    if (st != TT_OK) return st;
+                    return launch_reduce(a.dW, transpose_tiling(a.tW, k).cut, a.dtype, table, zr, k, rows_w, d.C, TT_ACT_NONE, parts,
+                                         a.stream, true);
                 }
-                st = launch_conv_wgrad_split(kp, nblk, nred, blk_ids, red_ids, parts, Gp, Xp, sums, Ns, Cs, d.K, d.H, d.W, d.R, d.S,
-                                             d.pad, choice.engine, a.stream);
-                if (st != TT_OK) return st;
-                return launch_reduce(a.dW, transpose_tiling(a.tW, k).cut, a.dtype, table, zr, k, rows_w, d.C, TT_ACT_NONE, parts,
-                                     a.stream, true);
             }
         }
+        if ((st = prepare_operand(X, transpose_tiling(aXt, k), k, esz, nullptr, a.dtype, ws, a.stream, &Xa)) != TT_OK) return st;
         if ((st = prepare_operand(G, aG, k, esz, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga)) != TT_OK) return st;
         // the output grid on the filter storage matrix (K*R*S) x C: F1 cuts its columns, F2 its rows
         uint8_t zl[TT_MAX_K];

@@ -146,6 +146,10 @@ def test_weight_gradient_of_shards_that_share_the_images_runs_as_one_product():
     run_conv(8, 32, 256, 8, 8, 3, 3, 1, 2, False, "Rr", "rC", "RC", "RC", "Rr", "12", "13", "32", 186)   # a batch cut beside it: two shards add up
     run_conv(4, 64, 512, 8, 8, 3, 3, 1, 2, True, "Cr", "RC", "rC", "rC", "Cr", "32", "23", "12", 187)    # an input-channel cut beside it: two blocks
     run_conv(4, 16, 384, 4, 16, 1, 1, 0, 3, False, "rrR", "CCr", "CCR", "CCR", "rrR", "221", "331", "223", 188)  # 96 channels per shard, three cuts
+    # ... and the mirror case, at most 128 input channels per shard with dY replicated over the cuts that split them
+    run_conv(4, 256, 256, 8, 8, 3, 3, 1, 2, True, "rr", "RR", "CC", "rr", "CC", "22", "22", "11", 189)   # the planner's kind of tiling: one group
+    run_conv(4, 256, 256, 8, 8, 3, 3, 1, 2, False, "Cr", "RC", "rC", "rC", "Cr", "32", "23", "12", 190)  # both kinds of cut: one product is left
+    run_conv(8, 256, 192, 8, 8, 3, 3, 1, 2, True, "CR", "Rr", "rR", "rR", "CR", "31", "21", "13", 191)   # a batch cut beside it: two shards add up
 
 
 def test_fp32_convolutions():
