@@ -211,6 +211,54 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
         int k1, k2, k3;
         form_counts(f, k, &k1, &k2, &k3);
         Sharded Ga, Wa;
+        // Output channels cut (F3) so far that a shard keeps at most 128 of them: every shard's product then has a short
+        // reduction (nine K tiles at 64 channels and 3 x 3 taps) and writes a whole fp32 partial sum of dX, which the
+        // reduction kernel reads again.  On one GPU nothing forces that: the shards of a group (equal at every other cut)
+        // read disjoint channel blocks of dY and of the filters, so with both brought to the aligned tiling with the F3
+        // cuts replicated instead of split (one more copy of dY, which the weight gradient below then uses as it is; the
+        // filters are small) the group is ONE product over all output channels that writes dX once, in its final type;
+        // what is left of the output conversion is the copy into the stored tiling (its replicas, if it has any).
+        const F2Group fg0 = f2_group(f, k, d.C >> k2, a.dtype);
+        if (bf16 && k3 > 0 && (d.K >> k3) <= 128 && d.K > 128 && fg0.members == 1 && tuning_int("TT_DGRAD_MERGE", 1) != 0) {
+            uint32_t mask_m = 0;
+            uint8_t zl[TT_MAX_K];
+            tt_tiling aGm = aG, aWm = aWt;
+            for (int j = 0; j < k; ++j) {
+                if (f[j] == TT_F3) {
+                    mask_m |= 1u << (k - 1 - j);
+                    aGm.cut[j] = aWm.cut[j] = TT_REP;
+                }
+                zl[j] = f[j] == TT_F1 ? TT_R : (f[j] == TT_F2 ? TT_C : TT_REP);
+            }
+            const uint32_t mask_keep = ((1u << k) - 1u) & ~mask_m;
+            const int kp = k - k3, np = 1 << kp;
+            if ((st = prepare_operand(G, aGm, k, esz, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga)) != TT_OK) return st;
+            G = Ga; // gated (if it had to be) and whole in its channels: the weight gradient starts from this copy
+            gated = true;
+            if ((st = prepare_operand(W, aWm, k, esz, nullptr, a.dtype, ws, a.stream, &Wa)) != TT_OK) return st;
+            Grid gz;
+            if (!make_grid(zl, k, d.N * hw, d.C, &gz)) return TT_EINFEASIBLE;
+            const size_t out_bytes = (size_t)gz.srows * (size_t)gz.scols * 2;
+            const size_t fbytes = (size_t)d.K * (size_t)rs * (size_t)(d.C >> k2) * 2;
+            const void *Gp[kMaxShards], *Wp[kMaxShards], *src[kMaxShards];
+            void *outp[kMaxShards], *flipp[kMaxShards];
+            for (int sp = 0; sp < np; ++sp) {
+                const uint32_t sid = deposit((uint32_t)sp, mask_keep, k);
+                Gp[sp] = Ga.ptr[sid];
+                Wp[sp] = Wa.ptr[sid];
+                outp[sp] = ws.take(out_bytes);
+                flipp[sp] = ws.take(fbytes);
+            }
+            for (int sh = 0; sh < n; ++sh) src[sh] = outp[extract((uint32_t)sh, mask_keep, k)]; // the group's result, whichever member is asked
+            if (ws.overflow) return TT_EWORKSPACE;
+            if (!ws.dry) {
+                st = launch_conv(TT_OP_DGRAD, np, Gp, Wp, outp, d.N >> k1, d.C >> k2, d.K, d.H, d.W, d.R, d.S, d.pad, a.dtype,
+                                 TT_ACT_NONE, a.stream, flipp, a.dtype);
+                if (st != TT_OK) return st;
+                st = launch_convert(a.dX, a.tdX.cut, src, zl, nullptr, nullptr, k, d.N * hw, d.C, esz, 0, false, a.stream);
+                if (st != TT_OK) return st;
+            }
+        } else {
         if ((st = prepare_operand(G, aG, k, esz, gated ? nullptr : &Y, a.dtype, ws, a.stream, &Ga)) != TT_OK) return st;
         if (!gated) { G = Ga; gated = true; }
         // aligned tiling of W^T, expressed on W, then on the filter storage matrix: two swaps cancel
@@ -258,6 +306,7 @@ tt_status backward(const ConvArgs &a, const Dims &d, Workspace &ws)
             if (st != TT_OK) return st;
             if ((st = finish_output(op, a.tdX, a.dX, d.N * hw, d.C, k, a.dtype, TT_ACT_NONE, a.stream)) != TT_OK) return st;
         }
+        } // (the per-shard / fused path)
     }
     {
         // dW (C x K) = X^T (C x batch) times G (batch x K): F1 input channels, F2 output channels, F3 batch
