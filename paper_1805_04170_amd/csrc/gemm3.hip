@@ -54,7 +54,7 @@ template <bool A_KC, bool B_KC, bool OUT_BF16, bool STAGED> tt_status launch_cfg
 template <bool A_KC, bool B_KC> tt_status launch_layout4(core3::Params3 &p, int out_dtype, bool vec, hipStream_t s)
 {
     const bool bf = out_dtype == TT_BF16;
-    if (bf && vec) return launch_cfg4<A_KC, B_KC, true, true>(p, s);
+    if (vec) return bf ? launch_cfg4<A_KC, B_KC, true, true>(p, s) : launch_cfg4<A_KC, B_KC, false, true>(p, s);
     return bf ? launch_cfg4<A_KC, B_KC, true, false>(p, s) : launch_cfg4<A_KC, B_KC, false, false>(p, s);
 }
 
@@ -126,8 +126,7 @@ tt_status launch_cfg(core3::Params3 &p, hipStream_t s)
 
 template <bool A_KC, bool B_KC> tt_status launch_layout(core3::Params3 &p, int out_dtype, bool vec, hipStream_t s)
 {
-    // bf16 results with 16-byte rows: staged epilogue (ring + 18 KB).  Everything else (fp32 partial sums, odd pitches)
-    // stores element-wise from registers.  Ring: two stages of 64 (TT_V3_RING=324: four stages of 32; tuning aid).
+    // results with 16-byte rows: staged epilogue (ring + 18 KB).  Odd pitches store element-wise from registers.  Ring: two stages of 64 (TT_V3_RING=324: four stages of 32; tuning aid).
     const int ring = tuning_int("TT_V3_RING", 642);
     const bool bf = out_dtype == TT_BF16;
     if (ring == 324) {
@@ -141,7 +140,8 @@ template <bool A_KC, bool B_KC> tt_status launch_layout(core3::Params3 &p, int o
     if (bf && vec) return ilv ? launch_cfg<64, 2, A_KC, B_KC, true, true, true>(p, s) : launch_cfg<64, 2, A_KC, B_KC, true, true>(p, s);
     // ... and, among the products that write fp32 partial sums, for the NN layout (B read with LDS transpose reads)
     if constexpr (A_KC && !B_KC)
-        if (!bf && ilv) return launch_cfg<64, 2, A_KC, B_KC, false, false, true>(p, s);
+        if (!bf && ilv) return vec ? launch_cfg<64, 2, A_KC, B_KC, false, true, true>(p, s) : launch_cfg<64, 2, A_KC, B_KC, false, false, true>(p, s);
+    if (!bf && vec) return launch_cfg<64, 2, A_KC, B_KC, false, true>(p, s); // fp32 partial sums with 16-byte rows: staged too
     return bf ? launch_cfg<64, 2, A_KC, B_KC, true, false>(p, s) : launch_cfg<64, 2, A_KC, B_KC, false, false>(p, s);
 }
 
@@ -206,10 +206,10 @@ tt_status launch_gemm_v6(int count, const void *const *A, const void *const *B, 
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const bool bf = out_dtype == TT_BF16;
     if (b_kc) {
-        if (bf && vec) return launch_cfg6<true, true, true>(p, s);
+        if (vec) return bf ? launch_cfg6<true, true, true>(p, s) : launch_cfg6<true, false, true>(p, s);
         return bf ? launch_cfg6<true, true, false>(p, s) : launch_cfg6<true, false, false>(p, s);
     }
-    if (bf && vec) return launch_cfg6<false, true, true>(p, s);
+    if (vec) return bf ? launch_cfg6<false, true, true>(p, s) : launch_cfg6<false, false, true>(p, s);
     return bf ? launch_cfg6<false, true, false>(p, s) : launch_cfg6<false, false, false>(p, s);
 }
 

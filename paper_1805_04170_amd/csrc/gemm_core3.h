@@ -17,9 +17,10 @@
 //   - the loads are inline assembly with a scalar base and a 32-bit lane offset, computed once per output tile
 //     (the builtin form makes the compiler put s_waitcnt vmcnt(0) in front of every fragment read);
 //   - K must be a multiple of 64 (no tail handling in the K direction; the launcher falls back otherwise);
-//   - fp32 results (partial sums) are stored straight from the accumulators: a 32-lane half wave writes 128 contiguous
-//     bytes of one C row.  bf16 results go through a small wave-private LDS area that lies outside the ring, 16 rows at
-//     a time, so the epilogue needs no workgroup barrier and never touches a stage that a prefetch may be filling.
+//   - results go through a small wave-private LDS area that lies outside the ring (bf16: 16 rows at a time, fp32
+//     partial sums: 8), so the epilogue needs no workgroup barrier and never touches a stage that a prefetch may be
+//     filling, and leave as 16-byte vectors of whole row segments; rows that cannot take 16-byte stores are stored
+//     element by element straight from the accumulators.
 #pragma once
 #include <cstdint>
 #include "tt_device.h"
@@ -42,6 +43,46 @@ template <int BK> constexpr int loads_per_op() { return 256 * BK * 2 / 16 / kThr
 
 constexpr int kEpiRows = 16, kEpiLd = 64 + 8;         // bf16 staging strip of one wave: 16 rows x 64 columns, padded
 constexpr int kEpiBytes = 8 * kEpiRows * kEpiLd * 2;  // 18 KB for the eight waves
+// fp32 staging strip of one wave: 8 rows x 64 columns, padded (fits in the bf16 strip's place)
+constexpr int kEpiRowsF = 8, kEpiLdF = 64 + 4;
+static_assert(kEpiRowsF * kEpiLdF * 4 <= kEpiRows * kEpiLd * 2, "the fp32 strip fits where the bf16 strip lies");
+
+// Write-out of a wave's 128 x 64 fp32 accumulator tile (4 x 2 blocks of 32 x 32; a lane holds column lane % 32 and rows
+// 8 g + 4 (lane / 32) + e % 4, g = e / 4, of each block) through a wave-private strip of kEpiRowsF x kEpiLdF floats: eight
+// rows at a time are turned round in LDS and leave as 16-byte vectors, 16 lanes per 256-byte row segment, four rows per
+// store instruction (stored straight from the accumulators a row segment takes 32 four-byte stores of a half wave: four
+// times the store instructions, and measured 15-30 % slower on the products that write large fp32 partial sums).
+// N must be a multiple of 4 and C 16-byte aligned.  (row0, col0): the wave tile's origin in C.
+__device__ __forceinline__ void store_wave_tile_f32(f32x16 (&acc)[4][2], float *strip, float *C, int ldc, int row0, int col0, int M,
+                                                    int N, bool relu, int lane)
+{
+    const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int ee = 0; ee < 4; ++ee) {
+                    float v = acc[i][j][4 * g + ee];
+                    if (relu) v = fmaxf(v, 0.0f);
+                    strip[(row_l + ee) * kEpiLdF + j * 32 + col_l] = v;
+                }
+            // wave-private data and LDS operations of a wave execute in order: only the compiler needs a fence
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                const int idx = lane + 64 * v, lrow = idx >> 4, vc = (idx & 15) * 4;
+                const int row = row0 + i * 32 + 8 * g + lrow, col = col0 + vc;
+                const core::f32x4 o = *reinterpret_cast<const core::f32x4 *>(strip + lrow * kEpiLdF + vc);
+                if (row < M && col < N) // N is a multiple of 4 on this path: a vector is all in or all out
+                    __builtin_nontemporal_store(o, reinterpret_cast<core::f32x4 *>(C + (size_t)row * ldc + col));
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+}
+
 template <int BK, int NS, bool STAGED> constexpr size_t smem_bytes3()
 {
     return (size_t)NS * 2 * op_stage_bytes<BK>() + (STAGED ? kEpiBytes : 0);
@@ -288,7 +329,11 @@ __device__ __forceinline__ void run_tiles(const Params3 &p, char *smem)
         // so results could leave as 16-byte vectors without LDS; but each store instruction then touches 32 rows with
         // 32 bytes each, and those partial-line writes were slower than the staged row-contiguous ones below.)
         const int col_l = lane & 31, row_l = (lane >> 5) * 4;
-        if constexpr (!STAGED) {
+        if constexpr (STAGED && !OUT_BF16) {
+            float *strip = reinterpret_cast<float *>(smem + NS * STB) + wave * (kEpiRowsF * kEpiLdF);
+            store_wave_tile_f32(acc, strip, reinterpret_cast<float *>(p.C[cur.vshard]), ldc, cur.m0 + wm0, cur.n0 + wn0, M, N, relu,
+                                lane);
+        } else if constexpr (!STAGED) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll

@@ -93,8 +93,9 @@ template <int ROWS, bool KC> __device__ __forceinline__ bf16x8 read_frag4(const 
 }
 
 // Write-out of a workgroup's 256 x 128 accumulator tile (four waves as 2 x 2, 128 x 64 per wave: the wave tile of this
-// engine and of gemm_core6.h).  The ring must be drained and idle: STAGED turns bf16 results round in a wave-private
-// strip at the start of smem (at least 4 * 16 * 72 * 2 bytes), 16 rows at a time; everything else is stored element-wise.
+// engine and of gemm_core6.h).  The ring must be drained and idle: STAGED turns the results round in a wave-private
+// strip at the start of smem (at least 4 * 16 * 72 * 2 bytes; bf16 16 rows at a time, fp32 8) so that they leave as
+// 16-byte vectors of whole row segments; without it they are stored element by element.
 template <bool OUT_BF16, bool STAGED>
 __device__ __forceinline__ void write_tile4(f32x16 (&acc)[4][2], void *Cv, int ldc, int M, int N, int m0, int n0, bool relu,
                                             char *smem)
@@ -104,7 +105,11 @@ __device__ __forceinline__ void write_tile4(f32x16 (&acc)[4][2], void *Cv, int l
     const int wm0 = (wave / WN) * (TM * 32), wn0 = (wave % WN) * (TN * 32);
     // ---- epilogue.  A lane holds column (lane & 31) and rows 8*(e/4) + 4*(lane/32) + e%4 of each 32 x 32 block.
     const int col_l = lane & 31, row_l = (lane >> 5) * 4;
-    if constexpr (!STAGED) {
+    if constexpr (STAGED && !OUT_BF16) {
+        static_assert(4 * core3::kEpiRowsF * core3::kEpiLdF * 4 <= kSmem4, "strips fit in the ring");
+        float *strip = reinterpret_cast<float *>(smem) + wave * (core3::kEpiRowsF * core3::kEpiLdF);
+        core3::store_wave_tile_f32(acc, strip, reinterpret_cast<float *>(Cv), ldc, m0 + wm0, n0 + wn0, M, N, relu, lane);
+    } else if constexpr (!STAGED) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
