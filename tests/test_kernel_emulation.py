@@ -246,8 +246,8 @@ SHARD_CASES = [
     ((8, 3136, 4096, 256, 1, 0, 1, 1, 0, 1), 512 * 256),    # VGG-16 first weight gradient: the panel-in-registers engine, two workgroups of four waves per CU
     ((8, 1152, 4096, 128, 1, 0, 1, 1, 0, 1), 512 * 256),    # the same engine at a per-shard batch of 128
     ((8, 1024, 2048, 256, 1, 0, 1, 1, 0, 1), 512 * 256),    # ... and at the second VGG-16 weight gradient: two units per workgroup
-    ((16, 2048, 2048, 512, 1, 0, 1, 1, 0, 1), 256 * 256),   # wide-MLP weight gradient, per-shard batch 512: the same engine, one workgroup per CU
-    ((8, 3136, 4096, 192, 1, 0, 1, 1, 0, 1), 256 * 512),    # a batch it does not take: the persistent engine, one workgroup per CU
+    ((16, 1024, 2048, 512, 1, 0, 1, 1, 0, 1), 256 * 256),   # weight gradient at a per-shard batch of 512 (half a wide-MLP shard): the same engine, one workgroup per CU
+    ((8, 1568, 4096, 192, 1, 0, 1, 1, 0, 1), 256 * 512),    # a batch it does not take: the persistent engine, one workgroup per CU
     ((16, 256, 4096, 512, 0, 1, 1, 0, 0, 1), 256 * 512),    # skinny data gradient: 256 x 256 tiles loaded straight into LDS
     ((16, 256, 2048, 512, 0, 0, 1, 0, 0, 1), 128 * 512),    # skinny NN product: the persistent engine, 128 tiles
     ((4, 256, 128, 1024, 0, 0, 1, 1, 0, 1), 8 * 256),       # one narrow column of tiles: register-staged 256 x 128
