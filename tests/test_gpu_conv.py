@@ -146,6 +146,7 @@ def test_weight_gradient_of_shards_that_share_the_images_runs_as_one_product():
     run_conv(8, 32, 256, 8, 8, 3, 3, 1, 2, False, "Rr", "rC", "RC", "RC", "Rr", "12", "13", "32", 186)   # a batch cut beside it: two shards add up
     run_conv(4, 64, 512, 8, 8, 3, 3, 1, 2, True, "Cr", "RC", "rC", "rC", "Cr", "32", "23", "12", 187)    # an input-channel cut beside it: two blocks
     run_conv(4, 16, 384, 4, 16, 1, 1, 0, 3, False, "rrR", "CCr", "CCR", "CCR", "rrR", "221", "331", "223", 188)  # 96 channels per shard, three cuts
+    run_conv(4, 64, 256, 6, 8, 1, 3, 1, 2, False, "rr", "CC", "CC", "CC", "rr", "22", "33", "22", 192)    # 1 x 3 taps: the merged data gradient on the kernel that reads the filters as they are
     # ... and the mirror case, at most 128 input channels per shard with dY replicated over the cuts that split them
     run_conv(4, 256, 256, 8, 8, 3, 3, 1, 2, True, "rr", "RR", "CC", "rr", "CC", "22", "22", "11", 189)   # the planner's kind of tiling: one group
     run_conv(4, 256, 256, 8, 8, 3, 3, 1, 2, False, "Cr", "RC", "rC", "rC", "Cr", "32", "23", "12", 190)  # both kinds of cut: one product is left
