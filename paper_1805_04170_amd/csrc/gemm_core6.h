@@ -14,7 +14,10 @@
 //   - the streamed operand B (16 KB per K tile) has three stages, two tiles in flight; the L2-resident operand A (32 KB
 //     per K tile) has two stages, one tile in flight: 112 KB of LDS, all of it below 128 KB;
 //   - LDS layout of both operands: [row][8 chunks of 8 k], chunk position p of row r holds k-chunk p ^ ((r >> 1) & 7),
-//     fragments are plain 16-byte reads (the K-contiguous layout of gemm_core2.h);
+//     fragments are plain 16-byte reads (the K-contiguous layout of gemm_core2.h).  (B may also be given with its rows
+//     contiguous, K x N: the [k][16 chunks of 8 columns] layout and the LDS transpose reads of gemm_core2.h; built to
+//     measure the forward products with it, which came out no faster than on gemm_core4.h, so the launch code only
+//     takes that form when the engine is forced;)
 //   - waits count operations: the loads are issued in the order B(0) A(0) B(1) | A(1) B(2) | A(2) B(3) | ..., so at the
 //     top of step kt everything but the newest B tile (four loads per lane) has to be complete: s_waitcnt vmcnt(4)
 //     (a wave's loads retire in order on that counter).  Past the end of K the last tile is fetched again into stages
