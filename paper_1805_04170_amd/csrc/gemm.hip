@@ -136,30 +136,61 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(const GenericPar
     const void *B = p.B[shard];
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     float acc[4][4] = {};
-    for (int k0 = kbeg; k0 < kend; k0 += KB) {
-        for (int i = threadIdx.x; i < T * KB; i += kThreads) {
-            // A tile: pick the loop order that walks the contiguous stride
+    // A tile's elements come into registers first (four of each operand per thread, all loads in flight together, from
+    // clamped addresses with the out-of-range ones zeroed afterwards) and go to LDS when their step comes; the fetch
+    // runs PD tiles ahead of the arithmetic.  These products are small and the chip is nearly idle while they run: what
+    // a step costs is one trip to memory (about 2 us here), and PD of them are now under way at a time.
+    constexpr int PT = T * KB / kThreads, PD = 4;
+    float ra[PD][PT], rb[PD][PT];
+    auto fetch = [&](int k0, float (&xa)[PT], float (&xb)[PT]) {
+#pragma unroll
+        for (int u = 0; u < PT; ++u) {
+            const int i = threadIdx.x + u * kThreads;
+            // pick the loop order that walks the contiguous stride
             int kk, mm;
             if (p.sak == 1) { kk = i % KB; mm = i / KB; } else { mm = i % T; kk = i / T; }
-            int gm = m0 + mm, gk = k0 + kk;
-            As[kk][mm] = (gm < p.M && gk < kend) ? load_in<IN_BF16>(A, gm * p.sam + gk * p.sak) : 0.0f;
+            const int gm = m0 + mm, gk = k0 + kk;
+            const float va = load_in<IN_BF16>(A, (int64_t)(gm < p.M ? gm : p.M - 1) * p.sam + (int64_t)(gk < kend ? gk : kend - 1) * p.sak);
+            xa[u] = (gm < p.M && gk < kend) ? va : 0.0f;
             int kb, nn;
             if (p.sbk == 1) { kb = i % KB; nn = i / KB; } else { nn = i % T; kb = i / T; }
-            int gn = n0 + nn, gkb = k0 + kb;
-            Bs[kb][nn] = (gn < p.N && gkb < kend) ? load_in<IN_BF16>(B, gkb * p.sbk + gn * p.sbn) : 0.0f;
+            const int gn = n0 + nn, gkb = k0 + kb;
+            const float vb = load_in<IN_BF16>(B, (int64_t)(gkb < kend ? gkb : kend - 1) * p.sbk + (int64_t)(gn < p.N ? gn : p.N - 1) * p.sbn);
+            xb[u] = (gn < p.N && gkb < kend) ? vb : 0.0f;
         }
-        __syncthreads();
+    };
 #pragma unroll
-        for (int kk = 0; kk < KB; ++kk) {
-            float a[4], b[4];
+    for (int d = 0; d < PD; ++d)
+        if (kbeg + d * KB < kend) fetch(kbeg + d * KB, ra[d], rb[d]);
+    for (int k0 = kbeg; k0 < kend; k0 += PD * KB) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+        for (int d = 0; d < PD; ++d) { // (unrolled: the register ring is indexed by constants)
+            const int kd = k0 + d * KB;
+            if (kd >= kend) break;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int u = 0; u < PT; ++u) {
+                const int i = threadIdx.x + u * kThreads;
+                int kk, mm;
+                if (p.sak == 1) { kk = i % KB; mm = i / KB; } else { mm = i % T; kk = i / T; }
+                As[kk][mm] = ra[d][u];
+                int kb, nn;
+                if (p.sbk == 1) { kb = i % KB; nn = i / KB; } else { nn = i % T; kb = i / T; }
+                Bs[kb][nn] = rb[d][u];
+            }
+            __syncthreads();
+            if (kd + PD * KB < kend) fetch(kd + PD * KB, ra[d], rb[d]);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+            for (int kk = 0; kk < KB; ++kk) {
+                float a[4], b[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
