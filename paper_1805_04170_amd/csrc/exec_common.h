@@ -154,7 +154,9 @@ inline int pick_ksplit(int64_t M, int64_t N, int64_t K, int count, int dtype, bo
     static const int min_half = tuning_int("TT_KSPLIT_HALF", 192);
     if (min_half > 0 && ((M + 255) / 256) * ((N + 127) / 128) * count >= min_half) return 1;
     int s = 1;
-    static const int min_blocks = tuning_int("TT_KSPLIT_BLOCKS", 200);
+    // splitting stops once every second CU has a 256 x 256 tile's worth of work (at 200 the first AlexNet forward product,
+    // 8 x 256 x 1024 x 4608, was cut eight ways: twice the partial sums of four ways for no faster a product, 4 % of its step)
+    static const int min_blocks = tuning_int("TT_KSPLIT_BLOCKS", 128);
     while (blocks * s < min_blocks && s < 8 && K / (2 * s) >= (blocks * s < 64 ? 192 : 512) && count * 2 * s <= kMaxShards &&
            ksplit_fits(K, 2 * s))
         s *= 2;
